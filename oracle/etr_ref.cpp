@@ -1,0 +1,395 @@
+// CPU oracle for the forward pass of one Expert-Token Resonance MoE layer.
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, obviously-correct
+// statement of what the layer computes, written from the paper's definitions.
+// It shares no code with the GPU library and must never be called from the
+// product path; only the tests, the smoke check and the benchmark's
+// cpu-baseline leg use it.
+//
+// Everything is computed the slow way: double accumulators, full sorts,
+// triple-loop matrix products, no blocking, no fusion.  All pointers are HOST
+// pointers.  Floating-point inputs are fp32 or bf16 (dtype 0 / 1); bf16 values
+// are widened exactly.
+//
+// What each function follows:
+//   etr_ref_route       GrAP pooling (Sec. Cost-Efficient Sparse Expert-Token
+//                       Affinity, Eqs. 2-3: each gate vector is 1/(group size)
+//                       on its group, so x^T w_i is the group mean) and the
+//                       cosine affinity (Eq. 4); gate = row softmax (Eq. 1 text)
+//   etr_ref_select      token choice Top-l (Eq. 5); expert choice over the
+//                       candidates (Eq. 6, "Bottom-C" read as top-C by
+//                       affinity: the text around it says each expert keeps
+//                       the tokens with the highest affinity); pure TCR keep
+//                       rule "fewer than C earlier tokens went to the same
+//                       expert" (Proof of Theorem, part 1); pure ECR keep rule
+//                       "at most C-1 tokens score higher" (Proof, part 2)
+//   etr_ref_dispatch    the capacity-bounded per-expert slot table I_{ki} of
+//                       Eq. 6, materialised as rows
+//   etr_ref_ffn_rows    the expert network: a SwiGLU feed-forward block
+//   etr_ref_combine     the gate-weighted sum of Eq. 1
+//   etr_ref_moe_forward the chain of the above
+//
+// Readings of points the paper leaves open (all listed in the design notes):
+// ties go to the lowest index; slots inside an expert are in ascending token
+// order; the gate is the softmax over all experts of the affinity row with no
+// renormalisation over the selected set; a token kept by no expert gives a
+// zero output row.
+//
+// Every function here is pinned by CPU tests against worked examples derived
+// from the equations, closed forms, invariants and brute force (no "parity
+// unpinned" function).
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <numeric>
+#include <vector>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+namespace {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+enum { MODE_TCR = 0, MODE_ECR = 1, MODE_BIDIR = 2 };
+enum { COS_FULL = 0, COS_POOLED = 1 };
+
+inline float bf16_to_float(uint16_t b) {
+    uint32_t u = static_cast<uint32_t>(b) << 16;
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+// Round a double to the nearest bf16 (ties to even), directly, without going
+// through fp32 first (which could round twice).
+inline uint16_t double_to_bf16(double v) {
+    if (std::isnan(v)) return 0x7FC0;
+    if (std::isinf(v)) return v > 0 ? 0x7F80 : 0xFF80;
+    if (v == 0.0) return std::signbit(v) ? 0x8000 : 0x0000;
+    int e = std::ilogb(v);                 // v = m * 2^e, 1 <= |m| < 2
+    if (e < -126) e = -126;                // subnormal range: fixed quantum
+    // bf16 keeps 8 significant bits: quantum is 2^(e-7)
+    double q = std::nearbyint(std::ldexp(v, 7 - e));   // default mode: ties-to-even
+    double r = std::ldexp(q, e - 7);
+    float f = static_cast<float>(r);       // exact: r has <= 8 significant bits
+    if (std::isinf(f)) return f > 0 ? 0x7F80 : 0xFF80;
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+inline double load_elem(const void* p, int dtype, size_t i) {
+    if (dtype == DT_F32) return static_cast<double>(static_cast<const float*>(p)[i]);
+    return static_cast<double>(bf16_to_float(static_cast<const uint16_t*>(p)[i]));
+}
+
+inline void store_elem(void* p, int dtype, size_t i, double v) {
+    if (dtype == DT_F32) static_cast<float*>(p)[i] = static_cast<float>(v);
+    else static_cast<uint16_t*>(p)[i] = double_to_bf16(v);
+}
+
+inline size_t elem_size(int dtype) { return dtype == DT_F32 ? 4 : 2; }
+
+// "a ranks before b": higher score first, then lower index.  Compared on the
+// fp32 values as stored (so -0.0 and +0.0 tie and the index decides).
+struct ByScoreThenIndex {
+    const float* s;   // score of candidate i is s[i * stride]
+    size_t stride;
+    bool operator()(int a, int b) const {
+        float sa = s[a * stride], sb = s[b * stride];
+        if (sa != sb) return sa > sb;
+        return a < b;
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+// ---------------------------------------------------------------------------
+// Route: GrAP + cosine affinity + softmax gate.
+//   x[T][d] (dtype), w_emb[E][P] fp32 with P = d/D  ->  score[T][E], gate[T][E] fp32
+// cos_mode FULL: Eq. 4 literally, with the expert embedding lifted back to R^d
+//   (every pooled coordinate spread evenly over its group of D inputs):
+//   score = sqrt(D) * <g, w_e> / (|x| * |w_e|).
+// cos_mode POOLED: cosine between the pooled token and the embedding:
+//   score = <g, w_e> / (|g| * |w_e|).
+// A zero-norm token (or embedding) scores 0.
+// ---------------------------------------------------------------------------
+int etr_ref_route(int T, int d, int E, int D, int dtype, int cos_mode,
+                  const void* x, const float* w_emb, float* score, float* gate) {
+    if (T < 0 || d <= 0 || E <= 0 || D <= 0 || d % D != 0) return 2;
+    const int P = d / D;
+    std::vector<double> wnorm(E);
+    for (int e = 0; e < E; ++e) {
+        double s = 0;
+        for (int p = 0; p < P; ++p) s += double(w_emb[e * (size_t)P + p]) * double(w_emb[e * (size_t)P + p]);
+        wnorm[e] = std::sqrt(s);
+    }
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        std::vector<double> g(P);
+        double xx = 0, gg = 0;
+        for (int p = 0; p < P; ++p) {
+            double s = 0;
+            for (int j = 0; j < D; ++j) {
+                double v = load_elem(x, dtype, (size_t)t * d + (size_t)p * D + j);
+                s += v;
+                xx += v * v;
+            }
+            g[p] = s / D;                       // group mean
+            gg += g[p] * g[p];
+        }
+        std::vector<double> sc(E);
+        double mx = -INFINITY;
+        for (int e = 0; e < E; ++e) {
+            double dot = 0;
+            for (int p = 0; p < P; ++p) dot += g[p] * double(w_emb[e * (size_t)P + p]);
+            double den = (cos_mode == COS_FULL) ? std::sqrt(xx) * wnorm[e] : std::sqrt(gg) * wnorm[e];
+            double num = (cos_mode == COS_FULL) ? std::sqrt((double)D) * dot : dot;
+            double v = (den > 0) ? num / den : 0.0;
+            float vf = static_cast<float>(v);
+            score[(size_t)t * E + e] = vf;
+            sc[e] = v;
+            mx = std::max(mx, v);
+        }
+        double z = 0;
+        for (int e = 0; e < E; ++e) z += std::exp(sc[e] - mx);
+        for (int e = 0; e < E; ++e) gate[(size_t)t * E + e] = static_cast<float>(std::exp(sc[e] - mx) / z);
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Select: token choice, capacity-bounded keep, slots.
+//   score[T][E] fp32 (any source)  ->
+//   topk_expert[T][k] (descending score; may be NULL; not written in ECR mode),
+//   slot_of[T][E] (slot of token t in expert e's buffer, -1 if not kept),
+//   slot_token[E][capacity] (inverse; -1 = empty slot), counts[E].
+// ---------------------------------------------------------------------------
+int etr_ref_select(int T, int E, int k, int capacity, int mode, const float* score,
+                   int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts) {
+    if (T < 0 || E <= 0 || capacity < 1) return 2;
+    if (mode != MODE_ECR && (k < 1 || k > E)) return 2;
+    if (mode < 0 || mode > 2) return 3;
+
+    // Eq. 5: every token lists its k best experts.
+    std::vector<std::vector<int>> candidates(E);     // per expert, ascending token index
+    if (mode == MODE_ECR) {
+        for (int e = 0; e < E; ++e) {
+            candidates[e].resize(T);
+            std::iota(candidates[e].begin(), candidates[e].end(), 0);
+        }
+    } else {
+        std::vector<int> order(E);
+        for (int t = 0; t < T; ++t) {
+            std::iota(order.begin(), order.end(), 0);
+            std::stable_sort(order.begin(), order.end(), ByScoreThenIndex{score + (size_t)t * E, 1});
+            for (int j = 0; j < k; ++j) {
+                if (topk_expert) topk_expert[(size_t)t * k + j] = order[j];
+                candidates[order[j]].push_back(t);
+            }
+        }
+    }
+
+    for (size_t i = 0; i < (size_t)T * E; ++i) slot_of[i] = -1;
+    for (size_t i = 0; i < (size_t)E * capacity; ++i) slot_token[i] = -1;
+
+    for (int e = 0; e < E; ++e) {
+        std::vector<int> cand = candidates[e];
+        const int n_keep = std::min<int>(capacity, (int)cand.size());
+        std::vector<int> kept;
+        if (mode == MODE_TCR) {
+            // position priority: the first C tokens (in token order) that chose e
+            kept.assign(cand.begin(), cand.begin() + n_keep);
+        } else {
+            // Eq. 6 / pure ECR: the C candidates with the highest affinity to e
+            std::stable_sort(cand.begin(), cand.end(), ByScoreThenIndex{score + e, (size_t)E});
+            kept.assign(cand.begin(), cand.begin() + n_keep);
+            std::sort(kept.begin(), kept.end());      // slots in ascending token order
+        }
+        counts[e] = n_keep;
+        for (int s = 0; s < n_keep; ++s) {
+            slot_token[(size_t)e * capacity + s] = kept[s];
+            slot_of[(size_t)kept[s] * E + e] = s;
+        }
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Dispatch: xp[e][s][:] = x[slot_token[e][s]][:] for s < counts[e].
+// Rows past counts[e] are zero-filled here (the contract leaves them unspecified).
+// ---------------------------------------------------------------------------
+int etr_ref_dispatch(int T, int d, int E, int capacity, int dtype, const void* x,
+                     const int32_t* slot_token, const int32_t* counts, void* xp) {
+    const size_t es = elem_size(dtype);
+    std::memset(xp, 0, (size_t)E * capacity * d * es);
+    for (int e = 0; e < E; ++e)
+        for (int s = 0; s < counts[e]; ++s) {
+            int t = slot_token[(size_t)e * capacity + s];
+            if (t < 0 || t >= T) return 2;
+            std::memcpy(static_cast<char*>(xp) + ((size_t)e * capacity + s) * d * es,
+                        static_cast<const char*>(x) + (size_t)t * d * es, (size_t)d * es);
+        }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Expert FFN on a list of rows:  y = W_down * ( SiLU(W_gate * x) .* (W_up * x) )
+// with SiLU(a) = a / (1 + exp(-a)); no biases; no intermediate rounding.
+//   rows[r][d] (dtype), expert_of_row[r], w_gate/w_up[E][H][d], w_down[E][d][H]
+//   -> y[r][d] double
+// ---------------------------------------------------------------------------
+int etr_ref_ffn_rows(int n_rows, int d, int H, int dtype, const void* rows, const int32_t* expert_of_row,
+                     const void* w_gate, const void* w_up, const void* w_down, double* y) {
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int r = 0; r < n_rows; ++r) {
+        const int e = expert_of_row[r];
+        std::vector<double> xr(d), h(H);
+        for (int j = 0; j < d; ++j) xr[j] = load_elem(rows, dtype, (size_t)r * d + j);
+        for (int i = 0; i < H; ++i) {
+            double a = 0, b = 0;
+            const size_t base = ((size_t)e * H + i) * d;
+            for (int j = 0; j < d; ++j) {
+                a += load_elem(w_gate, dtype, base + j) * xr[j];
+                b += load_elem(w_up, dtype, base + j) * xr[j];
+            }
+            h[i] = a / (1.0 + std::exp(-a)) * b;
+        }
+        for (int j = 0; j < d; ++j) {
+            double s = 0;
+            const size_t base = ((size_t)e * d + j) * H;
+            for (int i = 0; i < H; ++i) s += load_elem(w_down, dtype, base + i) * h[i];
+            y[(size_t)r * d + j] = s;
+        }
+    }
+    return 0;
+}
+
+// Expert FFN over the capacity-bounded buffers: yp[e][s][:] for s < counts[e]; other rows 0.
+int etr_ref_expert_ffn(int d, int E, int capacity, int H, int dtype, const void* xp, const int32_t* counts,
+                       const void* w_gate, const void* w_up, const void* w_down, double* yp) {
+    std::memset(yp, 0, sizeof(double) * (size_t)E * capacity * d);
+    const size_t es = elem_size(dtype);
+    for (int e = 0; e < E; ++e) {
+        int n = counts[e];
+        if (n < 0 || n > capacity) return 2;
+        std::vector<int32_t> eid(n, e);
+        int rc = etr_ref_ffn_rows(n, d, H, dtype, static_cast<const char*>(xp) + (size_t)e * capacity * d * es,
+                                  eid.data(), w_gate, w_up, w_down, yp + (size_t)e * capacity * d);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Combine (Eq. 1): out[t][:] = sum over experts e (ascending) that kept t of
+// gate[t][e] * yp[e][slot_of[t][e]][:]; accumulated in double, rounded once.
+// ---------------------------------------------------------------------------
+int etr_ref_combine(int T, int d, int E, int capacity, int dtype, const double* yp, const float* gate,
+                    const int32_t* slot_of, void* out) {
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        std::vector<double> acc(d, 0.0);
+        for (int e = 0; e < E; ++e) {
+            int s = slot_of[(size_t)t * E + e];
+            if (s < 0) continue;
+            const double gt = gate[(size_t)t * E + e];
+            const double* yr = yp + ((size_t)e * capacity + s) * d;
+            for (int j = 0; j < d; ++j) acc[j] += gt * yr[j];
+        }
+        for (int j = 0; j < d; ++j) store_elem(out, dtype, (size_t)t * d + j, acc[j]);
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Whole layer.  If score_in is non-NULL the routing starts from those fp32
+// scores (gate is then their row softmax) instead of from x; this is how the
+// tests compare the rest of the layer on identical routing inputs.
+// If n_tokens >= 0, the FFN and the sum are evaluated only for the listed
+// tokens and out holds n_tokens rows (out[i] = layer output of tokens[i]);
+// routing is always done for all T tokens.  Routing tables are returned when
+// the pointers are non-NULL.
+// ---------------------------------------------------------------------------
+int etr_ref_moe_forward(int T, int d, int E, int D, int k, int capacity, int H, int dtype, int mode, int cos_mode,
+                        const void* x, const float* w_emb, const void* w_gate, const void* w_up,
+                        const void* w_down, const float* score_in, const int32_t* tokens, int n_tokens,
+                        void* out, float* score_out, float* gate_out, int32_t* topk_out, int32_t* slot_of_out,
+                        int32_t* slot_token_out, int32_t* counts_out) {
+    std::vector<float> score((size_t)T * E), gate((size_t)T * E);
+    int rc = 0;
+    if (!score_in) {
+        rc = etr_ref_route(T, d, E, D, dtype, cos_mode, x, w_emb, score.data(), gate.data());
+        if (rc) return rc;
+    } else {
+        std::copy(score_in, score_in + (size_t)T * E, score.begin());
+        for (int t = 0; t < T; ++t) {
+            double mx = -INFINITY, z = 0;
+            for (int e = 0; e < E; ++e) mx = std::max(mx, (double)score[(size_t)t * E + e]);
+            for (int e = 0; e < E; ++e) z += std::exp((double)score[(size_t)t * E + e] - mx);
+            for (int e = 0; e < E; ++e)
+                gate[(size_t)t * E + e] = static_cast<float>(std::exp((double)score[(size_t)t * E + e] - mx) / z);
+        }
+    }
+    std::vector<int32_t> topk((size_t)T * std::max(k, 1)), slot_of((size_t)T * E),
+        slot_token((size_t)E * capacity), counts(E);
+    rc = etr_ref_select(T, E, k, capacity, mode, score.data(), topk.data(), slot_of.data(), slot_token.data(),
+                        counts.data());
+    if (rc) return rc;
+
+    std::vector<int32_t> all;
+    if (n_tokens < 0) {
+        all.resize(T);
+        std::iota(all.begin(), all.end(), 0);
+        tokens = all.data();
+        n_tokens = T;
+    }
+    // one FFN row per kept (token, expert) pair of the requested tokens
+    std::vector<int32_t> pair_expert, pair_token_pos;
+    for (int i = 0; i < n_tokens; ++i) {
+        int t = tokens[i];
+        if (t < 0 || t >= T) return 2;
+        for (int e = 0; e < E; ++e)
+            if (slot_of[(size_t)t * E + e] >= 0) { pair_expert.push_back(e); pair_token_pos.push_back(i); }
+    }
+    const size_t es = elem_size(dtype);
+    const int n_pairs = (int)pair_expert.size();
+    std::vector<char> rows((size_t)n_pairs * d * es);
+    for (int r = 0; r < n_pairs; ++r)
+        std::memcpy(rows.data() + (size_t)r * d * es,
+                    static_cast<const char*>(x) + (size_t)tokens[pair_token_pos[r]] * d * es, (size_t)d * es);
+    std::vector<double> y((size_t)n_pairs * d);
+    rc = etr_ref_ffn_rows(n_pairs, d, H, dtype, rows.data(), pair_expert.data(), w_gate, w_up, w_down, y.data());
+    if (rc) return rc;
+    std::vector<double> acc((size_t)n_tokens * d, 0.0);
+    for (int r = 0; r < n_pairs; ++r) {          // pairs are listed token-major, experts ascending
+        int i = pair_token_pos[r];
+        double gt = gate[(size_t)tokens[i] * E + pair_expert[r]];
+        for (int j = 0; j < d; ++j) acc[(size_t)i * d + j] += gt * y[(size_t)r * d + j];
+    }
+    for (size_t i = 0; i < (size_t)n_tokens * d; ++i) store_elem(out, dtype, i, acc[i]);
+
+    if (score_out) std::copy(score.begin(), score.end(), score_out);
+    if (gate_out) std::copy(gate.begin(), gate.end(), gate_out);
+    if (topk_out && mode != MODE_ECR) std::copy(topk.begin(), topk.begin() + (size_t)T * k, topk_out);
+    if (slot_of_out) std::copy(slot_of.begin(), slot_of.end(), slot_of_out);
+    if (slot_token_out) std::copy(slot_token.begin(), slot_token.end(), slot_token_out);
+    if (counts_out) std::copy(counts.begin(), counts.end(), counts_out);
+    return 0;
+}
+
+// helpers exposed for the tests
+uint16_t etr_ref_double_to_bf16(double v) { return double_to_bf16(v); }
+int etr_ref_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+}  // extern "C"

@@ -1,0 +1,187 @@
+"""Pins for the oracle's selection step (token choice, expert choice, slots): CPU only."""
+import itertools
+from fractions import Fraction
+
+import numpy as np
+import pytest
+from scipy import stats
+
+from conftest import load_golden
+
+TCR, ECR, BIDIR = 0, 1, 2
+
+
+def kept_sets(slot_token, counts):
+    return [list(slot_token[e, :counts[e]]) for e in range(slot_token.shape[0])]
+
+
+def check_permutation_tables(T, E, C, slot_of, slot_token, counts):
+    assert slot_of.shape == (T, E) and slot_token.shape == (E, C) and counts.shape == (E,)
+    assert int((slot_of >= 0).sum()) == int(counts.sum())
+    for e in range(E):
+        n = counts[e]
+        assert 0 <= n <= C
+        row = slot_token[e]
+        assert np.all(row[n:] == -1)
+        assert np.all(np.diff(row[:n]) > 0)                      # ascending token order, no duplicates
+        assert np.all(slot_of[row[:n], e] == np.arange(n))
+        col = slot_of[:, e]
+        assert int((col >= 0).sum()) == n
+
+
+def test_worked_example(oracle):
+    g = load_golden("select_worked_example.json")
+    S = np.array(g["score"], np.float32)
+    C = g["capacity"]
+    for kname, k in (("k1", 1), ("k2", 2)):
+        for mname, mode in (("tcr", TCR), ("bidir", BIDIR)):
+            topk, slot_of, slot_token, counts = oracle.select(S, k, C, mode)
+            assert topk.tolist() == g[kname]["topk"]
+            assert [list(map(int, s)) for s in kept_sets(slot_token, counts)] == g[kname][mname]["kept"]
+            check_permutation_tables(6, 3, C, slot_of, slot_token, counts)
+    for k in (1, 2, 3):
+        _, slot_of, slot_token, counts = oracle.select(S, k, C, ECR)
+        assert [list(map(int, s)) for s in kept_sets(slot_token, counts)] == g["ecr"]["kept"]
+
+
+def _scores(rng, T, E, levels=None):
+    if levels:                                                   # many exact ties
+        return (rng.integers(-levels, levels + 1, size=(T, E)) / levels).astype(np.float32)
+    return rng.uniform(-1, 1, size=(T, E)).astype(np.float32)
+
+
+def _best_subset(cands, n, key):
+    """Brute force: the size-n subset with the largest exact score sum; among
+    equal sums the lexicographically smallest index tuple."""
+    best, best_sum = None, None
+    for sub in itertools.combinations(cands, n):                 # generated in lexicographic order
+        s = sum((Fraction(float(key(i))) for i in sub), Fraction(0))
+        if best is None or s > best_sum:
+            best, best_sum = sub, s
+    return list(best) if best is not None else []
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("levels", [None, 3])
+def test_brute_force_small(oracle, seed, levels):
+    rng = np.random.default_rng(100 + seed)
+    T, E = int(rng.integers(5, 13)), int(rng.integers(2, 5))
+    k = int(rng.integers(1, E + 1))
+    C = int(rng.integers(1, T + 2))
+    S = _scores(rng, T, E, levels)
+    # token choice by enumeration
+    choice = []
+    for t in range(T):
+        sub = _best_subset(range(E), k, lambda e: S[t, e])
+        choice.append(sorted(sub, key=lambda e: (-S[t, e], e)))
+    for mode in (TCR, BIDIR, ECR):
+        topk, slot_of, slot_token, counts = oracle.select(S, k, C, mode)
+        check_permutation_tables(T, E, C, slot_of, slot_token, counts)
+        if mode != ECR:
+            assert topk.tolist() == choice
+        for e in range(E):
+            cands = list(range(T)) if mode == ECR else [t for t in range(T) if e in choice[t]]
+            n = min(C, len(cands))
+            if mode == TCR:
+                expect = cands[:n]
+            else:
+                expect = sorted(_best_subset(cands, n, lambda t: S[t, e]))
+            assert list(slot_token[e, :counts[e]]) == expect, (mode, e)
+
+
+@pytest.mark.parametrize("levels", [None, 5])
+def test_invariants_medium(oracle, levels):
+    rng = np.random.default_rng(7)
+    T, E, k, C = 700, 9, 3, 150
+    S = _scores(rng, T, E, levels)
+    order = np.lexsort((np.arange(E)[None, :].repeat(T, 0), -S.astype(np.float64)), axis=1)   # score desc, idx asc
+    chose = np.zeros((T, E), bool)
+    np.put_along_axis(chose, order[:, :k], True, axis=1)
+    res = {m: oracle.select(S, k, C, m) for m in (TCR, ECR, BIDIR)}
+    for m, (topk, slot_of, slot_token, counts) in res.items():
+        check_permutation_tables(T, E, C, slot_of, slot_token, counts)
+        kept = slot_of >= 0
+        if m != ECR:
+            np.testing.assert_array_equal(topk, order[:, :k])
+            assert np.all(kept <= chose)                          # kept only where chosen
+            assert np.all(kept.sum(1) <= k)
+            np.testing.assert_array_equal(counts, np.minimum(C, chose.sum(0)))
+        else:
+            assert np.all(counts == min(C, T))
+        if m == TCR:
+            for e in range(E):
+                np.testing.assert_array_equal(slot_token[e, :counts[e]], np.flatnonzero(chose[:, e])[:C])
+        else:
+            # exchange property: no unkept candidate ranks before a kept one
+            for e in range(E):
+                cand = np.ones(T, bool) if m == ECR else chose[:, e]
+                kk = np.flatnonzero(kept[:, e])
+                uu = np.flatnonzero(cand & ~kept[:, e])
+                if len(kk) and len(uu):
+                    worst_kept = max(kk, key=lambda t: (-S[t, e], t))
+                    best_unkept = min(uu, key=lambda t: (-S[t, e], t))
+                    assert (-S[worst_kept, e], worst_kept) < (-S[best_unkept, e], best_unkept)
+    # BIDIR subset of TCR candidates, ECR/BIDIR equal when every token lists every expert
+    _, so_b, st_b, c_b = oracle.select(S, E, C, BIDIR)
+    _, so_e, st_e, c_e = oracle.select(S, E, C, ECR)
+    np.testing.assert_array_equal(so_b, so_e)
+    np.testing.assert_array_equal(st_b, st_e)
+    # capacity >= T: nothing is dropped, TCR == BIDIR == all choosers
+    _, so_t, _, c_t = oracle.select(S, k, T + 3, TCR)
+    _, so_b, _, c_b = oracle.select(S, k, T + 3, BIDIR)
+    np.testing.assert_array_equal(so_t, so_b)
+    np.testing.assert_array_equal(so_t >= 0, chose)
+    np.testing.assert_array_equal(c_t, chose.sum(0))
+
+
+def test_negative_zero_ties_by_index(oracle):
+    S = np.array([[0.0, -0.0], [-0.0, 0.0], [0.0, 0.0]], np.float32)
+    topk, _, slot_token, counts = oracle.select(S, 1, 2, TCR)
+    assert topk[:, 0].tolist() == [0, 0, 0]
+    _, _, st, c = oracle.select(S, 1, 2, ECR)
+    assert st.tolist() == [[0, 1], [0, 1]]
+
+
+def test_tcr_keep_rate_is_binomial(oracle):
+    """Proof of the Theorem, part 1: under isotropic tokens and top-1 choice the
+    number of earlier tokens on the same expert is Binomial(k-1, 1/n), so the
+    token at (1-based) position k is kept with probability P(Bin(k-1,1/n) < C)."""
+    rng = np.random.default_rng(11)
+    T, n, C, trials = 48, 4, 6, 3000
+    kept = np.zeros(T)
+    for _ in range(trials):
+        S = rng.uniform(-1, 1, size=(T, n)).astype(np.float32)
+        _, slot_of, _, _ = oracle.select(S, 1, C, TCR)
+        kept += (slot_of >= 0).any(1)
+    rate = kept / trials
+    for pos in (1, 6, 7, 16, 24, 32, 48):
+        p = stats.binom.cdf(C - 1, pos - 1, 1.0 / n)
+        sigma = max(np.sqrt(p * (1 - p) / trials), 1e-9)
+        assert abs(rate[pos - 1] - p) <= 4.5 * sigma + 1e-12, (pos, rate[pos - 1], p)
+
+
+def test_ecr_success_is_binomial_tail(oracle):
+    """Proof of the Theorem, part 2: expert i keeps a given token iff at most
+    C-1 other tokens score higher; with i.i.d. continuous scores the number of
+    higher-scoring tokens is uniform on {0..s-1}, so P(kept) = C/s."""
+    rng = np.random.default_rng(12)
+    T, n, C, trials = 40, 3, 7, 3000
+    hit = 0
+    for _ in range(trials):
+        S = rng.uniform(-1, 1, size=(T, n)).astype(np.float32)
+        _, slot_of, _, _ = oracle.select(S, 1, C, ECR)
+        hit += slot_of[17, 1] >= 0
+        higher = int((S[:, 1] > S[17, 1]).sum())
+        assert (slot_of[17, 1] >= 0) == (higher <= C - 1)
+    p = C / T
+    assert abs(hit / trials - p) < 4.5 * np.sqrt(p * (1 - p) / trials)
+
+
+def test_rejects_bad_arguments(oracle):
+    S = np.zeros((4, 3), np.float32)
+    with pytest.raises(RuntimeError):
+        oracle.select(S, 4, 2, TCR)          # k > E
+    with pytest.raises(RuntimeError):
+        oracle.select(S, 1, 0, TCR)          # capacity < 1
+    # ECR ignores k
+    oracle.select(S, 7, 2, ECR)
