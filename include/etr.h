@@ -1,0 +1,151 @@
+/* etr.h - C ABI of the MI355X (gfx950) library for the forward pass of one
+ * Expert-Token Resonance (ETR) Mixture-of-Experts layer.
+ *
+ * Notation (paper symbol -> here): tokens s -> T; experts n -> E; hidden size d;
+ * GrAP group size D; pooled width P = d/D; token Top-l -> k; expert capacity C
+ * (`capacity`); FFN hidden size H; affinity delta_ti -> score[t][e].
+ *
+ * Conventions shared by every entry point
+ *  - Every pointer except the config is a DEVICE pointer owned by the caller.
+ *    The library never allocates, frees or keeps device memory and holds no
+ *    global state.  All arrays are dense, row-major, innermost index contiguous.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work; they never synchronise with the host.
+ *  - Arguments are checked on the host before anything is launched; on error
+ *    nothing is launched and a status is returned:
+ *      ETR_ERR_NULL         a required pointer is NULL
+ *      ETR_ERR_SHAPE        a dimension is <= 0, d % D != 0, k < 1 or k > E
+ *                           (k is ignored in ECR mode), capacity < 1
+ *      ETR_ERR_UNSUPPORTED  E > 64, d % 8 != 0, H % 8 != 0, unknown dtype/mode/cos
+ *      ETR_ERR_WORKSPACE    ws_bytes smaller than the matching *_workspace_bytes(cfg)
+ *      ETR_ERR_ALIGN        a pointer is not 16-byte aligned
+ *      ETR_ERR_HIP          the HIP runtime reported an error at launch
+ *  - capacity > T is legal: selection keeps min(capacity, #candidates) tokens
+ *    and the buffers keep the stride `capacity`.
+ *  - Ties are broken towards the lowest index (expert index in the token's
+ *    choice, token index in the expert's choice); comparisons are on the fp32
+ *    score as stored, -0.0 and +0.0 tie.  NaN or Inf in x or score: undefined
+ *    routing.
+ *  - dtype is the storage type of x, the FFN weights, xp, yp and out; all
+ *    arithmetic accumulates in fp32.  score, gate and w_emb are always fp32.
+ */
+#ifndef ETR_H
+#define ETR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ETR_OK = 0, ETR_ERR_NULL = 1, ETR_ERR_SHAPE = 2, ETR_ERR_UNSUPPORTED = 3,
+    ETR_ERR_WORKSPACE = 4, ETR_ERR_ALIGN = 5, ETR_ERR_HIP = 6
+} etr_status;
+
+typedef enum { ETR_F32 = 0, ETR_BF16 = 1 } etr_dtype;
+
+/* Which half of the bidirectional selection is active; a host-side choice
+ * (Sec. Training Strategy: token choice early in training, expert choice late). */
+typedef enum { ETR_MODE_TCR = 0, ETR_MODE_ECR = 1, ETR_MODE_BIDIR = 2 } etr_mode;
+
+/* Norm used in the cosine of Eq. 4 once the pooled width P may differ from E:
+ * FULL   cos(x_t, lift(w_e)) in R^d, lift = every pooled coordinate spread evenly
+ *        over its D inputs; equals Eqs. 2-4 exactly when P = E and w_emb = I;
+ * POOLED cos(GrAP(x_t), w_e) in R^P. */
+typedef enum { ETR_COS_FULL = 0, ETR_COS_POOLED = 1 } etr_cos_mode;
+
+typedef struct {
+    int32_t T, d, E, D, k, capacity, H;
+    int32_t dtype;      /* etr_dtype    */
+    int32_t mode;       /* etr_mode     */
+    int32_t cos;        /* etr_cos_mode */
+} etr_config;
+
+/* Bytes of device workspace for this config: etr_workspace_bytes is what
+ * etr_moe_forward needs (it covers the two stage calls as well);
+ * etr_select_workspace_bytes and etr_ffn_workspace_bytes are the smaller
+ * amounts that etr_select and etr_expert_ffn need when called on their own.
+ * Each returns 0 for an invalid config. Host-only, launches nothing. */
+size_t etr_workspace_bytes(const etr_config* cfg);
+size_t etr_select_workspace_bytes(const etr_config* cfg);
+size_t etr_ffn_workspace_bytes(const etr_config* cfg);
+
+/* Static, human-readable name of a status code. */
+const char* etr_status_string(etr_status s);
+
+/* GrAP + affinity + gate (Sec. Cost-Efficient Sparse Expert-Token Affinity, Eqs. 2-4;
+ * gate: the row softmax of Eq. 1's text, without the noise term).
+ *   x      [T][d]   dtype   in
+ *   w_emb  [E][d/D] fp32    in   expert embeddings (rows should be mutually orthogonal;
+ *                                their norm is computed, not assumed)
+ *   score  [T][E]   fp32    out  cosine affinity; 0 for a zero-norm token
+ *   gate   [T][E]   fp32    out  softmax over e of score[t][.]
+ */
+etr_status etr_route(const etr_config* cfg, const void* x, const float* w_emb,
+                     float* score, float* gate, void* stream);
+
+/* Bidirectional selection under the capacity bound (Sec. Routing Strategy, Eqs. 5-6;
+ * keep rules of the pure phases: Proof of the Theorem, parts 1 and 2).
+ *   TCR   every token lists its k best experts; expert e keeps the `capacity`
+ *         lowest-index tokens among those that listed it
+ *   ECR   expert e keeps its min(capacity, T) highest-score tokens of all T; k ignored
+ *   BIDIR expert e keeps its `capacity` highest-score tokens among those that listed it
+ *   score        [T][E]        fp32  in
+ *   topk_expert  [T][k]        int32 out  token's experts by descending score; may be NULL;
+ *                                         not written in ECR mode
+ *   slot_of      [T][E]        int32 out  slot of token t in expert e's buffer, -1 if not kept;
+ *                                         slots of one expert ascend with the token index
+ *   slot_token   [E][capacity] int32 out  inverse table; -1 marks an empty slot
+ *   counts       [E]           int32 out  kept tokens per expert
+ *   ws, ws_bytes               scratch, >= etr_select_workspace_bytes(cfg), 16-byte aligned
+ */
+etr_status etr_select(const etr_config* cfg, const float* score, int32_t* topk_expert,
+                      int32_t* slot_of, int32_t* slot_token, int32_t* counts,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* Token rearrangement into capacity-bounded per-expert buffers (the slot table I_{ki} of Eq. 6).
+ *   x [T][d] in; slot_token [E][capacity], counts [E] in
+ *   xp [E][capacity][d] dtype out: xp[e][s] = x[slot_token[e][s]] for s < counts[e];
+ *   rows s >= counts[e] are left untouched (never read downstream).
+ */
+etr_status etr_dispatch(const etr_config* cfg, const void* x, const int32_t* slot_token,
+                        const int32_t* counts, void* xp, void* stream);
+
+/* Expert networks on the kept rows (Sec. Locality Loss: experts are FFN layers; the
+ * Mixtral-style SwiGLU form): yp[e][s] = W_down[e] (SiLU(W_gate[e] xp[e][s]) .* (W_up[e] xp[e][s]))
+ * for s < counts[e].  bf16: MFMA grouped GEMM, fp32 accumulate, the hidden activation and
+ * yp are rounded to bf16.  fp32: plain FMA kernels.
+ *   xp [E][capacity][d] in; counts [E] in (device; the grid is sized for `capacity`)
+ *   w_gate, w_up [E][H][d]; w_down [E][d][H]   dtype in
+ *   yp [E][capacity][d] dtype out; rows s >= counts[e] are left untouched
+ *   ws, ws_bytes: scratch, >= etr_ffn_workspace_bytes(cfg); holds the hidden activation [E][capacity][H]
+ */
+etr_status etr_expert_ffn(const etr_config* cfg, const void* xp, const int32_t* counts,
+                          const void* w_gate, const void* w_up, const void* w_down,
+                          void* yp, void* ws, size_t ws_bytes, void* stream);
+
+/* Gate-weighted sum of Eq. 1 over the experts that kept the token, ascending e, fp32
+ * accumulation, one rounding to dtype.  A token kept by no expert gives a zero row.
+ *   yp [E][capacity][d] in; gate [T][E], slot_of [T][E] in; out [T][d] dtype out
+ */
+etr_status etr_combine(const etr_config* cfg, const void* yp, const float* gate,
+                       const int32_t* slot_of, void* out, void* stream);
+
+/* The whole layer (Sec. Model Architecture, Eqs. 1-6) on one stream, no host
+ * synchronisation: route -> select -> dispatch -> expert FFN -> combine.
+ *   x, w_emb, w_gate, w_up, w_down: as above; out [T][d] dtype
+ *   score, gate_out [T][E], topk_expert [T][k], slot_of [T][E], slot_token [E][capacity],
+ *   counts [E]: optional outputs, each may be NULL (then it lives in ws)
+ */
+etr_status etr_moe_forward(const etr_config* cfg, const void* x, const float* w_emb,
+                           const void* w_gate, const void* w_up, const void* w_down, void* out,
+                           float* score, float* gate_out, int32_t* topk_expert, int32_t* slot_of,
+                           int32_t* slot_token, int32_t* counts,
+                           void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ETR_H */

@@ -1,0 +1,143 @@
+"""Thin ctypes binding of the C-ABI library declared in include/etr.h.
+
+Argument marshalling only: torch tensors provide device memory and the current
+stream; every step of the layer runs in the HIP kernels.  There is no CPU
+fallback: if the shared library is missing or a status is non-zero the call
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from .inputs import EtrShape
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libetr_hip.so")
+
+EXPORTS = ("etr_workspace_bytes", "etr_select_workspace_bytes", "etr_ffn_workspace_bytes", "etr_status_string",
+           "etr_route", "etr_select", "etr_dispatch", "etr_expert_ffn", "etr_combine", "etr_moe_forward")
+
+
+class EtrConfig(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("T", "d", "E", "D", "k", "capacity", "H", "dtype", "mode", "cos")]
+
+
+class EtrError(RuntimeError):
+    def __init__(self, fn: str, status: int, text: str):
+        super().__init__(f"{fn}: status {status} ({text})")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library():
+    """Load libetr_hip.so (built in-tree by paper_2406_00023_amd/build.py). Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} not found: build it with `python -m paper_2406_00023_amd.build` "
+                                "(or __graft_entry__.build()); there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, cp = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(EtrConfig)
+    for name in ("etr_workspace_bytes", "etr_select_workspace_bytes", "etr_ffn_workspace_bytes"):
+        getattr(lib, name).restype = sz
+        getattr(lib, name).argtypes = [cp]
+    lib.etr_status_string.restype = ctypes.c_char_p
+    lib.etr_status_string.argtypes = [ctypes.c_int]
+    sigs = {
+        "etr_route": [cp, vp, vp, vp, vp, vp],
+        "etr_select": [cp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "etr_dispatch": [cp, vp, vp, vp, vp, vp],
+        "etr_expert_ffn": [cp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "etr_combine": [cp, vp, vp, vp, vp, vp],
+        "etr_moe_forward": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+    }
+    for name, args in sigs.items():
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = args
+    _lib = lib
+    return lib
+
+
+def make_config(shape: EtrShape, mode: Optional[int] = None, capacity: Optional[int] = None,
+                cos: Optional[int] = None) -> EtrConfig:
+    return EtrConfig(shape.T, shape.d, shape.E, shape.D, shape.k,
+                     shape.capacity if capacity is None else capacity, shape.H, shape.dtype,
+                     shape.mode if mode is None else mode, shape.cos if cos is None else cos)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> ctypes.c_void_p:
+    if t is None:
+        return ctypes.c_void_p(0)
+    if not t.is_contiguous():
+        raise ValueError("tensors handed to the library must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(fn: str, status: int):
+    if status != 0:
+        raise EtrError(fn, status, load_library().etr_status_string(status).decode())
+
+
+def _nbytes(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def etr_workspace_bytes(cfg: EtrConfig) -> int:
+    return int(load_library().etr_workspace_bytes(ctypes.byref(cfg)))
+
+
+def etr_select_workspace_bytes(cfg: EtrConfig) -> int:
+    return int(load_library().etr_select_workspace_bytes(ctypes.byref(cfg)))
+
+
+def etr_ffn_workspace_bytes(cfg: EtrConfig) -> int:
+    return int(load_library().etr_ffn_workspace_bytes(ctypes.byref(cfg)))
+
+
+def etr_route(cfg, x, w_emb, score, gate):
+    _check("etr_route", load_library().etr_route(ctypes.byref(cfg), _ptr(x), _ptr(w_emb), _ptr(score), _ptr(gate),
+                                                 _stream()))
+
+
+def etr_select(cfg, score, topk_expert, slot_of, slot_token, counts, ws):
+    _check("etr_select", load_library().etr_select(ctypes.byref(cfg), _ptr(score), _ptr(topk_expert), _ptr(slot_of),
+                                                   _ptr(slot_token), _ptr(counts), _ptr(ws), _nbytes(ws), _stream()))
+
+
+def etr_dispatch(cfg, x, slot_token, counts, xp):
+    _check("etr_dispatch", load_library().etr_dispatch(ctypes.byref(cfg), _ptr(x), _ptr(slot_token), _ptr(counts),
+                                                       _ptr(xp), _stream()))
+
+
+def etr_expert_ffn(cfg, xp, counts, w_gate, w_up, w_down, yp, ws):
+    _check("etr_expert_ffn", load_library().etr_expert_ffn(ctypes.byref(cfg), _ptr(xp), _ptr(counts), _ptr(w_gate),
+                                                           _ptr(w_up), _ptr(w_down), _ptr(yp), _ptr(ws), _nbytes(ws),
+                                                           _stream()))
+
+
+def etr_combine(cfg, yp, gate, slot_of, out):
+    _check("etr_combine", load_library().etr_combine(ctypes.byref(cfg), _ptr(yp), _ptr(gate), _ptr(slot_of), _ptr(out),
+                                                     _stream()))
+
+
+def etr_moe_forward(cfg, x, w_emb, w_gate, w_up, w_down, out, ws, score=None, gate=None, topk_expert=None,
+                    slot_of=None, slot_token=None, counts=None):
+    _check("etr_moe_forward", load_library().etr_moe_forward(
+        ctypes.byref(cfg), _ptr(x), _ptr(w_emb), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), _ptr(score),
+        _ptr(gate), _ptr(topk_expert), _ptr(slot_of), _ptr(slot_token), _ptr(counts), _ptr(ws), _nbytes(ws), _stream()))
+
+
+def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    """Device scratch as a uint8 tensor (torch allocations are 256-byte aligned or better)."""
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)

@@ -1,0 +1,53 @@
+// Internal launcher interface between the C-ABI layer (api.hip) and the kernel files.
+// Everything here takes device pointers that the API layer has already validated.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "etr.h"
+
+namespace etr {
+
+constexpr int kWave = 64;
+
+// ---- select workspace ------------------------------------------------------
+// Column-major copy of the per-expert selection keys plus the per-chunk prefix
+// counts of the two-level scan.  All offsets are multiples of 256 bytes.
+struct SelectWs {
+    uint64_t* cmask;     // [T]          bit e set: token listed expert e (Eq. 5)
+    uint32_t* keyT;      // [E][Tpad]    order-preserving key of score[t][e]; 0 = not a candidate
+    uint32_t* tau;       // [E]          threshold key of expert e
+    int32_t*  need_eq;   // [E]          how many candidates with key == tau are kept (lowest token first)
+    int32_t*  pre_gt;    // [E][kMaxChunks] kept-for-sure (key > tau) tokens before the chunk
+    int32_t*  pre_eq;    // [E][kMaxChunks] key == tau tokens before the chunk
+    int       Tpad;      // row stride of keyT
+    int       ipt;       // tokens per chunk (= per thread of the per-expert kernel)
+    int       nchunks;
+};
+constexpr int kSelThreads = 1024;       // threads of the per-expert kernel = max chunks
+size_t select_ws_bytes(int T, int E);
+SelectWs select_ws_carve(void* ws, int T, int E);
+
+// ---- launchers ---------------------------------------------------------------
+// route.hip
+hipError_t launch_route(const etr_config& c, const void* x, const float* w_emb, float* score, float* gate,
+                        hipStream_t st);
+// select.hip
+hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_expert, int32_t* slot_of,
+                         int32_t* slot_token, int32_t* counts, const SelectWs& w, hipStream_t st);
+// permute.hip
+hipError_t launch_dispatch(const etr_config& c, const void* x, const int32_t* slot_token, const int32_t* counts,
+                           void* xp, hipStream_t st);
+hipError_t launch_combine(const etr_config& c, const void* yp, const float* gate, const int32_t* slot_of,
+                          void* out, hipStream_t st);
+// ffn.hip
+size_t ffn_ws_bytes(const etr_config& c);
+hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t* counts, const void* w_gate,
+                             const void* w_up, const void* w_down, void* yp, void* hidden, hipStream_t st);
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+inline size_t elt_bytes(int dtype) { return dtype == ETR_F32 ? 4 : 2; }
+
+}  // namespace etr

@@ -1,0 +1,193 @@
+// GrAP pooling, cosine affinity and gate (Sec. Cost-Efficient Sparse Expert-Token
+// Affinity, Eqs. 2-4; gate = row softmax of Eq. 1's text).
+//
+// HBM-bound: every token row is read exactly once with 16-byte loads; one
+// wavefront owns one token.  The pooled vector g (P floats) is reduced inside
+// the wave with lane shuffles and staged in LDS; the expert embeddings sit in
+// LDS with a padded row stride so that the E x L lane grid of the dot-product
+// stage reads conflict-free.  Scores and gates leave as fp32.
+#include "etr_internal.h"
+
+namespace etr {
+namespace {
+
+constexpr int kRouteThreads = 256;
+constexpr int kRouteWaves = kRouteThreads / kWave;
+constexpr int kUnroll = 8;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+
+template <bool BF16>
+struct Chunk;   // one 16-byte piece of a token row
+
+template <>
+struct Chunk<false> {
+    static constexpr int kVec = 4;
+    __device__ static void load(const void* row, int c, bool ok, float* f) {
+        float4 v = ok ? reinterpret_cast<const float4*>(row)[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+    __device__ static float scalar(const void* row, int i) { return reinterpret_cast<const float*>(row)[i]; }
+};
+
+template <>
+struct Chunk<true> {
+    static constexpr int kVec = 8;
+    __device__ static void load(const void* row, int c, bool ok, float* f) {
+        uint4 v = ok ? reinterpret_cast<const uint4*>(row)[c] : make_uint4(0u, 0u, 0u, 0u);
+        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
+        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
+        f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xFFFF0000u);
+        f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xFFFF0000u);
+    }
+    __device__ static float scalar(const void* row, int i) {
+        return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(row)[i]) << 16);
+    }
+};
+
+struct RouteParams {
+    int T, d, E, D, P;
+    int cos_mode;
+    int L;          // lanes cooperating on one expert in the dot-product stage (power of two, E*L <= 64)
+    int w_stride;   // padded LDS row stride of the embeddings (floats)
+    int R;          // 16-byte chunks per pooling group when that is a power of two <= 64, else 0
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteParams p, const void* __restrict__ x,
+                                                              const float* __restrict__ w_emb,
+                                                              float* __restrict__ score, float* __restrict__ gate) {
+    using C = Chunk<BF16>;
+    constexpr int V = C::kVec;
+    extern __shared__ float smem[];
+    float* Ws = smem;                                  // [E][w_stride]
+    float* wn = Ws + p.E * p.w_stride;                 // [64] embedding norms
+    float* gs = wn + 64;                               // [waves][P]
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+
+    for (int i = tid; i < p.E * p.P; i += kRouteThreads) {
+        int e = i / p.P, q = i - e * p.P;
+        Ws[e * p.w_stride + q] = w_emb[i];
+    }
+    __syncthreads();
+    for (int e = wave; e < p.E; e += kRouteWaves) {
+        float s = 0.f;
+        for (int q = lane; q < p.P; q += kWave) { float w = Ws[e * p.w_stride + q]; s += w * w; }
+        s = wave_sum(s);
+        if (lane == 0) wn[e] = sqrtf(s);
+    }
+    __syncthreads();
+
+    float* g = gs + wave * p.P;
+    const int nchunks = p.d / V;
+    const float invD = 1.0f / static_cast<float>(p.D);
+    const float sqrtD = sqrtf(static_cast<float>(p.D));
+    const int e_lane = lane / p.L, sub = lane & (p.L - 1);
+    const size_t row_bytes = static_cast<size_t>(p.d) * (BF16 ? 2 : 4);
+
+    // every wave of the block runs the same number of iterations (block-wide barriers inside)
+    for (int t0 = blockIdx.x * kRouteWaves; t0 < p.T; t0 += gridDim.x * kRouteWaves) {
+        const int t = t0 + wave;
+        const bool live = t < p.T;
+        const char* row = reinterpret_cast<const char*>(x) + static_cast<size_t>(live ? t : 0) * row_bytes;
+        float xx = 0.f;
+        if (p.R > 0) {
+            for (int c0 = 0; c0 < nchunks; c0 += kWave * kUnroll) {
+                float f[kUnroll][V];
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    int c = c0 + u * kWave + lane;
+                    C::load(row, c, live && c < nchunks, f[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u) {
+                    int c = c0 + u * kWave + lane;
+                    float s = 0.f;
+#pragma unroll
+                    for (int j = 0; j < V; ++j) { s += f[u][j]; xx += f[u][j] * f[u][j]; }
+                    for (int m = 1; m < p.R; m <<= 1) s += __shfl_xor(s, m, kWave);
+                    if ((lane & (p.R - 1)) == 0 && c < nchunks) g[c / p.R] = s * invD;
+                }
+            }
+        } else {
+            // group size not a multiple of the 16-byte vector: scalar walk, one lane per pooled feature
+            for (int q = lane; q < p.P; q += kWave) {
+                float s = 0.f;
+                for (int j = 0; j < p.D; ++j) {
+                    float v = live ? C::scalar(row, q * p.D + j) : 0.f;
+                    s += v; xx += v * v;
+                }
+                g[q] = s * invD;
+            }
+        }
+        xx = wave_sum(xx);
+        __syncthreads();
+
+        float acc = 0.f, gg = 0.f;
+        if (e_lane < p.E) {
+            const float* wr = Ws + e_lane * p.w_stride;
+            for (int q = sub; q < p.P; q += p.L) acc += g[q] * wr[q];
+        }
+        for (int m = 1; m < p.L; m <<= 1) acc += __shfl_xor(acc, m, kWave);
+        float den;
+        if (p.cos_mode == ETR_COS_POOLED) {
+            for (int q = lane; q < p.P; q += kWave) gg += g[q] * g[q];
+            gg = wave_sum(gg);
+            den = sqrtf(gg);
+        } else {
+            den = sqrtf(xx);
+            acc *= sqrtD;
+        }
+        const bool is_e = e_lane < p.E;
+        den *= is_e ? wn[e_lane] : 0.f;
+        const float sc = (is_e && den > 0.f) ? acc / den : 0.f;
+        float mx = is_e ? sc : -INFINITY;
+        for (int m = p.L; m < kWave; m <<= 1) mx = fmaxf(mx, __shfl_xor(mx, m, kWave));
+        const float ex = is_e ? expf(sc - mx) : 0.f;
+        float z = ex;
+        for (int m = p.L; m < kWave; m <<= 1) z += __shfl_xor(z, m, kWave);
+        if (live && is_e && sub == 0) {
+            score[static_cast<size_t>(t) * p.E + e_lane] = sc;
+            gate[static_cast<size_t>(t) * p.E + e_lane] = ex / z;
+        }
+        __syncthreads();      // g is rewritten by the next iteration
+    }
+}
+
+}  // namespace
+
+hipError_t launch_route(const etr_config& c, const void* x, const float* w_emb, float* score, float* gate,
+                        hipStream_t st) {
+    RouteParams p;
+    p.T = c.T; p.d = c.d; p.E = c.E; p.D = c.D; p.P = c.d / c.D; p.cos_mode = c.cos;
+    int e2 = 1;
+    while (e2 < c.E) e2 <<= 1;
+    p.L = kWave / e2;
+    p.w_stride = p.P + ((p.L - p.P % 64) % 64 + 64) % 64;
+    const int V = c.dtype == ETR_BF16 ? 8 : 4;
+    p.R = 0;
+    if (c.D % V == 0) {
+        int r = c.D / V;
+        if (r <= 64 && (r & (r - 1)) == 0) p.R = r;
+    }
+    const size_t lds = sizeof(float) * (static_cast<size_t>(p.E) * p.w_stride + 64 + kRouteWaves * p.P);
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    int blocks = (c.T + kRouteWaves - 1) / kRouteWaves;
+    if (blocks > 256 * 8) blocks = 256 * 8;
+    if (blocks < 1) blocks = 1;
+    auto kern = c.dtype == ETR_BF16 ? route_kernel<true> : route_kernel<false>;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(kRouteThreads), lds, st, p, x, w_emb, score, gate);
+    return hipGetLastError();
+}
+
+}  // namespace etr

@@ -1,0 +1,303 @@
+// Bidirectional selection under the capacity bound (Sec. Routing Strategy, Eqs. 5-6; keep
+// rules of the pure phases from the Proof of the Theorem, parts 1 and 2) and the
+// prefix-sum permutation tables.
+//
+// Three launches, no atomics, so the result is bit-reproducible:
+//   1. token_choice_kernel   one lane per (token, expert): k rounds of arg-max inside a
+//                            lane group give the token's Top-k list (Eq. 5); writes the
+//                            candidate mask and a column-major copy of the selection keys
+//   2. expert_choice_kernel  one 1024-thread workgroup per expert: finds the key tau_e of
+//                            the C-th best candidate by bitwise bisection over the 32-bit
+//                            order-preserving keys held in registers (Eq. 6), then scans
+//                            the (key > tau, key == tau) indicator pairs into per-chunk
+//                            exclusive prefixes
+//   3. slot_kernel           one thread per (chunk, expert) walks its tokens in order and
+//                            emits slot_of / slot_token; coalesced over the expert index
+// All three phases are one algorithm: in TCR every candidate has the same key, so
+// "the C best, lowest token first among equals" is "the first C in token order".
+#include "etr_internal.h"
+
+namespace etr {
+namespace {
+
+// fp32 -> uint32 that preserves order; 0 is reserved for "not a candidate".
+__device__ __forceinline__ uint32_t order_key(float s) {
+    uint32_t u = __float_as_uint(s);
+    if (u == 0x80000000u) u = 0u;                       // -0.0 ties with +0.0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ uint32_t selection_key(float s, bool cand, int mode) {
+    if (!cand) return 0u;
+    return mode == ETR_MODE_TCR ? 1u : order_key(s);
+}
+
+// ---------------------------------------------------------------------------------------
+// 1. token choice
+// ---------------------------------------------------------------------------------------
+template <int G>   // lanes per token, power of two >= E
+__global__ __launch_bounds__(256) void token_choice_kernel(const float* __restrict__ score, int T, int E, int k,
+                                                           int mode, int32_t* __restrict__ topk,
+                                                           uint64_t* __restrict__ cmask,
+                                                           uint32_t* __restrict__ keyT, int Tpad) {
+    const int gid = blockIdx.x * 256 + threadIdx.x;
+    const int t = gid / G, e = gid % G;
+    const bool valid = t < T && e < E;
+    const float val = valid ? score[static_cast<size_t>(t) * E + e] : 0.f;
+    uint64_t mask = 0;
+    if (mode != ETR_MODE_ECR) {
+        int taken = valid ? 0 : 1;
+        for (int r = 0; r < k; ++r) {
+            float bv = val; int bi = e; int bt = taken;
+#pragma unroll
+            for (int m = 1; m < G; m <<= 1) {
+                float ov = __shfl_xor(bv, m, kWave);
+                int oi = __shfl_xor(bi, m, kWave);
+                int ot = __shfl_xor(bt, m, kWave);
+                bool better = (ot < bt) || (ot == bt && (ov > bv || (ov == bv && oi < bi)));
+                if (better) { bv = ov; bi = oi; bt = ot; }
+            }
+            if (bi == e) taken = 1;
+            mask |= 1ull << bi;
+            if (e == 0 && t < T && topk) topk[static_cast<size_t>(t) * k + r] = bi;
+        }
+    } else {
+        mask = E >= 64 ? ~0ull : ((1ull << E) - 1ull);
+    }
+    if (valid) keyT[static_cast<size_t>(e) * Tpad + t] = selection_key(val, (mask >> e) & 1ull, mode);
+    if (e == 0 && t < T) cmask[t] = mask;
+}
+
+// ---------------------------------------------------------------------------------------
+// 2. expert choice: threshold search + chunk prefixes
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+
+// Block-wide sums of three counters (all threads get the totals).
+__device__ __forceinline__ void block_sum3(int& a, int& b, int& c, int (*red)[3]) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    a = wave_sum_i(a); b = wave_sum_i(b); c = wave_sum_i(c);
+    __syncthreads();                                   // previous readers of red are done
+    if (lane == 0) { red[wave][0] = a; red[wave][1] = b; red[wave][2] = c; }
+    __syncthreads();
+    a = b = c = 0;
+#pragma unroll
+    for (int w = 0; w < kSelThreads / kWave; ++w) { a += red[w][0]; b += red[w][1]; c += red[w][2]; }
+}
+
+// IPT > 0: the thread's ipt (<= IPT) keys live in registers.  IPT == 0: streamed from memory.
+template <int IPT>
+__global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32_t* __restrict__ keyT, int Tpad, int T,
+                                                                    int ipt, int capacity, int mode,
+                                                                    uint32_t* __restrict__ tau_out,
+                                                                    int32_t* __restrict__ need_eq_out,
+                                                                    int32_t* __restrict__ pre_gt,
+                                                                    int32_t* __restrict__ pre_eq,
+                                                                    int32_t* __restrict__ counts) {
+    __shared__ int red[kSelThreads / kWave][3];
+    __shared__ int wave_tot[kSelThreads / kWave][2];
+    const int e = blockIdx.x, tid = threadIdx.x;
+    const uint32_t* col = keyT + static_cast<size_t>(e) * Tpad;
+    const int base = tid * ipt;
+
+    uint32_t keys[IPT > 0 ? IPT : 1];
+    if constexpr (IPT > 0) {
+#pragma unroll
+        for (int j = 0; j < IPT; j += 4) {
+            const int idx = base + j;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (j < ipt && idx < Tpad) v = *reinterpret_cast<const uint4*>(col + idx);   // ipt, Tpad multiples of 4
+            keys[j + 0] = idx + 0 < T ? v.x : 0u;
+            keys[j + 1] = idx + 1 < T ? v.y : 0u;
+            keys[j + 2] = idx + 2 < T ? v.z : 0u;
+            keys[j + 3] = idx + 3 < T ? v.w : 0u;
+        }
+    }
+    // count_ge of up to three thresholds at once, over the whole column
+    auto count3 = [&](uint32_t t1, uint32_t t2, uint32_t t3, int& c1, int& c2, int& c3) {
+        c1 = c2 = c3 = 0;
+        if constexpr (IPT > 0) {
+#pragma unroll
+            for (int j = 0; j < IPT; ++j) {
+                c1 += keys[j] >= t1; c2 += keys[j] >= t2; c3 += keys[j] >= t3;
+            }
+        } else {
+            for (int idx = tid; idx < T; idx += kSelThreads) {
+                uint32_t key = col[idx];
+                c1 += key >= t1; c2 += key >= t2; c3 += key >= t3;
+            }
+        }
+        block_sum3(c1, c2, c3, red);
+    };
+
+    int ncand, d1, d2;
+    count3(1u, 0xFFFFFFFFu, 0xFFFFFFFFu, ncand, d1, d2);
+    const int n_keep = ncand < capacity ? ncand : capacity;
+
+    uint32_t tau;
+    if (n_keep == 0) {
+        tau = 0xFFFFFFFFu;
+    } else if (mode == ETR_MODE_TCR) {
+        tau = 1u;                                       // every candidate carries key 1
+    } else {
+        // largest tau with #(key >= tau) >= n_keep, two bits per round
+        tau = 0u;
+        for (int shift = 30; shift >= 0; shift -= 2) {
+            int c1, c2, c3;
+            count3(tau | (1u << shift), tau | (2u << shift), tau | (3u << shift), c1, c2, c3);
+            uint32_t b = c3 >= n_keep ? 3u : (c2 >= n_keep ? 2u : (c1 >= n_keep ? 1u : 0u));
+            tau |= b << shift;
+        }
+    }
+
+    // per-thread (= per-chunk) counts in token order, then an exclusive block scan
+    int gt = 0, eq = 0;
+    if constexpr (IPT > 0) {
+#pragma unroll
+        for (int j = 0; j < IPT; ++j) { gt += keys[j] > tau; eq += (keys[j] == tau) && keys[j] != 0u; }
+    } else {
+        for (int j = 0; j < ipt; ++j) {
+            const int idx = base + j;
+            uint32_t key = idx < T ? col[idx] : 0u;
+            gt += key > tau; eq += (key == tau) && key != 0u;
+        }
+    }
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    int igt = gt, ieq = eq;                             // inclusive scan inside the wave
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) {
+        int a = __shfl_up(igt, m, kWave), b = __shfl_up(ieq, m, kWave);
+        if (lane >= m) { igt += a; ieq += b; }
+    }
+    if (lane == kWave - 1) { wave_tot[wave][0] = igt; wave_tot[wave][1] = ieq; }
+    __syncthreads();
+    int off_gt = 0, off_eq = 0, tot_gt = 0;
+#pragma unroll
+    for (int w = 0; w < kSelThreads / kWave; ++w) {
+        if (w < wave) { off_gt += wave_tot[w][0]; off_eq += wave_tot[w][1]; }
+        tot_gt += wave_tot[w][0];
+    }
+    pre_gt[e * kSelThreads + tid] = off_gt + igt - gt;
+    pre_eq[e * kSelThreads + tid] = off_eq + ieq - eq;
+    if (tid == 0) {
+        tau_out[e] = tau;
+        need_eq_out[e] = n_keep - tot_gt;
+        counts[e] = n_keep;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// 3. slots
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void slot_kernel(const float* __restrict__ score, const uint64_t* __restrict__ cmask,
+                                                   int T, int E, int capacity, int mode, int ipt, int nchunks,
+                                                   const uint32_t* __restrict__ tau_in,
+                                                   const int32_t* __restrict__ need_eq_in,
+                                                   const int32_t* __restrict__ pre_gt,
+                                                   const int32_t* __restrict__ pre_eq,
+                                                   const int32_t* __restrict__ counts, int32_t* __restrict__ slot_of,
+                                                   int32_t* __restrict__ slot_token) {
+    const int gid = blockIdx.x * 256 + threadIdx.x;
+    const int c = gid / E, e = gid - c * E;
+    if (c < nchunks) {
+        const uint32_t tau = tau_in[e];
+        const int need = need_eq_in[e];
+        int gt = pre_gt[e * kSelThreads + c], eq = pre_eq[e * kSelThreads + c];
+        const int t_end = min(T, (c + 1) * ipt);
+        for (int t = c * ipt; t < t_end; ++t) {
+            const float s = score[static_cast<size_t>(t) * E + e];
+            const uint32_t key = selection_key(s, (cmask[t] >> e) & 1ull, mode);
+            int slot = -1;
+            if (key > tau) {
+                slot = gt + min(eq, need);
+                ++gt;
+            } else if (key == tau && key != 0u) {
+                if (eq < need) slot = gt + eq;
+                ++eq;
+            }
+            slot_of[static_cast<size_t>(t) * E + e] = slot;
+            if (slot >= 0) slot_token[static_cast<size_t>(e) * capacity + slot] = t;
+        }
+    }
+    // empty slots
+    const int total = gridDim.x * 256;
+    for (long long i = gid; i < static_cast<long long>(E) * capacity; i += total) {
+        const int ee = static_cast<int>(i / capacity), s = static_cast<int>(i - static_cast<long long>(ee) * capacity);
+        if (s >= counts[ee]) slot_token[i] = -1;
+    }
+}
+
+}  // namespace
+
+static int chunk_tokens(int T) {
+    int ipt = (T + kSelThreads - 1) / kSelThreads;
+    ipt = (ipt + 3) / 4 * 4;
+    return ipt < 4 ? 4 : ipt;
+}
+
+size_t select_ws_bytes(int T, int E) {
+    const size_t Tpad = align_up(static_cast<size_t>(T), 64);
+    return align_up(sizeof(uint64_t) * T) + align_up(sizeof(uint32_t) * E * Tpad) + 2 * align_up(sizeof(int32_t) * E) +
+           2 * align_up(sizeof(int32_t) * E * kSelThreads);
+}
+
+SelectWs select_ws_carve(void* ws, int T, int E) {
+    SelectWs w;
+    char* p = static_cast<char*>(ws);
+    w.Tpad = static_cast<int>(align_up(static_cast<size_t>(T), 64));
+    w.cmask = reinterpret_cast<uint64_t*>(p);  p += align_up(sizeof(uint64_t) * T);
+    w.keyT = reinterpret_cast<uint32_t*>(p);   p += align_up(sizeof(uint32_t) * E * w.Tpad);
+    w.tau = reinterpret_cast<uint32_t*>(p);    p += align_up(sizeof(int32_t) * E);
+    w.need_eq = reinterpret_cast<int32_t*>(p); p += align_up(sizeof(int32_t) * E);
+    w.pre_gt = reinterpret_cast<int32_t*>(p);  p += align_up(sizeof(int32_t) * E * kSelThreads);
+    w.pre_eq = reinterpret_cast<int32_t*>(p);
+    w.ipt = chunk_tokens(T);
+    w.nchunks = (T + w.ipt - 1) / w.ipt;
+    return w;
+}
+
+hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_expert, int32_t* slot_of,
+                         int32_t* slot_token, int32_t* counts, const SelectWs& w, hipStream_t st) {
+    int G = 1;
+    while (G < c.E) G <<= 1;
+    const long long lanes = static_cast<long long>(c.T) * G;
+    const int blocks1 = static_cast<int>((lanes + 255) / 256);
+#define ETR_TC(GG)                                                                                              \
+    hipLaunchKernelGGL(token_choice_kernel<GG>, dim3(blocks1), dim3(256), 0, st, score, c.T, c.E, c.k, c.mode, \
+                       topk_expert, w.cmask, w.keyT, w.Tpad)
+    switch (G) {
+        case 1: ETR_TC(1); break;
+        case 2: ETR_TC(2); break;
+        case 4: ETR_TC(4); break;
+        case 8: ETR_TC(8); break;
+        case 16: ETR_TC(16); break;
+        case 32: ETR_TC(32); break;
+        default: ETR_TC(64); break;
+    }
+#undef ETR_TC
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+
+#define ETR_EC(II)                                                                                               \
+    hipLaunchKernelGGL(expert_choice_kernel<II>, dim3(c.E), dim3(kSelThreads), 0, st, w.keyT, w.Tpad, c.T, w.ipt, \
+                       c.capacity, c.mode, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts)
+    if (w.ipt <= 4) ETR_EC(4);
+    else if (w.ipt <= 16) ETR_EC(16);
+    else if (w.ipt <= 64) ETR_EC(64);
+    else ETR_EC(0);
+#undef ETR_EC
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+
+    const long long pairs = static_cast<long long>(w.nchunks) * c.E;
+    const int blocks3 = static_cast<int>((pairs + 255) / 256);
+    hipLaunchKernelGGL(slot_kernel, dim3(blocks3), dim3(256), 0, st, score, w.cmask, c.T, c.E, c.capacity, c.mode, w.ipt,
+                       w.nchunks, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts, slot_of, slot_token);
+    return hipGetLastError();
+}
+
+}  // namespace etr
