@@ -72,7 +72,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
 
     int e, mt, nt;
     if (!decode_tile(p, e, mt, nt)) return;
-    const int count = p.counts[e];
+    const int count = min(p.counts[e], p.capacity);
     const int m0 = mt * BM, n0 = nt * BN;
     if (m0 >= count) return;
 
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
     __shared__ float Bs[GLU ? 2 : 1][BK][LD];
     int e, mt, nt;
     if (!decode_tile(p, e, mt, nt)) return;
-    const int count = p.counts[e];
+    const int count = min(p.counts[e], p.capacity);
     const int m0 = mt * BM, n0 = nt * BN;
     if (m0 >= count) return;
     const int tid = threadIdx.x, K = p.K;

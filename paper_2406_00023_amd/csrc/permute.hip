@@ -15,14 +15,15 @@ constexpr int kRowWaves = kRowThreads / kWave;
 __global__ __launch_bounds__(kRowThreads) void dispatch_kernel(const uint4* __restrict__ x,
                                                                const int32_t* __restrict__ slot_token,
                                                                const int32_t* __restrict__ counts,
-                                                               uint4* __restrict__ xp, int capacity, long long rows,
-                                                               int row_vecs) {
+                                                               uint4* __restrict__ xp, int T, int capacity,
+                                                               long long rows, int row_vecs) {
     const int lane = threadIdx.x & (kWave - 1);
     const long long r = static_cast<long long>(blockIdx.x) * kRowWaves + threadIdx.x / kWave;
     if (r >= rows) return;
     const int e = static_cast<int>(r / capacity), s = static_cast<int>(r - static_cast<long long>(e) * capacity);
     if (s >= counts[e]) return;
     const int t = slot_token[r];
+    if (t < 0 || t >= T) return;                       // a table that does not belong to this x: skip the row
     const uint4* src = x + static_cast<size_t>(t) * row_vecs;
     uint4* dst = xp + static_cast<size_t>(r) * row_vecs;
     constexpr int U = 8;
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(kRowThreads) void combine_kernel(const uint4* __res
         my_slot = slot_of[static_cast<size_t>(t) * E + lane];
         my_gate = gate[static_cast<size_t>(t) * E + lane];
     }
-    const uint64_t kept = __ballot(my_slot >= 0);
+    const uint64_t kept = __ballot(my_slot >= 0 && my_slot < capacity);
     constexpr int U = 4;
     for (int c0 = 0; c0 < row_vecs; c0 += kWave * U) {
         float acc[U][V];
@@ -136,8 +137,8 @@ hipError_t launch_dispatch(const etr_config& c, const void* x, const int32_t* sl
     const int row_vecs = static_cast<int>(static_cast<size_t>(c.d) * elt_bytes(c.dtype) / 16);
     const long long blocks = (rows + kRowWaves - 1) / kRowWaves;
     hipLaunchKernelGGL(dispatch_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kRowThreads), 0, st,
-                       static_cast<const uint4*>(x), slot_token, counts, static_cast<uint4*>(xp), c.capacity, rows,
-                       row_vecs);
+                       static_cast<const uint4*>(x), slot_token, counts, static_cast<uint4*>(xp), c.T, c.capacity,
+                       rows, row_vecs);
     return hipGetLastError();
 }
 

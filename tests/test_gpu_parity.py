@@ -36,7 +36,7 @@ SMALL = {
     "cfg2s": lambda: I.small_variant(I.CONFIGS["cfg2"], T=1100, d=512, H=704),
     "cfg3s": lambda: I.small_variant(I.CONFIGS["cfg3"], T=900, d=1024, H=1032),
     "cfg4s": lambda: I.small_variant(I.CONFIGS["cfg4"], T=1500, d=1024, H=328),
-    "cfg5s": lambda: I.small_variant(I.CONFIGS["cfg5"], T=1300, d=1024, H=200),
+    "cfg5s": lambda: I.small_variant(I.CONFIGS["cfg5"], T=700, H=200),     # full d: 64 pooled features for 64 global experts
 }
 
 
