@@ -1,0 +1,154 @@
+#!/usr/bin/env python3
+"""Benchmark of the ETR MoE-layer forward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2] [--capacity C] [--no-cpu-baseline]
+
+A "step" is one pass of the whole hot path (route -> select -> dispatch -> expert FFN ->
+combine, one etr_moe_forward call) over one batch of seeded synthetic tokens that is
+already resident in HBM.  Prints ONE JSON line: tokens/s of the whole layer, the roofline
+position of the dominant kernel (the gate/up MFMA grouped GEMM) measured with HIP events
+on the launch stream, per-stage times, and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3       # fp32 vector
+PEAK_HBM_GBS = 8000.0
+
+
+def _to_np(t):
+    import numpy as np
+    import torch
+    t = t.detach().cpu().contiguous()
+    return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+
+
+def cpu_baseline(shape, cfg, tensors, budget_tokens: int):
+    """Times the oracle (as it stands) on the host cores: routing on all T tokens, the expert
+    FFN and the weighted sum on the first `budget_tokens` tokens, extrapolated linearly in tokens."""
+    import numpy as np
+    from oracle import etr_ref
+    host = {k: _to_np(v) for k, v in tensors.items()}
+    n = min(budget_tokens, shape.T)
+    t0 = time.perf_counter()
+    score, _ = etr_ref.route(host["x"], host["w_emb"], shape.D, shape.dtype, cfg.cos)
+    etr_ref.select(score, shape.k, cfg.capacity, cfg.mode)
+    t_routing = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    etr_ref.moe_forward(host["x"], host["w_emb"], host["w_gate"], host["w_up"], host["w_down"], D=shape.D, k=shape.k,
+                        capacity=cfg.capacity, dtype=shape.dtype, mode=cfg.mode, cos_mode=cfg.cos,
+                        tokens=np.arange(n, dtype=np.int32))
+    t_sample = time.perf_counter() - t0
+    t_full = t_routing + max(t_sample - t_routing, 0.0) * (shape.T / n)
+    return {"value": shape.T / t_full, "unit": "tokens/s", "cores": etr_ref.num_threads(), "kind": "oracle",
+            "sample": f"routing on all {shape.T} tokens ({t_routing:.2f} s); FFN+combine on the first {n} tokens "
+                      f"({t_sample - t_routing:.2f} s), extrapolated linearly to {shape.T}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--capacity", type=int, default=None, help="override the capacity (cfg4's schedule)")
+    ap.add_argument("--cpu-tokens", type=int, default=8192, help="tokens of the oracle's FFN sample")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1")
+
+    import torch
+    from paper_2406_00023_amd import binding as B
+    from paper_2406_00023_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    B.load_library()
+    shape = I.CONFIGS[args.config]
+    cfg = B.make_config(shape, capacity=args.capacity)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    t = I.make_inputs(shape, dev)
+    out = torch.empty(shape.T, shape.d, dtype=shape.torch_dtype, device=dev)
+    counts = torch.zeros(shape.E, dtype=torch.int32, device=dev)
+    ws = B.alloc_workspace(B.etr_workspace_bytes(cfg), dev)
+
+    def step(events=None):
+        if events is None:
+            B.etr_moe_forward(cfg, t["x"], t["w_emb"], t["w_gate"], t["w_up"], t["w_down"], out, ws, counts=counts)
+        else:
+            B.etr_moe_forward_profiled(cfg, t["x"], t["w_emb"], t["w_gate"], t["w_up"], t["w_down"], out, ws, events,
+                                       counts=counts)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [B.StageEvents() for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    stage = [0.0] * (B.N_STAGE_EVENTS - 1)
+    for ev in events:
+        for i, ms in enumerate(ev.stage_ms()):
+            stage[i] += ms / args.steps
+    rows = int(counts.sum().item())
+    elt = 4 if shape.dtype == I.DT_F32 else 2
+    # dominant kernel: FFN GEMM-1 (gate and up projections + SwiGLU), 4*d*H flop per kept row
+    flops_gemm1 = 4.0 * rows * shape.d * shape.H
+    t_gemm1 = stage[3] * 1e-3
+    peak = PEAK_BF16_TFLOPS if shape.dtype == I.DT_BF16 else PEAK_F32_TFLOPS
+    achieved = flops_gemm1 / t_gemm1 / 1e12
+    stages = {name: round(ms, 5) for name, ms in zip(B.STAGE_NAMES, stage)}
+    # algorithmic bytes of the HBM-bound stages -> GB/s (for the report; the roofline object is the GEMM's)
+    TE = shape.T * shape.E
+    bytes_alg = {
+        "route": shape.T * shape.d * elt + 2 * TE * 4,
+        "dispatch": rows * (2 * shape.d * elt + 4),
+        "combine": rows * shape.d * elt + shape.T * shape.d * elt + TE * 8,
+    }
+    hbm = {k: round(v / (stages[k] * 1e-3) / 1e9, 1) for k, v in bytes_alg.items() if stages[k] > 0}
+    flops_gemm2 = 2.0 * rows * shape.d * shape.H
+    res = {
+        "metric": "MoE-layer tokens/sec on 1 MI355X",
+        "value": shape.T / (elapsed / args.steps),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.dtype == I.DT_BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{shape.name}: T={shape.T} d={shape.d} E={shape.E} D={shape.D} k={shape.k} "
+                               f"capacity={cfg.capacity} H={shape.H} mode={('TCR', 'ECR', 'BIDIR')[cfg.mode]} "
+                               f"tokens={shape.recipe}",
+                   "kept_rows": rows},
+        "roofline": {"kernel": "gemm_bf16_kernel<GLU> (FFN gate/up + SwiGLU)" if shape.dtype == I.DT_BF16
+                     else "gemm_f32_kernel<GLU>",
+                     "bound": "mfma" if shape.dtype == I.DT_BF16 else "alu",
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None},
+        "stage_ms": stages,
+        "stage_hbm_GBs": hbm,
+        "ffn_down_TFLOPs": flops_gemm2 / (stage[4] * 1e-3) / 1e12 if stage[4] > 0 else None,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(shape, cfg, t, args.cpu_tokens)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -145,6 +145,19 @@ etr_status etr_moe_forward(const etr_config* cfg, const void* x, const float* w_
                            int32_t* slot_token, int32_t* counts,
                            void* ws, size_t ws_bytes, void* stream);
 
+/* etr_moe_forward with stage boundaries marked on the stream, for measurement.
+ *   events: HOST array of ETR_N_STAGE_EVENTS hipEvent_t handles (as void*), created by the
+ *   caller; event i is recorded on `stream` at boundary i:
+ *     0 start | 1 after route | 2 after select | 3 after dispatch | 4 after FFN GEMM-1
+ *     (gate/up + SwiGLU) | 5 after FFN GEMM-2 (down) | 6 after combine
+ * Computes exactly what etr_moe_forward computes, with the same kernels. */
+#define ETR_N_STAGE_EVENTS 7
+etr_status etr_moe_forward_profiled(const etr_config* cfg, const void* x, const float* w_emb,
+                                    const void* w_gate, const void* w_up, const void* w_down, void* out,
+                                    float* score, float* gate_out, int32_t* topk_expert, int32_t* slot_of,
+                                    int32_t* slot_token, int32_t* counts,
+                                    void* ws, size_t ws_bytes, void* stream, void* const* events);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libetr_hip.so")
 
 EXPORTS = ("etr_workspace_bytes", "etr_select_workspace_bytes", "etr_ffn_workspace_bytes", "etr_status_string",
-           "etr_route", "etr_select", "etr_dispatch", "etr_expert_ffn", "etr_combine", "etr_moe_forward")
+           "etr_route", "etr_select", "etr_dispatch", "etr_expert_ffn", "etr_combine", "etr_moe_forward",
+           "etr_moe_forward_profiled")
+N_STAGE_EVENTS = 7
+STAGE_NAMES = ("route", "select", "dispatch", "ffn_gate_up", "ffn_down", "combine")
 
 
 class EtrConfig(ctypes.Structure):
@@ -57,6 +60,8 @@ def load_library():
         "etr_expert_ffn": [cp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "etr_combine": [cp, vp, vp, vp, vp, vp],
         "etr_moe_forward": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "etr_moe_forward_profiled": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
+                                     ctypes.POINTER(ctypes.c_void_p)],
     }
     for name, args in sigs.items():
         getattr(lib, name).restype = ctypes.c_int
@@ -136,6 +141,53 @@ def etr_moe_forward(cfg, x, w_emb, w_gate, w_up, w_down, out, ws, score=None, ga
     _check("etr_moe_forward", load_library().etr_moe_forward(
         ctypes.byref(cfg), _ptr(x), _ptr(w_emb), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), _ptr(score),
         _ptr(gate), _ptr(topk_expert), _ptr(slot_of), _ptr(slot_token), _ptr(counts), _ptr(ws), _nbytes(ws), _stream()))
+
+
+class StageEvents:
+    """ETR_N_STAGE_EVENTS HIP events owned by the caller, for etr_moe_forward_profiled.
+    Created and read through the HIP runtime directly so that they are recorded on exactly
+    the stream the kernels run on."""
+
+    def __init__(self):
+        self._hip = ctypes.CDLL("libamdhip64.so")
+        self._hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self._hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self._hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self._hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.handles = (ctypes.c_void_p * N_STAGE_EVENTS)()
+        for i in range(N_STAGE_EVENTS):
+            ev = ctypes.c_void_p()
+            if self._hip.hipEventCreate(ctypes.byref(ev)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+            self.handles[i] = ev
+
+    def stage_ms(self):
+        """Milliseconds of each stage (after the last event has completed)."""
+        if self._hip.hipEventSynchronize(self.handles[N_STAGE_EVENTS - 1]) != 0:
+            raise RuntimeError("hipEventSynchronize failed")
+        out = []
+        for i in range(N_STAGE_EVENTS - 1):
+            ms = ctypes.c_float()
+            if self._hip.hipEventElapsedTime(ctypes.byref(ms), self.handles[i], self.handles[i + 1]) != 0:
+                raise RuntimeError("hipEventElapsedTime failed")
+            out.append(float(ms.value))
+        return out
+
+    def __del__(self):
+        try:
+            for h in self.handles:
+                if h:
+                    self._hip.hipEventDestroy(h)
+        except Exception:
+            pass
+
+
+def etr_moe_forward_profiled(cfg, x, w_emb, w_gate, w_up, w_down, out, ws, events: StageEvents, score=None, gate=None,
+                             topk_expert=None, slot_of=None, slot_token=None, counts=None):
+    _check("etr_moe_forward_profiled", load_library().etr_moe_forward_profiled(
+        ctypes.byref(cfg), _ptr(x), _ptr(w_emb), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), _ptr(score),
+        _ptr(gate), _ptr(topk_expert), _ptr(slot_of), _ptr(slot_token), _ptr(counts), _ptr(ws), _nbytes(ws), _stream(),
+        events.handles))
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:

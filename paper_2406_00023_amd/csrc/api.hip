@@ -149,10 +149,10 @@ etr_status etr_combine(const etr_config* cfg, const void* yp, const float* gate,
     return ETR_OK;
 }
 
-etr_status etr_moe_forward(const etr_config* cfg, const void* x, const float* w_emb, const void* w_gate,
-                           const void* w_up, const void* w_down, void* out, float* score, float* gate_out,
-                           int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts, void* ws,
-                           size_t ws_bytes, void* stream) {
+static etr_status forward_impl(const etr_config* cfg, const void* x, const float* w_emb, const void* w_gate,
+                               const void* w_up, const void* w_down, void* out, float* score, float* gate_out,
+                               int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts, void* ws,
+                               size_t ws_bytes, void* stream, void* const* events) {
     etr_status s = check_config(cfg);
     if (s != ETR_OK) return s;
     ETR_REQUIRE_PTR(x); ETR_REQUIRE_PTR(w_emb); ETR_REQUIRE_PTR(w_gate); ETR_REQUIRE_PTR(w_up);
@@ -174,12 +174,41 @@ etr_status etr_moe_forward(const etr_config* cfg, const void* x, const float* w_
     const SelectWs sw = select_ws_carve(base + L.select, cfg->T, cfg->E);
     hipStream_t st = static_cast<hipStream_t>(stream);
 
+    auto mark = [&](int i) -> hipError_t {
+        return events ? hipEventRecord(static_cast<hipEvent_t>(events[i]), st) : hipSuccess;
+    };
+    ETR_HIP(mark(0));
     ETR_HIP(launch_route(*cfg, x, w_emb, sc, gt, st));
+    ETR_HIP(mark(1));
     ETR_HIP(launch_select(*cfg, sc, tk, so, stn, cn, sw, st));
+    ETR_HIP(mark(2));
     ETR_HIP(launch_dispatch(*cfg, x, stn, cn, xp, st));
-    ETR_HIP(launch_expert_ffn(*cfg, xp, cn, w_gate, w_up, w_down, yp, hidden, st));
+    ETR_HIP(mark(3));
+    ETR_HIP(launch_expert_ffn(*cfg, xp, cn, w_gate, w_up, w_down, yp, hidden, st,
+                              events ? static_cast<hipEvent_t>(events[4]) : nullptr));
+    ETR_HIP(mark(5));
     ETR_HIP(launch_combine(*cfg, yp, gt, so, out, st));
+    ETR_HIP(mark(6));
     return ETR_OK;
+}
+
+etr_status etr_moe_forward(const etr_config* cfg, const void* x, const float* w_emb, const void* w_gate,
+                           const void* w_up, const void* w_down, void* out, float* score, float* gate_out,
+                           int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts, void* ws,
+                           size_t ws_bytes, void* stream) {
+    return forward_impl(cfg, x, w_emb, w_gate, w_up, w_down, out, score, gate_out, topk_expert, slot_of, slot_token,
+                        counts, ws, ws_bytes, stream, nullptr);
+}
+
+etr_status etr_moe_forward_profiled(const etr_config* cfg, const void* x, const float* w_emb, const void* w_gate,
+                                    const void* w_up, const void* w_down, void* out, float* score, float* gate_out,
+                                    int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts,
+                                    void* ws, size_t ws_bytes, void* stream, void* const* events) {
+    if (!events) return ETR_ERR_NULL;
+    for (int i = 0; i < ETR_N_STAGE_EVENTS; ++i)
+        if (!events[i]) return ETR_ERR_NULL;
+    return forward_impl(cfg, x, w_emb, w_gate, w_up, w_down, out, score, gate_out, topk_expert, slot_of, slot_token,
+                        counts, ws, ws_bytes, stream, events);
 }
 
 }  // extern "C"

@@ -45,7 +45,8 @@ hipError_t launch_combine(const etr_config& c, const void* yp, const float* gate
 // ffn.hip
 size_t ffn_ws_bytes(const etr_config& c);
 hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t* counts, const void* w_gate,
-                             const void* w_up, const void* w_down, void* yp, void* hidden, hipStream_t st);
+                             const void* w_up, const void* w_down, void* yp, void* hidden, hipStream_t st,
+                             hipEvent_t between = nullptr);   // optional event recorded between the two GEMMs
 
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline size_t elt_bytes(int dtype) { return dtype == ETR_F32 ? 4 : 2; }

@@ -305,17 +305,20 @@ size_t ffn_ws_bytes(const etr_config& c) {
 }
 
 hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t* counts, const void* w_gate,
-                             const void* w_up, const void* w_down, void* yp, void* hidden, hipStream_t st) {
+                             const void* w_up, const void* w_down, void* yp, void* hidden, hipStream_t st,
+                             hipEvent_t between) {
     GemmParams g1{xp, w_gate, w_up, hidden, counts, c.E, c.capacity, c.H, c.d, 0, 0};
     GemmParams g2{hidden, w_down, nullptr, yp, counts, c.E, c.capacity, c.d, c.H, 0, 0};
     hipError_t err;
     if (c.dtype == ETR_BF16) {
         err = launch_bf16<128, 64, 64, 2, 2, true, 0>(g1, st);
         if (err != hipSuccess) return err;
+        if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
         return launch_bf16<128, 128, 64, 2, 2, false, 0>(g2, st);
     }
     err = launch_f32<true>(g1, st);
     if (err != hipSuccess) return err;
+    if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
     return launch_f32<false>(g2, st);
 }
 
