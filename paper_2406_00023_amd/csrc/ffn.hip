@@ -26,6 +26,7 @@ struct GemmParams {
     const int32_t* counts;
     int E, capacity, N, K;
     int MT, NT;           // row tiles per expert, column tiles
+    const int32_t* row_index;   // optional [E][capacity]: A row m of expert e is row row_index[e][m] of A
 };
 
 __device__ __forceinline__ uint32_t f2bf(float f) {            // fp32 -> bf16 bits, round to nearest even
@@ -201,6 +202,347 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
 }
 
 // ---------------------------------------------------------------------------------------
+// Pipelined bf16 MFMA grouped GEMM for K % 64 == 0: 256 x 256 staged rows, BK = 64, four
+// waves (one per SIMD), each owning a 128 x 128 slice of accumulators (256 registers).
+//   * global -> LDS copies bypass the registers (global_load_lds_dwordx4): a wave-load
+//     fills 1 KiB = 8 tile rows; the XOR swizzle is applied on the source side (lane l
+//     fetches the chunk that belongs in LDS slot l), two LDS buffers of 64 KiB;
+//   * the copy of tile kt+2 is issued right after the barrier that retires tile kt, so
+//     it has a whole iteration (64 MFMAs per wave) to land;
+//   * MFMA operands are double-buffered in registers: the ds_reads of k-substep s+1 are
+//     issued before the 16 MFMAs of substep s;
+//   * one barrier per iteration.
+// With GLU the 256 staged weight rows are 128 gate rows + 128 up rows of the same output
+// columns and the epilogue is SiLU(gate)*up.  With row_index the A rows are gathered
+// straight from the token matrix (dispatch folded into the load).
+// ---------------------------------------------------------------------------------------
+typedef const __attribute__((address_space(1))) void* global_cptr;
+typedef __attribute__((address_space(3))) void* lds_ptr;
+
+template <bool GLU, int SWZ, bool PROF = false, int WN = 2>
+__global__ __launch_bounds__(128 * WN) void gemm_bf16_pipe_kernel(GemmParams p, long long* prof = nullptr) {
+    constexpr int BM = 256, BR = 256, CPR = 8;
+    constexpr int NW = 2 * WN;                          // waves: 2 row groups x WN column groups
+    constexpr int TB = 4 / (WN / 2);                    // weight fragments per wave and k-substep (4 or 2)
+    constexpr int NCP = 32 / NW;                        // row groups (of 8 rows) each wave copies per operand
+    constexpr int BN = GLU ? 128 : 256;                 // output columns per tile
+    constexpr int STAGE = (BM + BR) * CPR;              // uint4 per LDS buffer (64 KiB)
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    uint4* lds = reinterpret_cast<uint4*>(lds_raw);
+
+    int e, mt, nt;
+    if (!decode_tile(p, e, mt, nt)) return;
+    const int count = min(p.counts[e], p.capacity);
+    const int m0 = mt * BM, n0 = nt * BN;
+    if (m0 >= count) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int r32 = lane & 31, half = lane >> 5;
+    const int KC = p.K / 8, KT = p.K / 64;
+
+    // ---- sources of the asynchronous copies: wave w fills row groups w*NCP .. w*NCP+NCP-1 (8 rows each)
+    const uint4* Abase = reinterpret_cast<const uint4*>(p.A) +
+                         (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KC);
+    const uint4* Bbase = reinterpret_cast<const uint4*>((GLU && wave >= NW / 2) ? p.B1 : p.B0) +
+                         static_cast<size_t>(e) * p.N * KC;
+    uint32_t a_off[NCP], b_off[NCP];
+#pragma unroll
+    for (int i = 0; i < NCP; ++i) {
+        const int r = (wave * NCP + i) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((r >> SWZ) & 7);
+        int m = m0 + r;
+        m = m < count ? m : count - 1;                   // rows past the count replay a valid row; never stored
+        const int row = p.row_index ? p.row_index[static_cast<size_t>(e) * p.capacity + m] : m;
+        a_off[i] = static_cast<uint32_t>(row) * KC + c;
+        int n = n0 + (GLU ? (r & 127) : r);
+        n = n < p.N ? n : p.N - 1;
+        b_off[i] = static_cast<uint32_t>(n) * KC + c;
+    }
+    auto issue_copies = [&](int kt, int buf) {
+        uint4* dstA = lds + buf * STAGE + wave * (NCP * 64);
+        uint4* dstB = dstA + BM * CPR;
+#pragma unroll
+        for (int i = 0; i < NCP; ++i) {
+            __builtin_amdgcn_global_load_lds((global_cptr)(Abase + a_off[i] + kt * CPR), (lds_ptr)(dstA + i * 64), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((global_cptr)(Bbase + b_off[i] + kt * CPR), (lds_ptr)(dstB + i * 64), 16, 0, 0);
+        }
+    };
+
+    // ---- MFMA operand addressing: row offsets are multiples of 32, so the swizzle term
+    // depends on the lane only
+    const int sw = (r32 >> SWZ) & 7;
+    int a_row[4], b_row[TB];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a_row[i] = (wm * 128 + i * 32 + r32) * CPR;
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+        // GLU: first half of the fragments are gate rows, second half the up rows of the same columns
+        const int br = GLU ? ((j / (TB / 2)) * 128 + wn * (16 * TB) + (j % (TB / 2)) * 32) : (wn * (32 * TB) + j * 32);
+        b_row[j] = BM * CPR + (br + r32) * CPR;
+    }
+    int ck[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) ck[ks] = (ks * 2 + half) ^ sw;
+
+    f32x16 acc[4][TB];                                  // [m block][weight block]
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < TB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    bf16x8 fa[2][4], fb[2][TB];
+    auto load_frags = [&](int set, int buf, int ks) {
+        const uint4* base = lds + buf * STAGE + ck[ks];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
+#pragma unroll
+        for (int j = 0; j < TB; ++j) fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
+    };
+    auto mfma_step = [&](int set) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < TB; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
+    };
+
+    // ---- prologue: tiles 0 and 1 in flight, wait for tile 0 only (copies retire in order)
+    issue_copies(0, 0);
+    if (KT > 1) {
+        issue_copies(1, 1);
+        if constexpr (NCP == 8) __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16)
+        else __builtin_amdgcn_s_waitcnt(0x0F78);                      // vmcnt(8)
+    } else {
+        __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0)
+    }
+    __builtin_amdgcn_s_barrier();
+    load_frags(0, 0, 0);
+
+    long long t_wait = 0, t_bar = 0, t_loop0 = 0;
+    if constexpr (PROF) t_loop0 = clock64();
+    for (int kt = 0; kt < KT; ++kt) {
+        const int cur = kt & 1;
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(1, cur, 1);
+        mfma_step(0);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(0, cur, 2);
+        mfma_step(1);
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(1, cur, 3);
+        mfma_step(0);
+        __builtin_amdgcn_sched_barrier(0);
+        // tile kt+1 has landed for every wave and nobody reads buffer `cur` any more
+        long long c0 = 0, c1 = 0;
+        if constexpr (PROF) { c0 = clock64(); __builtin_amdgcn_sched_barrier(0); }
+        __builtin_amdgcn_s_waitcnt(0x0070);             // vmcnt(0) lgkmcnt(0)
+        if constexpr (PROF) { __builtin_amdgcn_sched_barrier(0); c1 = clock64(); __builtin_amdgcn_sched_barrier(0); }
+        __builtin_amdgcn_s_barrier();
+        if constexpr (PROF) {
+            __builtin_amdgcn_sched_barrier(0);
+            long long c2 = clock64();
+            t_wait += c1 - c0; t_bar += c2 - c1;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt + 2 < KT) issue_copies(kt + 2, cur);
+        if (kt + 1 < KT) load_frags(0, cur ^ 1, 0);
+        mfma_step(1);
+    }
+
+    if constexpr (PROF) {
+        if (lane == 0 && prof) {
+            long long* o = prof + (static_cast<size_t>(blockIdx.x) * NW + wave) * 4;
+            o[0] = clock64() - t_loop0; o[1] = t_wait; o[2] = t_bar; o[3] = KT;
+        }
+    }
+    // ---- epilogue: lane holds, per 32x32 block, row m = lane%32 and columns (v/4)*8 + (lane/32)*4 + v%4
+    uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(e) * p.capacity * p.N;
+    constexpr int TO = GLU ? TB / 2 : TB;              // output blocks per wave row
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + wm * 128 + i * 32 + r32;
+        if (m >= count) continue;
+#pragma unroll
+        for (int j = 0; j < TO; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * (32 * TO) + j * 32 + q * 8 + half * 4;
+                if (n >= p.N) continue;
+                float o[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    if constexpr (GLU) o[v] = silu(acc[i][j][q * 4 + v]) * acc[i][TO + j][q * 4 + v];
+                    else o[v] = acc[i][j][q * 4 + v];
+                }
+                uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
+                *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Variant with BK = 32 and a ring of four 32 KiB LDS buffers: the asynchronous copies of
+// tile kt+3 are spread one by one between the MFMAs of iteration kt (a copy issued in a
+// burst blocks the wave's MFMA issue for about 25 cycles each), and they have two full
+// iterations to land: before barrier(kt) a wave waits only until at most 12 copies are
+// outstanding (s_waitcnt vmcnt(12)), i.e. until its share of tile kt+1 is in LDS.
+// ---------------------------------------------------------------------------------------
+template <bool GLU, int WN = 2>
+__global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) {
+    constexpr int BM = 256, BR = 256, CPR = 4, NBUF = 4;
+    constexpr int BN = GLU ? 128 : 256;
+    constexpr int STAGE = (BM + BR) * CPR;              // uint4 per LDS buffer (32 KiB)
+    constexpr int NW = 2 * WN;                          // waves: 2 row groups x WN column groups
+    constexpr int TB = 4 / (WN / 2);                    // weight fragments per wave and k-substep (4 or 2)
+    constexpr int NCP = 16 / NW;                        // row groups (of 16 rows) each wave copies per operand
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    uint4* lds = reinterpret_cast<uint4*>(lds_raw);
+
+    int e, mt, nt;
+    if (!decode_tile(p, e, mt, nt)) return;
+    const int count = min(p.counts[e], p.capacity);
+    const int m0 = mt * BM, n0 = nt * BN;
+    if (m0 >= count) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int r32 = lane & 31, half = lane >> 5;
+    const int KC = p.K / 8, KT = p.K / 32;
+
+    // ---- copy sources: wave w fills row groups w*NCP .. (16 rows x 4 chunks = 1 KiB each)
+    // Addresses are a wave-uniform 64-bit base (scalar registers, advanced by 64 bytes per tile)
+    // plus a per-lane 32-bit byte offset that never changes (the host checks that it fits).
+    const char* Abase = reinterpret_cast<const char*>(p.A) +
+                        (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KC * 16);
+    const char* Bbase = reinterpret_cast<const char*>((GLU && wave >= NW / 2) ? p.B1 : p.B0) +
+                        static_cast<size_t>(e) * p.N * KC * 16;
+    uint32_t off[2 * NCP];                              // first NCP: A groups, then B groups
+#pragma unroll
+    for (int i = 0; i < NCP; ++i) {
+        const int r = (wave * NCP + i) * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((r >> 2) & 3);
+        int m = m0 + r;
+        m = m < count ? m : count - 1;                   // rows past the count replay a valid row; never stored
+        const int row = p.row_index ? p.row_index[static_cast<size_t>(e) * p.capacity + m] : m;
+        off[i] = (static_cast<uint32_t>(row) * KC + c) * 16u;
+        int n = n0 + (GLU ? (r & 127) : r);
+        n = n < p.N ? n : p.N - 1;
+        off[NCP + i] = (static_cast<uint32_t>(n) * KC + c) * 16u;
+    }
+    auto issue_copy = [&](int kt, int j) {
+        uint4* dst = lds + (kt & (NBUF - 1)) * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
+        // re-materialise the tile base as a scalar every time, so that the address stays
+        // "scalar base + 32-bit lane offset" instead of a per-lane 64-bit pointer
+        const uint64_t b64 = reinterpret_cast<uint64_t>(j < NCP ? Abase : Bbase) + static_cast<uint64_t>(kt) * (CPR * 16);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
+        const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
+        const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+        __builtin_amdgcn_global_load_lds((global_cptr)(base + off[j]), (lds_ptr)dst, 16, 0, 0);
+    };
+
+    const int sw = (r32 >> 2) & 3;
+    int a_row[4], b_row[TB];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a_row[i] = (wm * 128 + i * 32 + r32) * CPR;
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+        const int br = GLU ? ((j / (TB / 2)) * 128 + wn * (16 * TB) + (j % (TB / 2)) * 32) : (wn * (32 * TB) + j * 32);
+        b_row[j] = BM * CPR + (br + r32) * CPR;
+    }
+    const int ck0 = half ^ sw, ck1 = (2 + half) ^ sw;
+
+    f32x16 acc[4][TB];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < TB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    bf16x8 fa[2][4], fb[2][TB];
+    auto load_frags = [&](int set, int kt, int ck) {
+        const uint4* base = lds + (kt & (NBUF - 1)) * STAGE + ck;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
+#pragma unroll
+        for (int j = 0; j < TB; ++j) fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
+    };
+    // the MFMAs of one k-substep; with `copy`, NCP copies of tile kt_copy go in between, one per 4 MFMAs
+    auto mfma_step = [&](int set, bool copy, int kt_copy, int j0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int j = 0; j < TB; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
+            if (copy && (i + 1) % (4 / NCP) == 0) issue_copy(kt_copy, j0 + i / (4 / NCP));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ---- prologue: three tiles in flight, wait for the first
+    const int pre = KT < 3 ? KT : 3;
+    for (int t = 0; t < pre; ++t)
+#pragma unroll
+        for (int j = 0; j < 2 * NCP; ++j) issue_copy(t, j);
+    if (pre == 3) __builtin_amdgcn_s_waitcnt(NCP == 4 ? 0x4F70 : 0x0F78);        // vmcnt(4*NCP)
+    else if (pre == 2) __builtin_amdgcn_s_waitcnt(NCP == 4 ? 0x0F78 : 0x0F74);   // vmcnt(2*NCP)
+    else __builtin_amdgcn_s_waitcnt(0x0F70);                                     // vmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    load_frags(0, 0, ck0);
+
+    int kt = 0;
+    for (; kt + 3 < KT; ++kt) {                              // steady state: tile kt+3 is being fetched
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(1, kt, ck1);
+        mfma_step(0, true, kt + 3, 0);
+        __builtin_amdgcn_s_waitcnt(0x0070 | (3 * NCP));      // vmcnt(3*NCP) lgkmcnt(0): tile kt+1 is in LDS
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(0, kt + 1, ck0);
+        mfma_step(1, true, kt + 3, NCP);
+    }
+    for (; kt < KT; ++kt) {                                  // drain: nothing left to fetch
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(1, kt, ck1);
+        mfma_step(0, false, 0, 0);
+        __builtin_amdgcn_s_waitcnt(0x0070);                  // vmcnt(0) lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt + 1 < KT) load_frags(0, kt + 1, ck0);
+        mfma_step(1, false, 0, 0);
+    }
+
+    // ---- epilogue: lane holds, per 32x32 block, row m = lane%32 and columns (v/4)*8 + (lane/32)*4 + v%4
+    uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(e) * p.capacity * p.N;
+    constexpr int TO = GLU ? TB / 2 : TB;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + wm * 128 + i * 32 + r32;
+        if (m >= count) continue;
+#pragma unroll
+        for (int j = 0; j < TO; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * (32 * TO) + j * 32 + q * 8 + half * 4;
+                if (n >= p.N) continue;
+                float o[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    if constexpr (GLU) o[v] = silu(acc[i][j][q * 4 + v]) * acc[i][TO + j][q * 4 + v];
+                    else o[v] = acc[i][j][q * 4 + v];
+                }
+                uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
+                *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // fp32 grouped GEMM, 64x64 tile, 4x4 outputs per thread, plain FMA
 // ---------------------------------------------------------------------------------------
 template <bool GLU>
@@ -288,6 +630,36 @@ hipError_t launch_bf16(GemmParams p, hipStream_t st) {
     return hipGetLastError();
 }
 
+template <bool GLU, int SWZ, int WN = 2>
+hipError_t launch_bf16_pipe(GemmParams p, hipStream_t st) {
+    constexpr size_t lds = 2ull * 512 * 64 * 2;        // two buffers of 256 + 256 rows x 64 bf16
+    p.MT = (p.capacity + 255) / 256;
+    p.NT = (p.N + (GLU ? 128 : 256) - 1) / (GLU ? 128 : 256);
+    const long long bands = static_cast<long long>(p.E) * p.NT;
+    const long long blocks = (bands + 7) / 8 * 8 * p.MT;
+    auto kern = gemm_bf16_pipe_kernel<GLU, SWZ, false, WN>;
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(blocks)), dim3(128 * WN), lds, st, p, static_cast<long long*>(nullptr));
+    return hipGetLastError();
+}
+
+template <bool GLU, int WN = 2>
+hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
+    constexpr size_t lds = 4ull * 512 * 32 * 2;        // four buffers of 256 + 256 rows x 32 bf16
+    p.MT = (p.capacity + 255) / 256;
+    p.NT = (p.N + (GLU ? 128 : 256) - 1) / (GLU ? 128 : 256);
+    const long long bands = static_cast<long long>(p.E) * p.NT;
+    const long long blocks = (bands + 7) / 8 * 8 * p.MT;
+    auto kern = gemm_bf16_ring_kernel<GLU, WN>;
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(blocks)), dim3(128 * WN), lds, st, p);
+    return hipGetLastError();
+}
+
 template <bool GLU>
 hipError_t launch_f32(GemmParams p, hipStream_t st) {
     p.MT = (p.capacity + 63) / 64;
@@ -304,17 +676,25 @@ size_t ffn_ws_bytes(const etr_config& c) {
     return align_up(static_cast<size_t>(c.E) * c.capacity * c.H * elt_bytes(c.dtype));
 }
 
+// The pipelined kernels need K % 64 == 0 (copies cannot zero-fill a K tail) and 32-bit byte
+// offsets inside one operand; everything else takes the register-staged kernel.
+static bool pipelined_ok(const GemmParams& g, size_t a_rows) {
+    const size_t row_bytes = static_cast<size_t>(g.K) * 2;
+    return g.K % 64 == 0 && a_rows * row_bytes < (1ull << 32) && static_cast<size_t>(g.N) * row_bytes < (1ull << 32);
+}
+
 hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t* counts, const void* w_gate,
                              const void* w_up, const void* w_down, void* yp, void* hidden, hipStream_t st,
                              hipEvent_t between) {
-    GemmParams g1{xp, w_gate, w_up, hidden, counts, c.E, c.capacity, c.H, c.d, 0, 0};
-    GemmParams g2{hidden, w_down, nullptr, yp, counts, c.E, c.capacity, c.d, c.H, 0, 0};
+    GemmParams g1{xp, w_gate, w_up, hidden, counts, c.E, c.capacity, c.H, c.d, 0, 0, nullptr};
+    GemmParams g2{hidden, w_down, nullptr, yp, counts, c.E, c.capacity, c.d, c.H, 0, 0, nullptr};
     hipError_t err;
     if (c.dtype == ETR_BF16) {
-        err = launch_bf16<128, 64, 64, 2, 2, true, 0>(g1, st);
+        err = pipelined_ok(g1, c.capacity) ? launch_bf16_ring<true, 4>(g1, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g1, st);
         if (err != hipSuccess) return err;
         if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
-        return launch_bf16<128, 128, 64, 2, 2, false, 0>(g2, st);
+        return pipelined_ok(g2, c.capacity) ? launch_bf16_ring<false, 4>(g2, st)
+                                            : launch_bf16<128, 128, 64, 2, 2, false, 1>(g2, st);
     }
     err = launch_f32<true>(g1, st);
     if (err != hipSuccess) return err;

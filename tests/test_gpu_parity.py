@@ -167,7 +167,10 @@ def test_select_external_scores(H, oracle, T, E, k, C, levels):
     (I.DT_BF16, 3, 300, 264, 328, [300, 0, 37]),       # K not a multiple of the k-tile, N tails in both GEMMs
     (I.DT_BF16, 2, 130, 512, 128, [129, 1]),
     (I.DT_F32, 4, 70, 72, 40, [70, 3, 0, 64]),
-    (I.DT_BF16, 1, 513, 1024, 704, [513]),
+    (I.DT_BF16, 1, 513, 1024, 704, [513]),            # pipelined kernels: row tail of 1, column tail in GEMM-1
+    (I.DT_BF16, 2, 40, 64, 64, [40, 7]),               # pipelined kernels with only two k-tiles
+    (I.DT_BF16, 1, 300, 128, 192, [300]),              # four and six k-tiles: prologue meets drain
+    (I.DT_BF16, 3, 600, 2048, 512, [600, 256, 257]),   # counts on and just past a row-tile boundary
 ])
 def test_expert_ffn(H, oracle, dtype, E, C, d, H_, counts):
     _say(f"case ffn dtype={dtype} E={E} C={C} d={d} H={H_} counts={counts}")
