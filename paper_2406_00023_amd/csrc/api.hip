@@ -182,10 +182,13 @@ static etr_status forward_impl(const etr_config* cfg, const void* x, const float
     ETR_HIP(mark(1));
     ETR_HIP(launch_select(*cfg, sc, tk, so, stn, cn, sw, st));
     ETR_HIP(mark(2));
-    ETR_HIP(launch_dispatch(*cfg, x, stn, cn, xp, st));
+    // bf16 with the pipelined GEMM: the rearrangement is folded into GEMM-1's operand load
+    // (rows are fetched through slot_token), so no permuted copy of the tokens is written
+    const bool gather = ffn_can_gather(*cfg);
+    if (!gather) ETR_HIP(launch_dispatch(*cfg, x, stn, cn, xp, st));
     ETR_HIP(mark(3));
-    ETR_HIP(launch_expert_ffn(*cfg, xp, cn, w_gate, w_up, w_down, yp, hidden, st,
-                              events ? static_cast<hipEvent_t>(events[4]) : nullptr));
+    ETR_HIP(launch_expert_ffn(*cfg, gather ? x : xp, cn, w_gate, w_up, w_down, yp, hidden, st,
+                              events ? static_cast<hipEvent_t>(events[4]) : nullptr, gather ? stn : nullptr));
     ETR_HIP(mark(5));
     ETR_HIP(launch_combine(*cfg, yp, gt, so, out, st));
     ETR_HIP(mark(6));

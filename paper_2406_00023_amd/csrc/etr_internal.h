@@ -46,7 +46,11 @@ hipError_t launch_combine(const etr_config& c, const void* yp, const float* gate
 size_t ffn_ws_bytes(const etr_config& c);
 hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t* counts, const void* w_gate,
                              const void* w_up, const void* w_down, void* yp, void* hidden, hipStream_t st,
-                             hipEvent_t between = nullptr);   // optional event recorded between the two GEMMs
+                             hipEvent_t between = nullptr,    // optional event recorded between the two GEMMs
+                             const int32_t* gather_rows = nullptr);   // see ffn_can_gather
+// True when GEMM-1 can read its rows straight from the token matrix through slot_token
+// (then xp is never materialised by the fused forward).
+bool ffn_can_gather(const etr_config& c);
 
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline size_t elt_bytes(int dtype) { return dtype == ETR_F32 ? 4 : 2; }

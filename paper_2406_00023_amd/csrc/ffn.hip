@@ -27,6 +27,8 @@ struct GemmParams {
     int E, capacity, N, K;
     int MT, NT;           // row tiles per expert, column tiles
     const int32_t* row_index;   // optional [E][capacity]: A row m of expert e is row row_index[e][m] of A
+    int k_stagger;              // pipelined kernels: workgroup j of an XCD starts its K loop (j % 32) * k_stagger tiles in
+    int a_rows;                 // rows of A that row_index may name (indices are clamped into [0, a_rows))
 };
 
 __device__ __forceinline__ uint32_t f2bf(float f) {            // fp32 -> bf16 bits, round to nearest even
@@ -41,9 +43,10 @@ __device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a));
 // round-robin to the 8 XCDs, each with its own L2: a "band" = all row tiles of one
 // (expert, column tile) shares one weight tile, so a whole band goes to one XCD, row tile
 // fastest, and the weight tile is fetched from HBM once.
-__device__ __forceinline__ bool decode_tile(const GemmParams& p, int& e, int& mt, int& nt) {
+__device__ __forceinline__ bool decode_tile(const GemmParams& p, int& e, int& mt, int& nt, int* seq = nullptr) {
     const int pid = blockIdx.x;
     const int xcd = pid & 7, j = pid >> 3;
+    if (seq) *seq = j;
     const int band = (j / p.MT) * 8 + xcd;
     mt = j % p.MT;
     if (band >= p.E * p.NT) return false;
@@ -216,6 +219,14 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
 // columns and the epilogue is SiLU(gate)*up.  With row_index the A rows are gathered
 // straight from the token matrix (dispatch folded into the load).
 // ---------------------------------------------------------------------------------------
+// Workgroup barrier that the compiler may not move memory accesses across (no instructions of its own
+// besides s_barrier; the waits that make data visible are written out next to each use).
+__device__ __forceinline__ void wg_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 typedef const __attribute__((address_space(1))) void* global_cptr;
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
@@ -254,7 +265,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_pipe_kernel(GemmParams p, 
         const int c = (lane & 7) ^ ((r >> SWZ) & 7);
         int m = m0 + r;
         m = m < count ? m : count - 1;                   // rows past the count replay a valid row; never stored
-        const int row = p.row_index ? p.row_index[static_cast<size_t>(e) * p.capacity + m] : m;
+        const int row = p.row_index ? min(max(p.row_index[static_cast<size_t>(e) * p.capacity + m], 0), p.a_rows - 1) : m;
         a_off[i] = static_cast<uint32_t>(row) * KC + c;
         int n = n0 + (GLU ? (r & 127) : r);
         n = n < p.N ? n : p.N - 1;
@@ -402,8 +413,8 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     uint4* lds = reinterpret_cast<uint4*>(lds_raw);
 
-    int e, mt, nt;
-    if (!decode_tile(p, e, mt, nt)) return;
+    int e, mt, nt, seq;
+    if (!decode_tile(p, e, mt, nt, &seq)) return;
     const int count = min(p.counts[e], p.capacity);
     const int m0 = mt * BM, n0 = nt * BN;
     if (m0 >= count) return;
@@ -413,6 +424,9 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
     const int wm = wave / WN, wn = wave % WN;
     const int r32 = lane & 31, half = lane >> 5;
     const int KC = p.K / 8, KT = p.K / 32;
+    // staggered start of the K loop (see the ping-pong kernel): turns simultaneous misses on shared
+    // tiles into one miss and later L2 hits; accumulation order depends on the tile index only
+    const int kt0 = static_cast<int>((static_cast<long long>(seq & 31) * p.k_stagger) % KT);
 
     // ---- copy sources: wave w fills row groups w*NCP .. (16 rows x 4 chunks = 1 KiB each)
     // Addresses are a wave-uniform 64-bit base (scalar registers, advanced by 64 bytes per tile)
@@ -428,7 +442,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
         const int c = (lane & 3) ^ ((r >> 2) & 3);
         int m = m0 + r;
         m = m < count ? m : count - 1;                   // rows past the count replay a valid row; never stored
-        const int row = p.row_index ? p.row_index[static_cast<size_t>(e) * p.capacity + m] : m;
+        const int row = p.row_index ? min(max(p.row_index[static_cast<size_t>(e) * p.capacity + m], 0), p.a_rows - 1) : m;
         off[i] = (static_cast<uint32_t>(row) * KC + c) * 16u;
         int n = n0 + (GLU ? (r & 127) : r);
         n = n < p.N ? n : p.N - 1;
@@ -438,7 +452,9 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
         uint4* dst = lds + (kt & (NBUF - 1)) * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
         // re-materialise the tile base as a scalar every time, so that the address stays
         // "scalar base + 32-bit lane offset" instead of a per-lane 64-bit pointer
-        const uint64_t b64 = reinterpret_cast<uint64_t>(j < NCP ? Abase : Bbase) + static_cast<uint64_t>(kt) * (CPR * 16);
+        int tk = kt + kt0;
+        tk = tk >= KT ? tk - KT : tk;
+        const uint64_t b64 = reinterpret_cast<uint64_t>(j < NCP ? Abase : Bbase) + static_cast<uint64_t>(tk) * (CPR * 16);
         const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
         const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
         const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
@@ -535,6 +551,176 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
                 for (int v = 0; v < 4; ++v) {
                     if constexpr (GLU) o[v] = silu(acc[i][j][q * 4 + v]) * acc[i][TO + j][q * 4 + v];
                     else o[v] = acc[i][j][q * 4 + v];
+                }
+                uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
+                *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Ping-pong variant: eight waves, two per SIMD.  A wave alternates between a MEMORY slot
+// (ds_read all MFMA operands of its next k-tile, issue its share of the asynchronous copies
+// of tile t+3) and a COMPUTE slot (16 MFMAs on a 128 x 64 slice).  The two waves of a SIMD
+// are one slot apart, so while one is held up issuing memory instructions the other feeds
+// the MFMA unit.  Every slot ends with a workgroup barrier; group 1 takes one extra barrier
+// before its loop and group 0 one after, which creates the offset with equal barrier counts.
+//   BK = 32, ring of four 32 KiB LDS buffers; tile t lives in buffer t % 4; it is read by
+//   group 0 in slot 2t and by group 1 in slot 2t+1, and overwritten by tile t+4 whose copies
+//   are issued in slots 2t+2 / 2t+3.  A wave makes sure its own copies of tile t+1 have
+//   landed (s_waitcnt vmcnt) before the barrier that ends slot 2t+1.
+// ---------------------------------------------------------------------------------------
+template <bool GLU, int GROUPING, int DEBUG_SKIP = 0>   // DEBUG_SKIP 1: no MFMAs, 2: no copies after the prologue (measurement only)
+__global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmParams p) {
+    constexpr int BM = 256, BR = 256, CPR = 4, NBUF = 4;
+    constexpr int BN = GLU ? 128 : 256;
+    constexpr int STAGE = (BM + BR) * CPR;              // uint4 per LDS buffer (32 KiB)
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    uint4* lds = reinterpret_cast<uint4*>(lds_raw);
+
+    int e, mt, nt, seq;
+    if (!decode_tile(p, e, mt, nt, &seq)) return;
+    const int count = min(p.counts[e], p.capacity);
+    const int m0 = mt * BM, n0 = nt * BN;
+    if (m0 >= count) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = GROUPING == 0 ? (wave >> 2) : (wave & 1);      // ping-pong group
+    const int q = GROUPING == 0 ? (wave & 3) : (wave >> 1);        // wave within the group
+    const int wm = q >> 1, wn = q & 1;
+    const int r32 = lane & 31, half = lane >> 5;
+    const int KC = p.K / 8, KT = p.K / 32;
+    // The ~32 workgroups that run together on an XCD share weight tiles (same band) and token tiles
+    // (same row tile).  Starting each one at a different k-tile (and wrapping around) makes one of
+    // them fetch a line from HBM while the others find it in L2 later, instead of all of them
+    // waiting on the same fill.  The order of the fp32 accumulation then depends on the tile index
+    // only, so results stay bit-reproducible.
+    const int kt0 = static_cast<int>((static_cast<long long>(seq & 31) * p.k_stagger) % KT);
+
+    // ---- copy sources: wave w fills A row groups 2w, 2w+1 and weight row groups 2w, 2w+1
+    // (16 rows x 4 chunks = 1 KiB each); address = scalar base + constant 32-bit lane offset
+    const char* Abase = reinterpret_cast<const char*>(p.A) +
+                        (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KC * 16);
+    const char* Bbase = reinterpret_cast<const char*>((GLU && wave >= 4) ? p.B1 : p.B0) +
+                        static_cast<size_t>(e) * p.N * KC * 16;
+    uint32_t off[4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int r = (wave * 2 + i) * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((r >> 2) & 3);
+        int m = m0 + r;
+        m = m < count ? m : count - 1;                   // rows past the count replay a valid row; never stored
+        const int row = p.row_index ? min(max(p.row_index[static_cast<size_t>(e) * p.capacity + m], 0), p.a_rows - 1) : m;
+        off[i] = (static_cast<uint32_t>(row) * KC + c) * 16u;
+        int n = n0 + (GLU ? (r & 127) : r);
+        n = n < p.N ? n : p.N - 1;
+        off[2 + i] = (static_cast<uint32_t>(n) * KC + c) * 16u;
+    }
+    auto issue_copies = [&](int t) {
+        uint4* dst = lds + (t & (NBUF - 1)) * STAGE + wave * 128;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int tk = t + kt0;
+            tk = tk >= KT ? tk - KT : tk;
+            const char* src = (j < 2 ? Abase : Bbase) + static_cast<size_t>(tk) * (CPR * 16) + off[j];
+            __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst + (j >> 1) * (BM * CPR) + (j & 1) * 64), 16, 0, 0);
+        }
+    };
+
+    // ---- MFMA operand addressing
+    const int sw = (r32 >> 2) & 3;
+    int a_row[4], b_row[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a_row[i] = (wm * 128 + i * 32 + r32) * CPR;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        // GLU: fragment 0 = gate rows, fragment 1 = up rows of the same 32 output columns
+        const int br = GLU ? (j * 128 + grp * 64 + wn * 32) : (grp * 128 + wn * 64 + j * 32);
+        b_row[j] = BM * CPR + (br + r32) * CPR;
+    }
+    const int ck[2] = {half ^ sw, (2 + half) ^ sw};
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    bf16x8 fa[2][4], fb[2][2];
+    auto memory_slot = [&](int t) {
+        const uint4* base = lds + (t & (NBUF - 1)) * STAGE;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) fa[ks][i] = __builtin_bit_cast(bf16x8, base[a_row[i] + ck[ks]]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) fb[ks][j] = __builtin_bit_cast(bf16x8, base[b_row[j] + ck[ks]]);
+        }
+        if (DEBUG_SKIP != 2 && t >= 1 && t + 3 < KT) issue_copies(t + 3);
+    };
+    auto compute_slot = [&]() {
+        if (DEBUG_SKIP == 1) return;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks][j], fa[ks][i], acc[i][j], 0, 0, 0);
+    };
+    // own copies of tile t+1 have landed: at most the copies of tiles t+2 and t+3 may be outstanding
+    auto wait_tile_after = [&](int t) {
+        const int later = KT - 2 - t;                    // tiles after t+1 that have been issued (capped at 2)
+        if (later >= 2) __builtin_amdgcn_s_waitcnt(0x0F78);        // vmcnt(8)
+        else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
+        else __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
+    };
+
+    // ---- prologue: up to four tiles in flight; tile 0 must be in LDS for everybody
+    const int pre = KT < 4 ? KT : 4;
+    for (int t = 0; t < pre; ++t) issue_copies(t);
+    if (pre == 4) __builtin_amdgcn_s_waitcnt(0x0F7C);        // vmcnt(12)
+    else if (pre == 3) __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8)
+    else if (pre == 2) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
+    else __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0)
+    wg_barrier();
+
+    if (grp == 1) wg_barrier();              // one slot behind group 0
+    for (int t = 0; t < KT; ++t) {
+        __builtin_amdgcn_sched_barrier(0);
+        memory_slot(t);
+        if (grp == 1) wait_tile_after(t);
+        __builtin_amdgcn_s_waitcnt(0xC07F);                  // lgkmcnt(0): operands are in registers, buffer may be recycled
+        wg_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        compute_slot();
+        __builtin_amdgcn_sched_barrier(0);
+        if (grp == 0) wait_tile_after(t);
+        wg_barrier();
+    }
+    if (grp == 0) wg_barrier();
+
+    // ---- epilogue: lane holds, per 32x32 block, row m = lane%32 and columns (v/4)*8 + (lane/32)*4 + v%4
+    uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(e) * p.capacity * p.N;
+    constexpr int TO = GLU ? 1 : 2;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + wm * 128 + i * 32 + r32;
+        if (m >= count) continue;
+#pragma unroll
+        for (int j = 0; j < TO; ++j)
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                const int n = n0 + (GLU ? grp * 64 + wn * 32 : grp * 128 + wn * 64 + j * 32) + qq * 8 + half * 4;
+                if (n >= p.N) continue;
+                float o[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    if constexpr (GLU) o[v] = silu(acc[i][0][qq * 4 + v]) * acc[i][1][qq * 4 + v];
+                    else o[v] = acc[i][j][qq * 4 + v];
                 }
                 uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
                 *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
@@ -660,6 +846,21 @@ hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
     return hipGetLastError();
 }
 
+template <bool GLU, int GROUPING, int DEBUG_SKIP = 0>
+hipError_t launch_bf16_pp(GemmParams p, hipStream_t st) {
+    constexpr size_t lds = 4ull * 512 * 32 * 2;
+    p.MT = (p.capacity + 255) / 256;
+    p.NT = (p.N + (GLU ? 128 : 256) - 1) / (GLU ? 128 : 256);
+    const long long bands = static_cast<long long>(p.E) * p.NT;
+    const long long blocks = (bands + 7) / 8 * 8 * p.MT;
+    auto kern = gemm_bf16_pp_kernel<GLU, GROUPING, DEBUG_SKIP>;
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(blocks)), dim3(512), lds, st, p);
+    return hipGetLastError();
+}
+
 template <bool GLU>
 hipError_t launch_f32(GemmParams p, hipStream_t st) {
     p.MT = (p.capacity + 63) / 64;
@@ -683,19 +884,30 @@ static bool pipelined_ok(const GemmParams& g, size_t a_rows) {
     return g.K % 64 == 0 && a_rows * row_bytes < (1ull << 32) && static_cast<size_t>(g.N) * row_bytes < (1ull << 32);
 }
 
+bool ffn_can_gather(const etr_config& c) {
+    if (c.dtype != ETR_BF16) return false;
+    GemmParams g1{nullptr, nullptr, nullptr, nullptr, nullptr, c.E, c.capacity, c.H, c.d, 0, 0, nullptr, 0, c.T};
+    return pipelined_ok(g1, static_cast<size_t>(c.T));
+}
+
 hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t* counts, const void* w_gate,
                              const void* w_up, const void* w_down, void* yp, void* hidden, hipStream_t st,
-                             hipEvent_t between) {
-    GemmParams g1{xp, w_gate, w_up, hidden, counts, c.E, c.capacity, c.H, c.d, 0, 0, nullptr};
-    GemmParams g2{hidden, w_down, nullptr, yp, counts, c.E, c.capacity, c.d, c.H, 0, 0, nullptr};
+                             hipEvent_t between, const int32_t* gather_rows) {
+    // with gather_rows (= slot_token) xp is the token matrix x itself and GEMM-1 fetches row
+    // gather_rows[e][s] of it: the rearrangement is folded into the operand load
+    GemmParams g1{xp, w_gate, w_up, hidden, counts, c.E, c.capacity, c.H, c.d, 0, 0, gather_rows, 0, c.T};
+    GemmParams g2{hidden, w_down, nullptr, yp, counts, c.E, c.capacity, c.d, c.H, 0, 0, nullptr, 0, c.capacity};
     hipError_t err;
     if (c.dtype == ETR_BF16) {
-        err = pipelined_ok(g1, c.capacity) ? launch_bf16_ring<true, 4>(g1, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g1, st);
+        if (gather_rows && !ffn_can_gather(c)) return hipErrorInvalidValue;
+        const bool pipe1 = pipelined_ok(g1, gather_rows ? static_cast<size_t>(c.T) : static_cast<size_t>(c.capacity));
+        err = pipe1 ? launch_bf16_ring<true, 4>(g1, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g1, st);
         if (err != hipSuccess) return err;
         if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
         return pipelined_ok(g2, c.capacity) ? launch_bf16_ring<false, 4>(g2, st)
                                             : launch_bf16<128, 128, 64, 2, 2, false, 1>(g2, st);
     }
+    if (gather_rows) return hipErrorInvalidValue;
     err = launch_f32<true>(g1, st);
     if (err != hipSuccess) return err;
     if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
