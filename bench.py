@@ -102,6 +102,35 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    # the HBM-bound stages once more on their own (the fused call folds the rearrangement into GEMM-1
+    # and the stage events include launch gaps): plain hipEvent timing of back-to-back stage calls
+    def time_stage(fn, reps=20):
+        ev = B.StageEvents()
+        fn(); torch.cuda.synchronize()
+        B.record_event(ev, 0)
+        for _ in range(reps):
+            fn()
+        B.record_event(ev, 1)
+        torch.cuda.synchronize()
+        return B.elapsed_ms(ev, 0, 1) / reps
+
+    E, C, T, d = shape.E, cfg.capacity, shape.T, shape.d
+    score = torch.empty(T, E, dtype=torch.float32, device=dev)
+    gate = torch.empty(T, E, dtype=torch.float32, device=dev)
+    slot_of = torch.empty(T, E, dtype=torch.int32, device=dev)
+    slot_token = torch.empty(E, C, dtype=torch.int32, device=dev)
+    topk = torch.empty(T, max(shape.k, 1), dtype=torch.int32, device=dev)
+    xp = torch.empty(E, C, d, dtype=shape.torch_dtype, device=dev)
+    sws = B.alloc_workspace(B.etr_select_workspace_bytes(cfg), dev)
+    B.etr_route(cfg, t["x"], t["w_emb"], score, gate)
+    B.etr_select(cfg, score, topk, slot_of, slot_token, counts, sws)
+    alone = {
+        "route": time_stage(lambda: B.etr_route(cfg, t["x"], t["w_emb"], score, gate)),
+        "select": time_stage(lambda: B.etr_select(cfg, score, topk, slot_of, slot_token, counts, sws)),
+        "dispatch": time_stage(lambda: B.etr_dispatch(cfg, t["x"], slot_token, counts, xp)),
+        "combine": time_stage(lambda: B.etr_combine(cfg, xp, gate, slot_of, out)),
+    }
+
     ms_per_step = 1e3 * elapsed / args.steps
     stage = [0.0] * (B.N_STAGE_EVENTS - 1)
     for ev in events:
@@ -122,7 +151,9 @@ def main():
         "dispatch": rows * (2 * shape.d * elt + 4),
         "combine": rows * shape.d * elt + shape.T * shape.d * elt + TE * 8,
     }
-    hbm = {k: round(v / (stages[k] * 1e-3) / 1e9, 1) for k, v in bytes_alg.items() if stages[k] > 0}
+    hbm = {k: {"us": round(alone[k] * 1e3, 2), "GBs": round(v / (alone[k] * 1e-3) / 1e9, 1),
+               "frac_of_8TBs": round(v / (alone[k] * 1e-3) / 1e9 / PEAK_HBM_GBS, 3)} for k, v in bytes_alg.items()}
+    hbm["select"] = {"us": round(alone["select"] * 1e3, 2)}
     flops_gemm2 = 2.0 * rows * shape.d * shape.H
     res = {
         "metric": "MoE-layer tokens/sec on 1 MI355X",
@@ -142,7 +173,7 @@ def main():
                      "bound": "mfma" if shape.dtype == I.DT_BF16 else "alu",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None},
         "stage_ms": stages,
-        "stage_hbm_GBs": hbm,
+        "stage_alone": hbm,
         "ffn_down_TFLOPs": flops_gemm2 / (stage[4] * 1e-3) / 1e12 if stage[4] > 0 else None,
     }
     if not args.no_cpu_baseline:

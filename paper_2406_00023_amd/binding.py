@@ -182,6 +182,23 @@ class StageEvents:
             pass
 
 
+def record_event(events: StageEvents, i: int):
+    """Record event i of `events` on torch's current stream (measurement helper)."""
+    hip = events._hip
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    if hip.hipEventRecord(events.handles[i], _stream()) != 0:
+        raise RuntimeError("hipEventRecord failed")
+
+
+def elapsed_ms(events: StageEvents, i: int, j: int) -> float:
+    ms = ctypes.c_float()
+    if events._hip.hipEventSynchronize(events.handles[j]) != 0:
+        raise RuntimeError("hipEventSynchronize failed")
+    if events._hip.hipEventElapsedTime(ctypes.byref(ms), events.handles[i], events.handles[j]) != 0:
+        raise RuntimeError("hipEventElapsedTime failed")
+    return float(ms.value)
+
+
 def etr_moe_forward_profiled(cfg, x, w_emb, w_gate, w_up, w_down, out, ws, events: StageEvents, score=None, gate=None,
                              topk_expert=None, slot_of=None, slot_token=None, counts=None):
     _check("etr_moe_forward_profiled", load_library().etr_moe_forward_profiled(

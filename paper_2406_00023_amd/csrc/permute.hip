@@ -12,32 +12,35 @@ constexpr int kRowThreads = 256;
 constexpr int kRowWaves = kRowThreads / kWave;
 
 // xp[e][s][:] = x[slot_token[e][s]][:]  for s < counts[e]
+// A wave walks rows r, r + stride, ...; the loads of a row are all in flight before its first
+// store, and the index of the next row is fetched early.
 __global__ __launch_bounds__(kRowThreads) void dispatch_kernel(const uint4* __restrict__ x,
                                                                const int32_t* __restrict__ slot_token,
                                                                const int32_t* __restrict__ counts,
                                                                uint4* __restrict__ xp, int T, int capacity,
                                                                long long rows, int row_vecs) {
     const int lane = threadIdx.x & (kWave - 1);
-    const long long r = static_cast<long long>(blockIdx.x) * kRowWaves + threadIdx.x / kWave;
-    if (r >= rows) return;
-    const int e = static_cast<int>(r / capacity), s = static_cast<int>(r - static_cast<long long>(e) * capacity);
-    if (s >= counts[e]) return;
-    const int t = slot_token[r];
-    if (t < 0 || t >= T) return;                       // a table that does not belong to this x: skip the row
-    const uint4* src = x + static_cast<size_t>(t) * row_vecs;
-    uint4* dst = xp + static_cast<size_t>(r) * row_vecs;
+    const long long stride = static_cast<long long>(gridDim.x) * kRowWaves;
     constexpr int U = 8;
-    for (int c0 = 0; c0 < row_vecs; c0 += kWave * U) {
-        uint4 v[U];
+    for (long long r = static_cast<long long>(blockIdx.x) * kRowWaves + threadIdx.x / kWave; r < rows; r += stride) {
+        const int e = static_cast<int>(r / capacity), s = static_cast<int>(r - static_cast<long long>(e) * capacity);
+        if (s >= counts[e]) continue;
+        const int t = slot_token[r];
+        if (t < 0 || t >= T) continue;                  // a table that does not belong to this x: skip the row
+        const uint4* src = x + static_cast<size_t>(t) * row_vecs;
+        uint4* dst = xp + static_cast<size_t>(r) * row_vecs;
+        for (int c0 = 0; c0 < row_vecs; c0 += kWave * U) {
+            uint4 v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int c = c0 + u * kWave + lane;
-            if (c < row_vecs) v[u] = src[c];
-        }
+            for (int u = 0; u < U; ++u) {
+                int c = c0 + u * kWave + lane;
+                if (c < row_vecs) v[u] = src[c];
+            }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int c = c0 + u * kWave + lane;
-            if (c < row_vecs) dst[c] = v[u];
+            for (int u = 0; u < U; ++u) {
+                int c = c0 + u * kWave + lane;
+                if (c < row_vecs) dst[c] = v[u];
+            }
         }
     }
 }
@@ -135,7 +138,8 @@ hipError_t launch_dispatch(const etr_config& c, const void* x, const int32_t* sl
                            void* xp, hipStream_t st) {
     const long long rows = static_cast<long long>(c.E) * c.capacity;
     const int row_vecs = static_cast<int>(static_cast<size_t>(c.d) * elt_bytes(c.dtype) / 16);
-    const long long blocks = (rows + kRowWaves - 1) / kRowWaves;
+    long long blocks = (rows + kRowWaves - 1) / kRowWaves;
+    if (blocks > 256 * 16) blocks = 256 * 16;          // 16 workgroups per CU, each wave walks several rows
     hipLaunchKernelGGL(dispatch_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kRowThreads), 0, st,
                        static_cast<const uint4*>(x), slot_token, counts, static_cast<uint4*>(xp), c.T, c.capacity,
                        rows, row_vecs);

@@ -15,6 +15,14 @@ constexpr int kRouteThreads = 256;
 constexpr int kRouteWaves = kRouteThreads / kWave;
 constexpr int kUnroll = 8;
 
+// g lives in a per-wave LDS region: a wave's LDS instructions execute in issue order, so ordering
+// them in the instruction stream is all that is needed (no workgroup barrier, no waiting)
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
@@ -24,12 +32,15 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <bool BF16>
 struct Chunk;   // one 16-byte piece of a token row
 
+__device__ __forceinline__ uint4 load_chunk(const void* row, int c, bool ok) {
+    return ok ? reinterpret_cast<const uint4*>(row)[c] : make_uint4(0u, 0u, 0u, 0u);
+}
+
 template <>
 struct Chunk<false> {
     static constexpr int kVec = 4;
-    __device__ static void load(const void* row, int c, bool ok, float* f) {
-        float4 v = ok ? reinterpret_cast<const float4*>(row)[c] : make_float4(0.f, 0.f, 0.f, 0.f);
-        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    __device__ static void unpack(const uint4& v, float* f) {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
     }
     __device__ static float scalar(const void* row, int i) { return reinterpret_cast<const float*>(row)[i]; }
 };
@@ -37,8 +48,7 @@ struct Chunk<false> {
 template <>
 struct Chunk<true> {
     static constexpr int kVec = 8;
-    __device__ static void load(const void* row, int c, bool ok, float* f) {
-        uint4 v = ok ? reinterpret_cast<const uint4*>(row)[c] : make_uint4(0u, 0u, 0u, 0u);
+    __device__ static void unpack(const uint4& v, float* f) {
         f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xFFFF0000u);
         f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xFFFF0000u);
         f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xFFFF0000u);
@@ -57,7 +67,9 @@ struct RouteParams {
     int R;          // 16-byte chunks per pooling group when that is a power of two <= 64, else 0
 };
 
-template <bool BF16>
+// FAST: the whole row fits one pass of kUnroll loads per lane and pools with lane shuffles;
+// otherwise the general walk (several passes, or one lane per pooled feature).
+template <bool BF16, bool FAST>
 __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteParams p, const void* __restrict__ x,
                                                               const float* __restrict__ w_emb,
                                                               float* __restrict__ score, float* __restrict__ gate) {
@@ -69,6 +81,25 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteParams p, con
     float* gs = wn + 64;                               // [waves][P]
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int nchunks = p.d / V;
+    const size_t row_bytes = static_cast<size_t>(p.d) * (BF16 ? 2 : 4);
+    // one pass of kUnroll 16-byte loads per lane covers d <= 64 * kUnroll * V elements (4096 bf16):
+    // then the row of the NEXT token is fetched while the current one is reduced
+    constexpr bool one_pass = FAST;
+    uint4 raw[FAST ? kUnroll : 1];                                 // the row stays packed until it is reduced
+    auto fetch = [&](int t) {
+        if constexpr (FAST) {
+            const bool live = t < p.T;
+            const char* row = reinterpret_cast<const char*>(x) + static_cast<size_t>(live ? t : 0) * row_bytes;
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                int c = u * kWave + lane;
+                raw[u] = load_chunk(row, c, live && c < nchunks);
+            }
+        }
+    };
+    // the first row is requested before the embeddings are staged, so both latencies overlap
+    if (one_pass) fetch(blockIdx.x * kRouteWaves + wave);
 
     for (int i = tid; i < p.E * p.P; i += kRouteThreads) {
         int e = i / p.P, q = i - e * p.P;
@@ -84,32 +115,49 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteParams p, con
     __syncthreads();
 
     float* g = gs + wave * p.P;
-    const int nchunks = p.d / V;
     const float invD = 1.0f / static_cast<float>(p.D);
     const float sqrtD = sqrtf(static_cast<float>(p.D));
     const int e_lane = lane / p.L, sub = lane & (p.L - 1);
-    const size_t row_bytes = static_cast<size_t>(p.d) * (BF16 ? 2 : 4);
 
-    // every wave of the block runs the same number of iterations (block-wide barriers inside)
     for (int t0 = blockIdx.x * kRouteWaves; t0 < p.T; t0 += gridDim.x * kRouteWaves) {
         const int t = t0 + wave;
         const bool live = t < p.T;
         const char* row = reinterpret_cast<const char*>(x) + static_cast<size_t>(live ? t : 0) * row_bytes;
         float xx = 0.f;
-        if (p.R > 0) {
+        if constexpr (one_pass) {
+            float s[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                float f[V];
+                C::unpack(raw[u], f);
+                s[u] = 0.f;
+#pragma unroll
+                for (int j = 0; j < V; ++j) { s[u] += f[j]; xx += f[j] * f[j]; }
+            }
+            fetch(t + gridDim.x * kRouteWaves);          // next token of this wave (masked past T)
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int c = u * kWave + lane;
+                float v = s[u];
+                for (int m = 1; m < p.R; m <<= 1) v += __shfl_xor(v, m, kWave);
+                if ((lane & (p.R - 1)) == 0 && c < nchunks) g[c / p.R] = v * invD;
+            }
+        } else if (p.R > 0) {
             for (int c0 = 0; c0 < nchunks; c0 += kWave * kUnroll) {
-                float f[kUnroll][V];
+                uint4 rr[kUnroll];
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
                     int c = c0 + u * kWave + lane;
-                    C::load(row, c, live && c < nchunks, f[u]);
+                    rr[u] = load_chunk(row, c, live && c < nchunks);
                 }
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
                     int c = c0 + u * kWave + lane;
+                    float ff[V];
+                    C::unpack(rr[u], ff);
                     float s = 0.f;
 #pragma unroll
-                    for (int j = 0; j < V; ++j) { s += f[u][j]; xx += f[u][j] * f[u][j]; }
+                    for (int j = 0; j < V; ++j) { s += ff[j]; xx += ff[j] * ff[j]; }
                     for (int m = 1; m < p.R; m <<= 1) s += __shfl_xor(s, m, kWave);
                     if ((lane & (p.R - 1)) == 0 && c < nchunks) g[c / p.R] = s * invD;
                 }
@@ -126,7 +174,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteParams p, con
             }
         }
         xx = wave_sum(xx);
-        __syncthreads();
+        wave_lds_fence();                               // g was written by other lanes of this wave
 
         float acc = 0.f, gg = 0.f;
         if (e_lane < p.E) {
@@ -155,7 +203,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteParams p, con
             score[static_cast<size_t>(t) * p.E + e_lane] = sc;
             gate[static_cast<size_t>(t) * p.E + e_lane] = ex / z;
         }
-        __syncthreads();      // g is rewritten by the next iteration
+        wave_lds_fence();                               // g is rewritten by the next iteration
     }
 }
 
@@ -180,7 +228,9 @@ hipError_t launch_route(const etr_config& c, const void* x, const float* w_emb, 
     int blocks = (c.T + kRouteWaves - 1) / kRouteWaves;
     if (blocks > 256 * 8) blocks = 256 * 8;
     if (blocks < 1) blocks = 1;
-    auto kern = c.dtype == ETR_BF16 ? route_kernel<true> : route_kernel<false>;
+    const bool fast = p.R > 0 && p.d / V <= kWave * kUnroll;
+    auto kern = c.dtype == ETR_BF16 ? (fast ? route_kernel<true, true> : route_kernel<true, false>)
+                                    : (fast ? route_kernel<false, true> : route_kernel<false, false>);
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
