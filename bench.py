@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--capacity", type=int, default=None, help="override the capacity (cfg4's schedule)")
     ap.add_argument("--cpu-tokens", type=int, default=8192, help="tokens of the oracle's FFN sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1")
@@ -176,6 +178,11 @@ def main():
         "stage_alone": hbm,
         "ffn_down_TFLOPs": flops_gemm2 / (stage[4] * 1e-3) / 1e12 if stage[4] > 0 else None,
     }
+    if args.calibrate_copy:
+        a = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(shape, cfg, t, args.cpu_tokens)
     print(json.dumps(res), flush=True)

@@ -26,6 +26,7 @@ struct GemmParams {
     const int32_t* counts;
     int E, capacity, N, K;
     int MT, NT;           // row tiles per expert, column tiles
+    int SM, SN;           // super-tile shape (see decode_tile)
     const int32_t* row_index;   // optional [E][capacity]: A row m of expert e is row row_index[e][m] of A
     int k_stagger;              // pipelined kernels: workgroup j of an XCD starts its K loop (j % 32) * k_stagger tiles in
     int a_rows;                 // rows of A that row_index may name (indices are clamped into [0, a_rows))
@@ -39,20 +40,36 @@ __device__ __forceinline__ uint32_t f2bf(float f) {            // fp32 -> bf16 b
 
 __device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a)); }
 
-// Workgroup -> (expert, column tile, row tile).  Hardware deals consecutive workgroups
-// round-robin to the 8 XCDs, each with its own L2: a "band" = all row tiles of one
-// (expert, column tile) shares one weight tile, so a whole band goes to one XCD, row tile
-// fastest, and the weight tile is fetched from HBM once.
+// Workgroup -> (expert, row tile, column tile).  Hardware deals consecutive workgroups round-robin
+// to the 8 XCDs, each with its own 4 MiB L2 and 32 CUs.  Tiles are grouped into "super-tiles" of
+// SM row tiles x SN column tiles (SM*SN = 32 = the workgroups that run together on one XCD); a whole
+// super-tile goes to one XCD, so while its 32 workgroups stream along K together every token-row
+// slice is shared by SN of them and every weight slice by SM of them through that XCD's L2.
 __device__ __forceinline__ bool decode_tile(const GemmParams& p, int& e, int& mt, int& nt, int* seq = nullptr) {
     const int pid = blockIdx.x;
     const int xcd = pid & 7, j = pid >> 3;
     if (seq) *seq = j;
-    const int band = (j / p.MT) * 8 + xcd;
-    mt = j % p.MT;
-    if (band >= p.E * p.NT) return false;
-    e = band / p.NT;
-    nt = band - e * p.NT;
-    return true;
+    const int per = p.SM * p.SN;
+    const int sidx = (j / per) * 8 + xcd, l = j % per;
+    const int MG = (p.MT + p.SM - 1) / p.SM, NG = (p.NT + p.SN - 1) / p.SN;
+    if (sidx >= p.E * MG * NG) return false;
+    e = sidx / (MG * NG);
+    const int r = sidx - e * (MG * NG);
+    mt = (r % MG) * p.SM + l % p.SM;
+    nt = (r / MG) * p.SN + l / p.SM;
+    return mt < p.MT && nt < p.NT;
+}
+
+// Fills MT, NT and the super-tile shape; returns the number of workgroups to launch.
+inline long long plan_tiles(GemmParams& p, int BM, int BN) {
+    p.MT = (p.capacity + BM - 1) / BM;
+    p.NT = (p.N + BN - 1) / BN;
+    p.SM = p.MT < 4 ? p.MT : 4;
+    p.SN = 32 / p.SM;
+    if (p.SN > p.NT) p.SN = p.NT;
+    const long long MG = (p.MT + p.SM - 1) / p.SM, NG = (p.NT + p.SN - 1) / p.SN;
+    const long long supers = static_cast<long long>(p.E) * MG * NG;
+    return (supers + 7) / 8 * 8 * (p.SM * p.SN);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -802,10 +819,7 @@ template <int BM, int BN, int BK, int WGM, int WGN, bool GLU, int SWZ>
 hipError_t launch_bf16(GemmParams p, hipStream_t st) {
     constexpr int BROWS = GLU ? 2 * BN : BN;
     constexpr size_t lds = 2ull * (BM + BROWS) * BK * 2;
-    p.MT = (p.capacity + BM - 1) / BM;
-    p.NT = (p.N + BN - 1) / BN;
-    const long long bands = static_cast<long long>(p.E) * p.NT;
-    const long long blocks = (bands + 7) / 8 * 8 * p.MT;
+    const long long blocks = plan_tiles(p, BM, BN);
     auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, GLU, SWZ>;
     if (lds > 64 * 1024) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -819,10 +833,7 @@ hipError_t launch_bf16(GemmParams p, hipStream_t st) {
 template <bool GLU, int SWZ, int WN = 2>
 hipError_t launch_bf16_pipe(GemmParams p, hipStream_t st) {
     constexpr size_t lds = 2ull * 512 * 64 * 2;        // two buffers of 256 + 256 rows x 64 bf16
-    p.MT = (p.capacity + 255) / 256;
-    p.NT = (p.N + (GLU ? 128 : 256) - 1) / (GLU ? 128 : 256);
-    const long long bands = static_cast<long long>(p.E) * p.NT;
-    const long long blocks = (bands + 7) / 8 * 8 * p.MT;
+    const long long blocks = plan_tiles(p, 256, GLU ? 128 : 256);
     auto kern = gemm_bf16_pipe_kernel<GLU, SWZ, false, WN>;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
@@ -834,10 +845,7 @@ hipError_t launch_bf16_pipe(GemmParams p, hipStream_t st) {
 template <bool GLU, int WN = 2>
 hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
     constexpr size_t lds = 4ull * 512 * 32 * 2;        // four buffers of 256 + 256 rows x 32 bf16
-    p.MT = (p.capacity + 255) / 256;
-    p.NT = (p.N + (GLU ? 128 : 256) - 1) / (GLU ? 128 : 256);
-    const long long bands = static_cast<long long>(p.E) * p.NT;
-    const long long blocks = (bands + 7) / 8 * 8 * p.MT;
+    const long long blocks = plan_tiles(p, 256, GLU ? 128 : 256);
     auto kern = gemm_bf16_ring_kernel<GLU, WN>;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
@@ -849,10 +857,7 @@ hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
 template <bool GLU, int GROUPING, int DEBUG_SKIP = 0>
 hipError_t launch_bf16_pp(GemmParams p, hipStream_t st) {
     constexpr size_t lds = 4ull * 512 * 32 * 2;
-    p.MT = (p.capacity + 255) / 256;
-    p.NT = (p.N + (GLU ? 128 : 256) - 1) / (GLU ? 128 : 256);
-    const long long bands = static_cast<long long>(p.E) * p.NT;
-    const long long blocks = (bands + 7) / 8 * 8 * p.MT;
+    const long long blocks = plan_tiles(p, 256, GLU ? 128 : 256);
     auto kern = gemm_bf16_pp_kernel<GLU, GROUPING, DEBUG_SKIP>;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
@@ -863,10 +868,7 @@ hipError_t launch_bf16_pp(GemmParams p, hipStream_t st) {
 
 template <bool GLU>
 hipError_t launch_f32(GemmParams p, hipStream_t st) {
-    p.MT = (p.capacity + 63) / 64;
-    p.NT = (p.N + 63) / 64;
-    const long long bands = static_cast<long long>(p.E) * p.NT;
-    const long long blocks = (bands + 7) / 8 * 8 * p.MT;
+    const long long blocks = plan_tiles(p, 64, 64);
     hipLaunchKernelGGL(gemm_f32_kernel<GLU>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, p);
     return hipGetLastError();
 }
@@ -886,7 +888,7 @@ static bool pipelined_ok(const GemmParams& g, size_t a_rows) {
 
 bool ffn_can_gather(const etr_config& c) {
     if (c.dtype != ETR_BF16) return false;
-    GemmParams g1{nullptr, nullptr, nullptr, nullptr, nullptr, c.E, c.capacity, c.H, c.d, 0, 0, nullptr, 0, c.T};
+    GemmParams g1{nullptr, nullptr, nullptr, nullptr, nullptr, c.E, c.capacity, c.H, c.d, 0, 0, 0, 0, nullptr, 0, c.T};
     return pipelined_ok(g1, static_cast<size_t>(c.T));
 }
 
@@ -895,8 +897,8 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
                              hipEvent_t between, const int32_t* gather_rows) {
     // with gather_rows (= slot_token) xp is the token matrix x itself and GEMM-1 fetches row
     // gather_rows[e][s] of it: the rearrangement is folded into the operand load
-    GemmParams g1{xp, w_gate, w_up, hidden, counts, c.E, c.capacity, c.H, c.d, 0, 0, gather_rows, 0, c.T};
-    GemmParams g2{hidden, w_down, nullptr, yp, counts, c.E, c.capacity, c.d, c.H, 0, 0, nullptr, 0, c.capacity};
+    GemmParams g1{xp, w_gate, w_up, hidden, counts, c.E, c.capacity, c.H, c.d, 0, 0, 0, 0, gather_rows, 0, c.T};
+    GemmParams g2{hidden, w_down, nullptr, yp, counts, c.E, c.capacity, c.d, c.H, 0, 0, 0, 0, nullptr, 0, c.capacity};
     hipError_t err;
     if (c.dtype == ETR_BF16) {
         if (gather_rows && !ffn_can_gather(c)) return hipErrorInvalidValue;
@@ -904,7 +906,7 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
         err = pipe1 ? launch_bf16_ring<true, 4>(g1, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g1, st);
         if (err != hipSuccess) return err;
         if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
-        return pipelined_ok(g2, c.capacity) ? launch_bf16_ring<false, 4>(g2, st)
+        return pipelined_ok(g2, c.capacity) ? launch_bf16_pipe<false, 1, 4>(g2, st)
                                             : launch_bf16<128, 128, 64, 2, 2, false, 1>(g2, st);
     }
     if (gather_rows) return hipErrorInvalidValue;
