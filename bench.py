@@ -25,6 +25,11 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3       # fp32 vector
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel (FFN gate/up GEMM), measured with rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE on this very command and scaled by what a plain 1 GiB copy reads on the same counters (fetch x2.0,
+# write x1.0); the summaries are profiles/moe_forward_<cfg>_kernels_and_traffic.txt. None = not measured.
+MEASURED_TRAFFIC_BYTES = {"cfg2": 1084.9e6 + 136.6e6, "cfg5": 12669.0e6 + 721.2e6}
+
 
 def _to_np(t):
     import numpy as np
@@ -170,10 +175,14 @@ def main():
                                f"capacity={cfg.capacity} H={shape.H} mode={('TCR', 'ECR', 'BIDIR')[cfg.mode]} "
                                f"tokens={shape.recipe}",
                    "kept_rows": rows},
-        "roofline": {"kernel": "gemm_bf16_kernel<GLU> (FFN gate/up + SwiGLU)" if shape.dtype == I.DT_BF16
-                     else "gemm_f32_kernel<GLU>",
+        "roofline": {"kernel": "gemm_bf16_ring_kernel<GLU> (FFN gate/up projections + SwiGLU)"
+                     if shape.dtype == I.DT_BF16 else "gemm_f32_kernel<GLU>",
                      "bound": "mfma" if shape.dtype == I.DT_BF16 else "alu",
-                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None},
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if args.capacity is None else None,
+                     "algorithmic_flop": flops_gemm1,
+                     "algorithmic_bytes": elt * (2.0 * shape.E * shape.H * shape.d + rows * shape.d
+                                                 + rows * shape.H)},
         "stage_ms": stages,
         "stage_alone": hbm,
         "ffn_down_TFLOPs": flops_gemm2 / (stage[4] * 1e-3) / 1e12 if stage[4] > 0 else None,
