@@ -101,13 +101,21 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    events = [B.StageEvents() for _ in range(args.steps)]
+    # timed region: K steps; only the dominant kernel (FFN gate/up GEMM) is bracketed by events
+    # (boundaries 3 and 4), because every recorded event costs a few microseconds of stream time
+    gemm_events = [B.StageEvents(only=(3, 4)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(events[i])
+        step(gemm_events[i])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    t_gemm1_ms = sum(B.elapsed_ms(ev, 3, 4) for ev in gemm_events) / args.steps
+    # second pass, all stage boundaries marked: the per-stage breakdown (not part of `value`)
+    events = [B.StageEvents() for _ in range(args.steps)]
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
 
     # the HBM-bound stages once more on their own (the fused call folds the rearrangement into GEMM-1
     # and the stage events include launch gaps): plain hipEvent timing of back-to-back stage calls
@@ -147,7 +155,7 @@ def main():
     elt = 4 if shape.dtype == I.DT_F32 else 2
     # dominant kernel: FFN GEMM-1 (gate and up projections + SwiGLU), 4*d*H flop per kept row
     flops_gemm1 = 4.0 * rows * shape.d * shape.H
-    t_gemm1 = stage[3] * 1e-3
+    t_gemm1 = t_gemm1_ms * 1e-3
     peak = PEAK_BF16_TFLOPS if shape.dtype == I.DT_BF16 else PEAK_F32_TFLOPS
     achieved = flops_gemm1 / t_gemm1 / 1e12
     stages = {name: round(ms, 5) for name, ms in zip(B.STAGE_NAMES, stage)}

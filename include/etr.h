@@ -147,7 +147,8 @@ etr_status etr_moe_forward(const etr_config* cfg, const void* x, const float* w_
 
 /* etr_moe_forward with stage boundaries marked on the stream, for measurement.
  *   events: HOST array of ETR_N_STAGE_EVENTS hipEvent_t handles (as void*), created by the
- *   caller; event i is recorded on `stream` at boundary i:
+ *   caller; an entry may be NULL (that boundary is then not marked: each recorded event costs a few
+ *   microseconds of stream time); event i is recorded on `stream` at boundary i:
  *     0 start | 1 after route | 2 after select | 3 after dispatch | 4 after FFN GEMM-1
  *     (gate/up + SwiGLU) | 5 after FFN GEMM-2 (down) | 6 after combine
  * Computes exactly what etr_moe_forward computes, with the same kernels. */

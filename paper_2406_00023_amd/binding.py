@@ -148,14 +148,15 @@ class StageEvents:
     Created and read through the HIP runtime directly so that they are recorded on exactly
     the stream the kernels run on."""
 
-    def __init__(self):
+    def __init__(self, only=None):
+        """only: iterable of boundary indices to create (the others stay NULL and are not recorded)."""
         self._hip = ctypes.CDLL("libamdhip64.so")
         self._hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
         self._hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
         self._hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
         self._hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
         self.handles = (ctypes.c_void_p * N_STAGE_EVENTS)()
-        for i in range(N_STAGE_EVENTS):
+        for i in (range(N_STAGE_EVENTS) if only is None else only):
             ev = ctypes.c_void_p()
             if self._hip.hipEventCreate(ctypes.byref(ev)) != 0:
                 raise RuntimeError("hipEventCreate failed")

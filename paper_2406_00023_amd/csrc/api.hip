@@ -175,7 +175,7 @@ static etr_status forward_impl(const etr_config* cfg, const void* x, const float
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     auto mark = [&](int i) -> hipError_t {
-        return events ? hipEventRecord(static_cast<hipEvent_t>(events[i]), st) : hipSuccess;
+        return (events && events[i]) ? hipEventRecord(static_cast<hipEvent_t>(events[i]), st) : hipSuccess;
     };
     ETR_HIP(mark(0));
     ETR_HIP(launch_route(*cfg, x, w_emb, sc, gt, st));
@@ -208,8 +208,6 @@ etr_status etr_moe_forward_profiled(const etr_config* cfg, const void* x, const 
                                     int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts,
                                     void* ws, size_t ws_bytes, void* stream, void* const* events) {
     if (!events) return ETR_ERR_NULL;
-    for (int i = 0; i < ETR_N_STAGE_EVENTS; ++i)
-        if (!events[i]) return ETR_ERR_NULL;
     return forward_impl(cfg, x, w_emb, w_gate, w_up, w_down, out, score, gate_out, topk_expert, slot_of, slot_token,
                         counts, ws, ws_bytes, stream, events);
 }

@@ -12,8 +12,9 @@ constexpr int kRowThreads = 256;
 constexpr int kRowWaves = kRowThreads / kWave;
 
 // xp[e][s][:] = x[slot_token[e][s]][:]  for s < counts[e]
-// A wave walks rows r, r + stride, ...; the loads of a row are all in flight before its first
-// store, and the index of the next row is fetched early.
+// A wave walks rows r, r + stride, ...  The source index of the next row is fetched while the
+// current row is copied (otherwise every row pays two dependent memory latencies before its first
+// load), and all loads of a row are in flight before its first store.
 __global__ __launch_bounds__(kRowThreads) void dispatch_kernel(const uint4* __restrict__ x,
                                                                const int32_t* __restrict__ slot_token,
                                                                const int32_t* __restrict__ counts,
@@ -22,26 +23,36 @@ __global__ __launch_bounds__(kRowThreads) void dispatch_kernel(const uint4* __re
     const int lane = threadIdx.x & (kWave - 1);
     const long long stride = static_cast<long long>(gridDim.x) * kRowWaves;
     constexpr int U = 8;
-    for (long long r = static_cast<long long>(blockIdx.x) * kRowWaves + threadIdx.x / kWave; r < rows; r += stride) {
+    // source row of buffer row r, or -1 when the slot is empty / the table does not belong to this x
+    auto source_of = [&](long long r) -> int {
+        if (r >= rows) return -1;
         const int e = static_cast<int>(r / capacity), s = static_cast<int>(r - static_cast<long long>(e) * capacity);
-        if (s >= counts[e]) continue;
+        if (s >= counts[e]) return -1;
         const int t = slot_token[r];
-        if (t < 0 || t >= T) continue;                  // a table that does not belong to this x: skip the row
-        const uint4* src = x + static_cast<size_t>(t) * row_vecs;
-        uint4* dst = xp + static_cast<size_t>(r) * row_vecs;
-        for (int c0 = 0; c0 < row_vecs; c0 += kWave * U) {
-            uint4 v[U];
+        return (t < 0 || t >= T) ? -1 : t;
+    };
+    long long r = static_cast<long long>(blockIdx.x) * kRowWaves + threadIdx.x / kWave;
+    int t = source_of(r);
+    for (; r < rows; r += stride) {
+        const int t_next = source_of(r + stride);
+        if (t >= 0) {
+            const uint4* src = x + static_cast<size_t>(t) * row_vecs;
+            uint4* dst = xp + static_cast<size_t>(r) * row_vecs;
+            for (int c0 = 0; c0 < row_vecs; c0 += kWave * U) {
+                uint4 v[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                int c = c0 + u * kWave + lane;
-                if (c < row_vecs) v[u] = src[c];
-            }
+                for (int u = 0; u < U; ++u) {
+                    int c = c0 + u * kWave + lane;
+                    if (c < row_vecs) v[u] = src[c];
+                }
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                int c = c0 + u * kWave + lane;
-                if (c < row_vecs) dst[c] = v[u];
+                for (int u = 0; u < U; ++u) {
+                    int c = c0 + u * kWave + lane;
+                    if (c < row_vecs) dst[c] = v[u];
+                }
             }
         }
+        t = t_next;
     }
 }
 
