@@ -8,6 +8,7 @@
 namespace etr {
 namespace {
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kRowThreads = 256;
 constexpr int kRowWaves = kRowThreads / kWave;
 
@@ -48,7 +49,9 @@ __global__ __launch_bounds__(kRowThreads) void dispatch_kernel(const uint4* __re
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     int c = c0 + u * kWave + lane;
-                    if (c < row_vecs) dst[c] = v[u];
+                    // streaming store: the permuted rows are not read again by this kernel
+                    if (c < row_vecs)
+                        __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v[u]), reinterpret_cast<u32x4*>(dst) + c);
                 }
             }
         }
@@ -138,7 +141,10 @@ __global__ __launch_bounds__(kRowThreads) void combine_kernel(const uint4* __res
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int c = c0 + u * kWave + lane;
-            if (c < row_vecs) out[static_cast<size_t>(t) * row_vecs + c] = R::pack(acc[u]);
+            // streaming store: the layer output is not read again here
+            if (c < row_vecs)
+                __builtin_nontemporal_store(__builtin_bit_cast(u32x4, R::pack(acc[u])),
+                                            reinterpret_cast<u32x4*>(out) + static_cast<size_t>(t) * row_vecs + c);
         }
     }
 }

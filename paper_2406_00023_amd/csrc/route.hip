@@ -43,6 +43,13 @@ struct Chunk<false> {
         f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
     }
     __device__ static float scalar(const void* row, int i) { return reinterpret_cast<const float*>(row)[i]; }
+    // s += sum of the chunk, xx += sum of squares
+    __device__ static void accumulate(const uint4& v, float& s, float& xx) {
+        float f[4];
+        unpack(v, f);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { s += f[j]; xx = fmaf(f[j], f[j], xx); }
+    }
 };
 
 template <>
@@ -56,6 +63,19 @@ struct Chunk<true> {
     }
     __device__ static float scalar(const void* row, int i) {
         return __uint_as_float(static_cast<uint32_t>(reinterpret_cast<const uint16_t*>(row)[i]) << 16);
+    }
+    // s += sum of the chunk, xx += sum of squares: two-element bf16 dot products with fp32 accumulation
+    // (v_dot2c_f32_bf16), one instruction per pair instead of unpack + add + fma
+    __device__ static void accumulate(const uint4& v, float& s, float& xx) {
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+        const bf16x2 one = __builtin_bit_cast(bf16x2, 0x3F803F80u);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bf16x2 p2 = __builtin_bit_cast(bf16x2, w[j]);
+            s = __builtin_amdgcn_fdot2_f32_bf16(p2, one, s, false);
+            xx = __builtin_amdgcn_fdot2_f32_bf16(p2, p2, xx, false);
+        }
     }
 };
 
@@ -128,11 +148,8 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteParams p, con
             float s[kUnroll];
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                float f[V];
-                C::unpack(raw[u], f);
                 s[u] = 0.f;
-#pragma unroll
-                for (int j = 0; j < V; ++j) { s[u] += f[j]; xx += f[j] * f[j]; }
+                C::accumulate(raw[u], s[u], xx);
             }
             fetch(t + gridDim.x * kRouteWaves);          // next token of this wave (masked past T)
 #pragma unroll
