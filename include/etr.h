@@ -145,6 +145,39 @@ etr_status etr_moe_forward(const etr_config* cfg, const void* x, const float* w_
                            int32_t* slot_token, int32_t* counts,
                            void* ws, size_t ws_bytes, void* stream);
 
+/* ---- beyond the forward chain: what a trainer reads off the routing ------------------------- */
+
+/* etr_select with a capacity that lives on the device: the selection uses
+ * min(cfg->capacity, max(1, *capacity_dev)); buffers keep the stride cfg->capacity.  Lets a
+ * capacity computed in-stream (etr_capacity_lower_bound) drive the selection without a host
+ * round trip.  capacity_dev: device int32[1], required. Everything else as etr_select. */
+etr_status etr_select_bounded(const etr_config* cfg, const float* score, const int32_t* capacity_dev,
+                              int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts,
+                              void* ws, size_t ws_bytes, void* stream);
+
+/* Scratch for the two reductions below. 0 for an invalid config. */
+size_t etr_stats_workspace_bytes(const etr_config* cfg);
+
+/* Statistics behind the losses of Sec. Locality Loss (all outputs on the device):
+ *   load_frac [E] fp32  D_c: counts[e] / sum(counts), the current distribution of kept
+ *                       (token, expert) assignments; all zero if nothing is kept
+ *   mean_gate [E] fp32  (1/T) sum_t gate[t][e]
+ *   kl        [1] fp32  KL(D_c || D_l) = sum_e D_c(e) ln(D_c(e) / target[e]); terms with D_c(e) = 0
+ *                       are 0, target[e] = 0 < D_c(e) gives +inf; L_loc = mu * kl is the caller's
+ *   n_unrouted[1] int32 tokens kept by no expert
+ *   gate [T][E], slot_of [T][E], counts [E], target [E] (D_l, fp32): in
+ * Fixed summation order: results are bit-reproducible. */
+etr_status etr_route_stats(const etr_config* cfg, const float* gate, const int32_t* slot_of,
+                           const int32_t* counts, const float* target, float* load_frac, float* mean_gate,
+                           float* kl, int32_t* n_unrouted, void* ws, size_t ws_bytes, void* stream);
+
+/* Lower bound of the expert capacity, Remark of Sec. Dynamic Lower Bound Module:
+ *   C_min = (1/n) exp{ d * dmax^2 / (2 - dmax^2) }, dmax = largest affinity of the batch, n = E.
+ *   dmax [1] fp32 out, capacity [1] int32 out = ceil(C_min) clamped into [1, T]; the exponent is
+ *   evaluated in fp64 and compared in the log domain (no overflow for real d). */
+etr_status etr_capacity_lower_bound(const etr_config* cfg, const float* score, float* dmax,
+                                    int32_t* capacity, void* ws, size_t ws_bytes, void* stream);
+
 /* etr_moe_forward with stage boundaries marked on the stream, for measurement.
  *   events: HOST array of ETR_N_STAGE_EVENTS hipEvent_t handles (as void*), created by the
  *   caller; an entry may be NULL (that boundary is then not marked: each recorded event costs a few

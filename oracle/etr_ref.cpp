@@ -28,6 +28,8 @@
 //   etr_ref_ffn_rows    the expert network: a SwiGLU feed-forward block
 //   etr_ref_combine     the gate-weighted sum of Eq. 1
 //   etr_ref_moe_forward the chain of the above
+//   etr_ref_route_stats expert load distribution, mean gate and KL(D_c || D_l) of Sec. Locality Loss
+//   etr_ref_capacity_lower_bound  C_min of the Remark in Sec. Dynamic Lower Bound Module
 //
 // Readings of points the paper leaves open (all listed in the design notes):
 // ties go to the lowest index; slots inside an expert are in ascending token
@@ -379,6 +381,62 @@ int etr_ref_moe_forward(int T, int d, int E, int D, int k, int capacity, int H, 
     if (slot_of_out) std::copy(slot_of.begin(), slot_of.end(), slot_of_out);
     if (slot_token_out) std::copy(slot_token.begin(), slot_token.end(), slot_token_out);
     if (counts_out) std::copy(counts.begin(), counts.end(), counts_out);
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Routing statistics that the losses of Sec. Locality Loss are built from:
+//   load[e]      = counts[e] / sum(counts): the current distribution D_c of kept
+//                  (token, expert) assignments over the experts (all 0 if nothing is kept)
+//   mean_gate[e] = (1/T) sum_t gate[t][e]
+//   kl           = KL(D_c || D_l) = sum_e D_c(e) ln(D_c(e) / D_l(e)) for a caller-given
+//                  localized distribution D_l (`target`); terms with D_c(e) = 0 are 0,
+//                  D_l(e) = 0 < D_c(e) gives +inf.  L_loc = mu * kl is left to the caller.
+//   n_unrouted   = tokens kept by no expert
+// ---------------------------------------------------------------------------
+int etr_ref_route_stats(int T, int E, const float* gate, const int32_t* slot_of, const int32_t* counts,
+                        const float* target, double* load, double* mean_gate, double* kl, int32_t* n_unrouted) {
+    long long total = 0;
+    for (int e = 0; e < E; ++e) total += counts[e];
+    double k = 0;
+    for (int e = 0; e < E; ++e) {
+        load[e] = total > 0 ? double(counts[e]) / double(total) : 0.0;
+        double s = 0;
+        for (int t = 0; t < T; ++t) s += double(gate[(size_t)t * E + e]);
+        mean_gate[e] = s / T;
+        if (load[e] > 0) k += (target[e] > 0) ? load[e] * std::log(load[e] / double(target[e])) : INFINITY;
+    }
+    *kl = k;
+    int32_t un = 0;
+    for (int t = 0; t < T; ++t) {
+        bool any = false;
+        for (int e = 0; e < E; ++e) any = any || slot_of[(size_t)t * E + e] >= 0;
+        un += any ? 0 : 1;
+    }
+    *n_unrouted = un;
+    return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Lower bound of the expert capacity from the Remark of Sec. Dynamic Lower Bound Module:
+//   C_min = (1/n) exp{ d * dmax^2 / (2 - dmax^2) },  dmax = largest affinity in the batch,
+// returned as an integer capacity: ceil(C_min) clamped into [1, T].  The exponent is
+// evaluated in double from the fp32 maximum; it is compared in the log domain so that
+// huge exponents (real d) do not overflow.
+// ---------------------------------------------------------------------------
+int etr_ref_capacity_lower_bound(int T, int E, int d, const float* score, float* dmax_out, int32_t* capacity_out) {
+    if (T < 1 || E < 1) return 2;
+    float mx = score[0];
+    for (size_t i = 0; i < (size_t)T * E; ++i) mx = std::max(mx, score[i]);
+    const double dm = double(mx);
+    const double log_c = double(d) * dm * dm / (2.0 - dm * dm) - std::log(double(E));
+    int32_t c;
+    if (log_c >= std::log(double(T))) c = T;
+    else c = (int32_t)std::ceil(std::exp(log_c));
+    if (c < 1) c = 1;
+    if (c > T) c = T;
+    *dmax_out = mx;
+    *capacity_out = c;
     return 0;
 }
 

@@ -152,6 +152,26 @@ def moe_forward(x, w_emb, w_gate, w_up, w_down, *, D: int, k: int, capacity: int
     return res
 
 
+def route_stats(gate: np.ndarray, slot_of: np.ndarray, counts: np.ndarray, target: np.ndarray):
+    """Returns load[E], mean_gate[E] (float64), kl (float), n_unrouted (int)."""
+    T, E = gate.shape
+    assert gate.dtype == np.float32 and target.dtype == np.float32 and slot_of.dtype == np.int32
+    load, mg = np.empty(E, np.float64), np.empty(E, np.float64)
+    kl, un = np.zeros(1, np.float64), np.zeros(1, np.int32)
+    _check(lib().etr_ref_route_stats(T, E, _p(gate), _p(slot_of), _p(np.ascontiguousarray(counts, np.int32)),
+                                     _p(target), _p(load), _p(mg), _p(kl), _p(un)), "route_stats")
+    return load, mg, float(kl[0]), int(un[0])
+
+
+def capacity_lower_bound(score: np.ndarray, d: int):
+    """Returns (dmax, capacity) of the Remark's C_min for this batch of scores."""
+    T, E = score.shape
+    assert score.dtype == np.float32
+    dm, c = np.zeros(1, np.float32), np.zeros(1, np.int32)
+    _check(lib().etr_ref_capacity_lower_bound(T, E, d, _p(score), _p(dm), _p(c)), "capacity_lower_bound")
+    return float(dm[0]), int(c[0])
+
+
 def bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
     """uint16 bf16 bit patterns -> float64 values (pure bit reinterpretation)."""
     return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)

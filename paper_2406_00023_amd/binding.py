@@ -20,7 +20,8 @@ LIB_PATH = os.path.join(_HERE, "libetr_hip.so")
 
 EXPORTS = ("etr_workspace_bytes", "etr_select_workspace_bytes", "etr_ffn_workspace_bytes", "etr_status_string",
            "etr_route", "etr_select", "etr_dispatch", "etr_expert_ffn", "etr_combine", "etr_moe_forward",
-           "etr_moe_forward_profiled")
+           "etr_moe_forward_profiled", "etr_select_bounded", "etr_stats_workspace_bytes", "etr_route_stats",
+           "etr_capacity_lower_bound")
 N_STAGE_EVENTS = 7
 STAGE_NAMES = ("route", "select", "dispatch", "ffn_gate_up", "ffn_down", "combine")
 
@@ -48,7 +49,8 @@ def load_library():
                                 "(or __graft_entry__.build()); there is no fallback path")
     lib = ctypes.CDLL(LIB_PATH)
     vp, sz, cp = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(EtrConfig)
-    for name in ("etr_workspace_bytes", "etr_select_workspace_bytes", "etr_ffn_workspace_bytes"):
+    for name in ("etr_workspace_bytes", "etr_select_workspace_bytes", "etr_ffn_workspace_bytes",
+                 "etr_stats_workspace_bytes"):
         getattr(lib, name).restype = sz
         getattr(lib, name).argtypes = [cp]
     lib.etr_status_string.restype = ctypes.c_char_p
@@ -60,6 +62,9 @@ def load_library():
         "etr_expert_ffn": [cp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "etr_combine": [cp, vp, vp, vp, vp, vp],
         "etr_moe_forward": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "etr_select_bounded": [cp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "etr_route_stats": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "etr_capacity_lower_bound": [cp, vp, vp, vp, vp, sz, vp],
         "etr_moe_forward_profiled": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
                                      ctypes.POINTER(ctypes.c_void_p)],
     }
@@ -118,6 +123,27 @@ def etr_route(cfg, x, w_emb, score, gate):
 def etr_select(cfg, score, topk_expert, slot_of, slot_token, counts, ws):
     _check("etr_select", load_library().etr_select(ctypes.byref(cfg), _ptr(score), _ptr(topk_expert), _ptr(slot_of),
                                                    _ptr(slot_token), _ptr(counts), _ptr(ws), _nbytes(ws), _stream()))
+
+
+def etr_select_bounded(cfg, score, capacity_dev, topk_expert, slot_of, slot_token, counts, ws):
+    _check("etr_select_bounded", load_library().etr_select_bounded(
+        ctypes.byref(cfg), _ptr(score), _ptr(capacity_dev), _ptr(topk_expert), _ptr(slot_of), _ptr(slot_token),
+        _ptr(counts), _ptr(ws), _nbytes(ws), _stream()))
+
+
+def etr_stats_workspace_bytes(cfg: EtrConfig) -> int:
+    return int(load_library().etr_stats_workspace_bytes(ctypes.byref(cfg)))
+
+
+def etr_route_stats(cfg, gate, slot_of, counts, target, load_frac, mean_gate, kl, n_unrouted, ws):
+    _check("etr_route_stats", load_library().etr_route_stats(
+        ctypes.byref(cfg), _ptr(gate), _ptr(slot_of), _ptr(counts), _ptr(target), _ptr(load_frac), _ptr(mean_gate),
+        _ptr(kl), _ptr(n_unrouted), _ptr(ws), _nbytes(ws), _stream()))
+
+
+def etr_capacity_lower_bound(cfg, score, dmax, capacity, ws):
+    _check("etr_capacity_lower_bound", load_library().etr_capacity_lower_bound(
+        ctypes.byref(cfg), _ptr(score), _ptr(dmax), _ptr(capacity), _ptr(ws), _nbytes(ws), _stream()))
 
 
 def etr_dispatch(cfg, x, slot_token, counts, xp):

@@ -120,6 +120,51 @@ etr_status etr_select(const etr_config* cfg, const float* score, int32_t* topk_e
     return ETR_OK;
 }
 
+etr_status etr_select_bounded(const etr_config* cfg, const float* score, const int32_t* capacity_dev,
+                              int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts, void* ws,
+                              size_t ws_bytes, void* stream) {
+    etr_status s = check_config(cfg);
+    if (s != ETR_OK) return s;
+    ETR_REQUIRE_PTR(score); ETR_REQUIRE_PTR(slot_of); ETR_REQUIRE_PTR(slot_token); ETR_REQUIRE_PTR(counts);
+    ETR_REQUIRE_PTR(ws); ETR_OPTIONAL_PTR(topk_expert);
+    if (!capacity_dev) return ETR_ERR_NULL;
+    if (ws_bytes < select_ws_bytes(cfg->T, cfg->E)) return ETR_ERR_WORKSPACE;
+    const SelectWs w = select_ws_carve(ws, cfg->T, cfg->E);
+    ETR_HIP(launch_select(*cfg, score, topk_expert, slot_of, slot_token, counts, w, static_cast<hipStream_t>(stream),
+                          capacity_dev));
+    return ETR_OK;
+}
+
+size_t etr_stats_workspace_bytes(const etr_config* cfg) {
+    if (check_config(cfg) != ETR_OK) return 0;
+    return stats_ws_bytes(cfg->T, cfg->E);
+}
+
+etr_status etr_route_stats(const etr_config* cfg, const float* gate, const int32_t* slot_of, const int32_t* counts,
+                           const float* target, float* load_frac, float* mean_gate, float* kl, int32_t* n_unrouted,
+                           void* ws, size_t ws_bytes, void* stream) {
+    etr_status s = check_config(cfg);
+    if (s != ETR_OK) return s;
+    ETR_REQUIRE_PTR(gate); ETR_REQUIRE_PTR(slot_of); ETR_REQUIRE_PTR(counts); ETR_REQUIRE_PTR(target);
+    ETR_REQUIRE_PTR(ws);
+    if (!load_frac || !mean_gate || !kl || !n_unrouted) return ETR_ERR_NULL;
+    if (ws_bytes < stats_ws_bytes(cfg->T, cfg->E)) return ETR_ERR_WORKSPACE;
+    ETR_HIP(launch_route_stats(*cfg, gate, slot_of, counts, target, load_frac, mean_gate, kl, n_unrouted, ws,
+                               static_cast<hipStream_t>(stream)));
+    return ETR_OK;
+}
+
+etr_status etr_capacity_lower_bound(const etr_config* cfg, const float* score, float* dmax, int32_t* capacity,
+                                    void* ws, size_t ws_bytes, void* stream) {
+    etr_status s = check_config(cfg);
+    if (s != ETR_OK) return s;
+    ETR_REQUIRE_PTR(score); ETR_REQUIRE_PTR(ws);
+    if (!dmax || !capacity) return ETR_ERR_NULL;
+    if (ws_bytes < stats_ws_bytes(cfg->T, cfg->E)) return ETR_ERR_WORKSPACE;
+    ETR_HIP(launch_capacity_lower_bound(*cfg, score, dmax, capacity, ws, static_cast<hipStream_t>(stream)));
+    return ETR_OK;
+}
+
 etr_status etr_dispatch(const etr_config* cfg, const void* x, const int32_t* slot_token, const int32_t* counts,
                         void* xp, void* stream) {
     etr_status s = check_config(cfg);

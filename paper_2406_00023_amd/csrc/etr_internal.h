@@ -36,7 +36,8 @@ hipError_t launch_route(const etr_config& c, const void* x, const float* w_emb, 
                         hipStream_t st);
 // select.hip
 hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_expert, int32_t* slot_of,
-                         int32_t* slot_token, int32_t* counts, const SelectWs& w, hipStream_t st);
+                         int32_t* slot_token, int32_t* counts, const SelectWs& w, hipStream_t st,
+                         const int32_t* capacity_dev = nullptr);   // optional device-side bound <= c.capacity
 // permute.hip
 hipError_t launch_dispatch(const etr_config& c, const void* x, const int32_t* slot_token, const int32_t* counts,
                            void* xp, hipStream_t st);
@@ -51,6 +52,14 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
 // True when GEMM-1 can read its rows straight from the token matrix through slot_token
 // (then xp is never materialised by the fused forward).
 bool ffn_can_gather(const etr_config& c);
+
+// stats.hip
+size_t stats_ws_bytes(int T, int E);
+hipError_t launch_route_stats(const etr_config& c, const float* gate, const int32_t* slot_of, const int32_t* counts,
+                              const float* target, float* load, float* mean_gate, float* kl, int32_t* n_unrouted,
+                              void* ws, hipStream_t st);
+hipError_t launch_capacity_lower_bound(const etr_config& c, const float* score, float* dmax, int32_t* capacity,
+                                       void* ws, hipStream_t st);
 
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline size_t elt_bytes(int dtype) { return dtype == ETR_F32 ? 4 : 2; }

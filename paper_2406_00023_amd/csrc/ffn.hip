@@ -419,7 +419,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_pipe_kernel(GemmParams p, 
 // iterations to land: before barrier(kt) a wave waits only until at most 12 copies are
 // outstanding (s_waitcnt vmcnt(12)), i.e. until its share of tile kt+1 is in LDS.
 // ---------------------------------------------------------------------------------------
-template <bool GLU, int WN = 2>
+template <bool GLU, int WN = 2, int AUXA = 0, int AUXB = 0>
 __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) {
     constexpr int BM = 256, BR = 256, CPR = 4, NBUF = 4;
     constexpr int BN = GLU ? 128 : 256;
@@ -475,7 +475,8 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
         const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
         const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
         const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
-        __builtin_amdgcn_global_load_lds((global_cptr)(base + off[j]), (lds_ptr)dst, 16, 0, 0);
+        if (j < NCP) __builtin_amdgcn_global_load_lds((global_cptr)(base + off[j]), (lds_ptr)dst, 16, 0, AUXA);
+        else __builtin_amdgcn_global_load_lds((global_cptr)(base + off[j]), (lds_ptr)dst, 16, 0, AUXB);
     };
 
     const int sw = (r32 >> 2) & 3;
@@ -842,11 +843,11 @@ hipError_t launch_bf16_pipe(GemmParams p, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <bool GLU, int WN = 2>
+template <bool GLU, int WN = 2, int AUXA = 0, int AUXB = 0>
 hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
     constexpr size_t lds = 4ull * 512 * 32 * 2;        // four buffers of 256 + 256 rows x 32 bf16
     const long long blocks = plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_ring_kernel<GLU, WN>;
+    auto kern = gemm_bf16_ring_kernel<GLU, WN, AUXA, AUXB>;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (err != hipSuccess) return err;

@@ -92,7 +92,8 @@ __device__ __forceinline__ void block_sum3(int& a, int& b, int& c, int (*red)[3]
 // IPT > 0: the thread's ipt (<= IPT) keys live in registers.  IPT == 0: streamed from memory.
 template <int IPT>
 __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32_t* __restrict__ keyT, int Tpad, int T,
-                                                                    int ipt, int capacity, int mode,
+                                                                    int ipt, int capacity_host, int mode,
+                                                                    const int32_t* __restrict__ capacity_dev,
                                                                     uint32_t* __restrict__ tau_out,
                                                                     int32_t* __restrict__ need_eq_out,
                                                                     int32_t* __restrict__ pre_gt,
@@ -101,6 +102,8 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
     __shared__ int red[kSelThreads / kWave][3];
     __shared__ int wave_tot[kSelThreads / kWave][2];
     const int e = blockIdx.x, tid = threadIdx.x;
+    // a capacity computed on the device (e.g. the lower bound of the Remark) may tighten the host one
+    const int capacity = capacity_dev ? min(capacity_host, max(1, *capacity_dev)) : capacity_host;
     const uint32_t* col = keyT + static_cast<size_t>(e) * Tpad;
     const int base = tid * ipt;
 
@@ -261,7 +264,8 @@ SelectWs select_ws_carve(void* ws, int T, int E) {
 }
 
 hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_expert, int32_t* slot_of,
-                         int32_t* slot_token, int32_t* counts, const SelectWs& w, hipStream_t st) {
+                         int32_t* slot_token, int32_t* counts, const SelectWs& w, hipStream_t st,
+                         const int32_t* capacity_dev) {
     int G = 1;
     while (G < c.E) G <<= 1;
     const long long lanes = static_cast<long long>(c.T) * G;
@@ -284,7 +288,7 @@ hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_
 
 #define ETR_EC(II)                                                                                               \
     hipLaunchKernelGGL(expert_choice_kernel<II>, dim3(c.E), dim3(kSelThreads), 0, st, w.keyT, w.Tpad, c.T, w.ipt, \
-                       c.capacity, c.mode, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts)
+                       c.capacity, c.mode, capacity_dev, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts)
     if (w.ipt <= 4) ETR_EC(4);
     else if (w.ipt <= 16) ETR_EC(16);
     else if (w.ipt <= 64) ETR_EC(64);
