@@ -147,13 +147,22 @@ etr_status etr_moe_forward(const etr_config* cfg, const void* x, const float* w_
 
 /* ---- beyond the forward chain: what a trainer reads off the routing ------------------------- */
 
-/* etr_select with a capacity that lives on the device: the selection uses
- * min(cfg->capacity, max(1, *capacity_dev)); buffers keep the stride cfg->capacity.  Lets a
- * capacity computed in-stream (etr_capacity_lower_bound) drive the selection without a host
- * round trip.  capacity_dev: device int32[1], required. Everything else as etr_select. */
-etr_status etr_select_bounded(const etr_config* cfg, const float* score, const int32_t* capacity_dev,
-                              int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts,
-                              void* ws, size_t ws_bytes, void* stream);
+/* etr_select with the two adaptive bounds of the method:
+ *  - capacity_dev (device int32[1], may be NULL): a capacity that lives on the device, e.g. the
+ *    output of etr_capacity_lower_bound; the selection uses min(cfg->capacity, max(1, *capacity_dev))
+ *    and the buffers keep the stride cfg->capacity, so no host round trip is needed;
+ *  - affinity_sum_threshold (host float; <= 0 switches it off): the adaptive token count of
+ *    Sec. Routing Strategy ("the expert chooses its Top-l tokens where l is determined by a threshold
+ *    of the sum of affinity scores"; the paper gives no value, so it is an argument).  Expert e walks
+ *    its candidates from the highest affinity down and stops at the first prefix whose affinity sum
+ *    reaches the threshold (all candidates if the positive affinities never get there); it keeps
+ *    min(capacity, that prefix length).  Affinities are summed as integers round(clamp(s,-1,1)*2^30),
+ *    so the decision does not depend on the order of summation.  Ignored in TCR mode (position
+ *    priority); T must be <= 2^22 when it is on.
+ * Everything else as etr_select. */
+etr_status etr_select_adaptive(const etr_config* cfg, const float* score, const int32_t* capacity_dev,
+                               float affinity_sum_threshold, int32_t* topk_expert, int32_t* slot_of,
+                               int32_t* slot_token, int32_t* counts, void* ws, size_t ws_bytes, void* stream);
 
 /* Scratch for the two reductions below. 0 for an invalid config. */
 size_t etr_stats_workspace_bytes(const etr_config* cfg);

@@ -171,8 +171,31 @@ int etr_ref_route(int T, int d, int E, int D, int dtype, int cos_mode,
 //   slot_of[T][E] (slot of token t in expert e's buffer, -1 if not kept),
 //   slot_token[E][capacity] (inverse; -1 = empty slot), counts[E].
 // ---------------------------------------------------------------------------
+// Fixed-point image of an affinity used for the adaptive token count: round(clamp(s,-1,1) * 2^30).
+// Sums of these integers do not depend on the order of addition, so "the prefix sum reaches the
+// threshold" is one well-defined integer decision on every implementation.
+static long long affinity_fixed(float s) {
+    double v = std::min(1.0, std::max(-1.0, (double)s));
+    return std::llrint(v * 1073741824.0);
+}
+
+int etr_ref_select_adaptive(int T, int E, int k, int capacity, int mode, const float* score, float sum_threshold,
+                            int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts);
+
 int etr_ref_select(int T, int E, int k, int capacity, int mode, const float* score,
                    int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts) {
+    return etr_ref_select_adaptive(T, E, k, capacity, mode, score, 0.0f, topk_expert, slot_of, slot_token, counts);
+}
+
+// Selection with the adaptive token count of Sec. Routing Strategy ("the expert chooses its Top-l
+// tokens where l is determined by a threshold of the sum of affinity scores"; the paper gives no
+// value for the threshold, so it is an argument).  Reading: expert e walks its candidates from the
+// highest affinity down and stops at the first prefix whose affinity sum reaches sum_threshold;
+// l_e is that prefix length, or all candidates if the sum of the positive affinities never gets
+// there; the expert then keeps min(capacity, l_e) tokens.  sum_threshold <= 0 switches it off; it
+// does not apply to pure token choice (TCR keeps by position, not by affinity).
+int etr_ref_select_adaptive(int T, int E, int k, int capacity, int mode, const float* score, float sum_threshold,
+                            int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts) {
     if (T < 0 || E <= 0 || capacity < 1) return 2;
     if (mode != MODE_ECR && (k < 1 || k > E)) return 2;
     if (mode < 0 || mode > 2) return 3;
@@ -201,7 +224,7 @@ int etr_ref_select(int T, int E, int k, int capacity, int mode, const float* sco
 
     for (int e = 0; e < E; ++e) {
         std::vector<int> cand = candidates[e];
-        const int n_keep = std::min<int>(capacity, (int)cand.size());
+        int n_keep = std::min<int>(capacity, (int)cand.size());
         std::vector<int> kept;
         if (mode == MODE_TCR) {
             // position priority: the first C tokens (in token order) that chose e
@@ -209,6 +232,18 @@ int etr_ref_select(int T, int E, int k, int capacity, int mode, const float* sco
         } else {
             // Eq. 6 / pure ECR: the C candidates with the highest affinity to e
             std::stable_sort(cand.begin(), cand.end(), ByScoreThenIndex{score + e, (size_t)E});
+            if (sum_threshold > 0.0f) {
+                const long long need = std::max(1ll, std::llrint((double)sum_threshold * 1073741824.0));
+                long long run = 0;
+                int ell = (int)cand.size();
+                for (int m = 0; m < (int)cand.size(); ++m) {
+                    const float sc = score[(size_t)cand[m] * E + e];
+                    if (!(sc > 0.0f)) break;                 // the sum cannot grow any further
+                    run += affinity_fixed(sc);
+                    if (run >= need) { ell = m + 1; break; }
+                }
+                n_keep = std::min(n_keep, ell);
+            }
             kept.assign(cand.begin(), cand.begin() + n_keep);
             std::sort(kept.begin(), kept.end());      // slots in ascending token order
         }

@@ -88,6 +88,18 @@ def select(score: np.ndarray, k: int, capacity: int, mode: int):
     return topk, slot_of, slot_token, counts
 
 
+def select_adaptive(score: np.ndarray, k: int, capacity: int, mode: int, sum_threshold: float):
+    T, E = score.shape
+    assert score.dtype == np.float32
+    topk = np.full((T, max(k, 1)), -1, np.int32)
+    slot_of = np.empty((T, E), np.int32)
+    slot_token = np.empty((E, capacity), np.int32)
+    counts = np.empty((E,), np.int32)
+    _check(lib().etr_ref_select_adaptive(T, E, k, capacity, mode, _p(score), ctypes.c_float(sum_threshold), _p(topk),
+                                         _p(slot_of), _p(slot_token), _p(counts)), "select_adaptive")
+    return topk, slot_of, slot_token, counts
+
+
 def dispatch(x: np.ndarray, slot_token: np.ndarray, counts: np.ndarray, dtype: int):
     T, d = x.shape
     E, C = slot_token.shape

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libetr_hip.so")
 
 EXPORTS = ("etr_workspace_bytes", "etr_select_workspace_bytes", "etr_ffn_workspace_bytes", "etr_status_string",
            "etr_route", "etr_select", "etr_dispatch", "etr_expert_ffn", "etr_combine", "etr_moe_forward",
-           "etr_moe_forward_profiled", "etr_select_bounded", "etr_stats_workspace_bytes", "etr_route_stats",
+           "etr_moe_forward_profiled", "etr_select_adaptive", "etr_stats_workspace_bytes", "etr_route_stats",
            "etr_capacity_lower_bound")
 N_STAGE_EVENTS = 7
 STAGE_NAMES = ("route", "select", "dispatch", "ffn_gate_up", "ffn_down", "combine")
@@ -62,7 +62,7 @@ def load_library():
         "etr_expert_ffn": [cp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "etr_combine": [cp, vp, vp, vp, vp, vp],
         "etr_moe_forward": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
-        "etr_select_bounded": [cp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "etr_select_adaptive": [cp, vp, vp, ctypes.c_float, vp, vp, vp, vp, vp, sz, vp],
         "etr_route_stats": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "etr_capacity_lower_bound": [cp, vp, vp, vp, vp, sz, vp],
         "etr_moe_forward_profiled": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
@@ -125,10 +125,10 @@ def etr_select(cfg, score, topk_expert, slot_of, slot_token, counts, ws):
                                                    _ptr(slot_token), _ptr(counts), _ptr(ws), _nbytes(ws), _stream()))
 
 
-def etr_select_bounded(cfg, score, capacity_dev, topk_expert, slot_of, slot_token, counts, ws):
-    _check("etr_select_bounded", load_library().etr_select_bounded(
-        ctypes.byref(cfg), _ptr(score), _ptr(capacity_dev), _ptr(topk_expert), _ptr(slot_of), _ptr(slot_token),
-        _ptr(counts), _ptr(ws), _nbytes(ws), _stream()))
+def etr_select_adaptive(cfg, score, capacity_dev, affinity_sum_threshold, topk_expert, slot_of, slot_token, counts, ws):
+    _check("etr_select_adaptive", load_library().etr_select_adaptive(
+        ctypes.byref(cfg), _ptr(score), _ptr(capacity_dev), ctypes.c_float(affinity_sum_threshold), _ptr(topk_expert),
+        _ptr(slot_of), _ptr(slot_token), _ptr(counts), _ptr(ws), _nbytes(ws), _stream()))
 
 
 def etr_stats_workspace_bytes(cfg: EtrConfig) -> int:

@@ -1,5 +1,6 @@
 // C-ABI layer: host-side argument validation, workspace carving and the stage chain
 // of the whole layer (Sec. Model Architecture, Eqs. 1-6).  Nothing here computes.
+#include <cmath>
 #include <cstdint>
 
 #include "etr_internal.h"
@@ -120,18 +121,26 @@ etr_status etr_select(const etr_config* cfg, const float* score, int32_t* topk_e
     return ETR_OK;
 }
 
-etr_status etr_select_bounded(const etr_config* cfg, const float* score, const int32_t* capacity_dev,
-                              int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts, void* ws,
-                              size_t ws_bytes, void* stream) {
+etr_status etr_select_adaptive(const etr_config* cfg, const float* score, const int32_t* capacity_dev,
+                               float affinity_sum_threshold, int32_t* topk_expert, int32_t* slot_of,
+                               int32_t* slot_token, int32_t* counts, void* ws, size_t ws_bytes, void* stream) {
     etr_status s = check_config(cfg);
     if (s != ETR_OK) return s;
     ETR_REQUIRE_PTR(score); ETR_REQUIRE_PTR(slot_of); ETR_REQUIRE_PTR(slot_token); ETR_REQUIRE_PTR(counts);
     ETR_REQUIRE_PTR(ws); ETR_OPTIONAL_PTR(topk_expert);
-    if (!capacity_dev) return ETR_ERR_NULL;
+    if (capacity_dev && (reinterpret_cast<uintptr_t>(capacity_dev) & 3u)) return ETR_ERR_ALIGN;
+    if (!(affinity_sum_threshold == affinity_sum_threshold)) return ETR_ERR_SHAPE;           // NaN
+    if (cfg->T > (1 << 22) && affinity_sum_threshold > 0.f) return ETR_ERR_UNSUPPORTED;       // fixed-point sum headroom
     if (ws_bytes < select_ws_bytes(cfg->T, cfg->E)) return ETR_ERR_WORKSPACE;
     const SelectWs w = select_ws_carve(ws, cfg->T, cfg->E);
+    long long need = 0;
+    if (affinity_sum_threshold > 0.f) {
+        const double scaled = static_cast<double>(affinity_sum_threshold) * 1073741824.0;
+        need = scaled >= 9.0e18 ? 9000000000000000000ll : llrint(scaled);
+        if (need < 1) need = 1;
+    }
     ETR_HIP(launch_select(*cfg, score, topk_expert, slot_of, slot_token, counts, w, static_cast<hipStream_t>(stream),
-                          capacity_dev));
+                          capacity_dev, need));
     return ETR_OK;
 }
 

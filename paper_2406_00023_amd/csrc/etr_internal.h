@@ -37,7 +37,8 @@ hipError_t launch_route(const etr_config& c, const void* x, const float* w_emb, 
 // select.hip
 hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_expert, int32_t* slot_of,
                          int32_t* slot_token, int32_t* counts, const SelectWs& w, hipStream_t st,
-                         const int32_t* capacity_dev = nullptr);   // optional device-side bound <= c.capacity
+                         const int32_t* capacity_dev = nullptr,   // optional device-side bound <= c.capacity
+                         long long sum_need = 0);   // > 0: affinity-sum threshold in 2^-30 units (adaptive token count)
 // permute.hip
 hipError_t launch_dispatch(const etr_config& c, const void* x, const int32_t* slot_token, const int32_t* counts,
                            void* xp, hipStream_t st);

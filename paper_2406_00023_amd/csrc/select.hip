@@ -94,6 +94,7 @@ template <int IPT>
 __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32_t* __restrict__ keyT, int Tpad, int T,
                                                                     int ipt, int capacity_host, int mode,
                                                                     const int32_t* __restrict__ capacity_dev,
+                                                                    long long sum_need,
                                                                     uint32_t* __restrict__ tau_out,
                                                                     int32_t* __restrict__ need_eq_out,
                                                                     int32_t* __restrict__ pre_gt,
@@ -139,7 +140,58 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
 
     int ncand, d1, d2;
     count3(1u, 0xFFFFFFFFu, 0xFFFFFFFFu, ncand, d1, d2);
-    const int n_keep = ncand < capacity ? ncand : capacity;
+    int n_keep = ncand < capacity ? ncand : capacity;
+
+    // Adaptive token count (Sec. Routing Strategy: "l is determined by a threshold of the sum of
+    // affinity scores"): walking the candidates from the highest affinity down, stop at the first
+    // prefix whose affinity sum reaches the threshold.  Affinities are summed as fixed-point
+    // integers round(clamp(s,-1,1) * 2^30), so the sum of "all candidates with key >= theta" is
+    // exact and order-free, and the prefix length follows from a bisection over theta.
+    if (sum_need > 0 && mode != ETR_MODE_TCR && n_keep > 0) {
+        __shared__ long long red_sum[kSelThreads / kWave];
+        __shared__ int red_cnt[kSelThreads / kWave];
+        // sum and count over the candidates with key >= thr (thr >= key(+0): positive affinities only)
+        auto sum_ge = [&](uint32_t thr, long long& sum, int& cnt) {
+            sum = 0; cnt = 0;
+            auto add = [&](uint32_t key) {
+                if (key >= thr) {
+                    const float sc = __uint_as_float(key & 0x7FFFFFFFu);
+                    sum += llrint(static_cast<double>(fminf(sc, 1.0f)) * 1073741824.0);
+                    ++cnt;
+                }
+            };
+            if constexpr (IPT > 0) {
+#pragma unroll
+                for (int j = 0; j < IPT; ++j) add(keys[j]);
+            } else {
+                for (int idx = tid; idx < T; idx += kSelThreads) add(col[idx]);
+            }
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) { sum += __shfl_xor(sum, m, kWave); cnt += __shfl_xor(cnt, m, kWave); }
+            __syncthreads();
+            if ((tid & (kWave - 1)) == 0) { red_sum[tid / kWave] = sum; red_cnt[tid / kWave] = cnt; }
+            __syncthreads();
+            sum = 0; cnt = 0;
+#pragma unroll
+            for (int w = 0; w < kSelThreads / kWave; ++w) { sum += red_sum[w]; cnt += red_cnt[w]; }
+        };
+        long long s_all; int c_all;
+        sum_ge(0x80000000u, s_all, c_all);
+        if (s_all >= sum_need) {                        // otherwise the positive affinities never get there: take all
+            uint32_t th = 0x80000000u;                  // largest theta with sum_ge(theta) >= need
+            for (int bit = 30; bit >= 0; --bit) {
+                long long sv; int cv;
+                sum_ge(th | (1u << bit), sv, cv);
+                if (sv >= sum_need) th |= 1u << bit;
+            }
+            long long s_gt = 0; int n_gt = 0;
+            if (th != 0xFFFFFFFFu) sum_ge(th + 1u, s_gt, n_gt);
+            const long long q_th = llrint(static_cast<double>(fminf(__uint_as_float(th & 0x7FFFFFFFu), 1.0f)) * 1073741824.0);
+            const long long j = q_th > 0 ? (sum_need - s_gt + q_th - 1) / q_th : 1;
+            const long long ell = n_gt + j;
+            if (ell < n_keep) n_keep = static_cast<int>(ell);
+        }
+    }
 
     uint32_t tau;
     if (n_keep == 0) {
@@ -265,7 +317,7 @@ SelectWs select_ws_carve(void* ws, int T, int E) {
 
 hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_expert, int32_t* slot_of,
                          int32_t* slot_token, int32_t* counts, const SelectWs& w, hipStream_t st,
-                         const int32_t* capacity_dev) {
+                         const int32_t* capacity_dev, long long sum_need) {
     int G = 1;
     while (G < c.E) G <<= 1;
     const long long lanes = static_cast<long long>(c.T) * G;
@@ -288,7 +340,7 @@ hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_
 
 #define ETR_EC(II)                                                                                               \
     hipLaunchKernelGGL(expert_choice_kernel<II>, dim3(c.E), dim3(kSelThreads), 0, st, w.keyT, w.Tpad, c.T, w.ipt, \
-                       c.capacity, c.mode, capacity_dev, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts)
+                       c.capacity, c.mode, capacity_dev, sum_need, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts)
     if (w.ipt <= 4) ETR_EC(4);
     else if (w.ipt <= 16) ETR_EC(16);
     else if (w.ipt <= 64) ETR_EC(64);

@@ -66,7 +66,7 @@ def test_capacity_lower_bound_and_bounded_select(oracle, T, E, d, dmax):
         slot_token = torch.empty(E, cfg_m.capacity, dtype=torch.int32, device="cuda")
         counts = torch.empty(E, dtype=torch.int32, device="cuda")
         sws = B.alloc_workspace(B.etr_select_workspace_bytes(cfg_m))
-        B.etr_select_bounded(cfg_m, Sd, cap, None, slot_of, slot_token, counts, sws)
+        B.etr_select_adaptive(cfg_m, Sd, cap, 0.0, None, slot_of, slot_token, counts, sws)
         torch.cuda.synchronize()
         _, o_so, o_st, o_c = oracle.select(S, shape.k, o_cap, mode)
         np.testing.assert_array_equal(counts.cpu().numpy(), o_c)
@@ -74,3 +74,31 @@ def test_capacity_lower_bound_and_bounded_select(oracle, T, E, d, dmax):
         st = slot_token.cpu().numpy()
         np.testing.assert_array_equal(st[:, :o_cap], o_st)
         assert np.all(st[:, o_cap:] == -1)
+
+
+@pytest.mark.parametrize("T,E,k,C,thr,levels", [(6, 3, 1, 6, 1.6, None), (1000, 8, 2, 300, 5.0, None),
+                                                (5000, 16, 4, 5000, 20.0, 8), (70001, 4, 2, 40000, 900.0, None),
+                                                (3000, 5, 5, 100, 1e9, None), (3000, 5, 2, 3000, 0.01, 3)])
+def test_select_adaptive_token_count(oracle, T, E, k, C, thr, levels):
+    rng = np.random.default_rng(T * 7 + E)
+    if levels:
+        S = (rng.integers(-levels, levels + 1, size=(T, E)) / levels).astype(np.float32)
+    else:
+        S = rng.uniform(-1, 1, (T, E)).astype(np.float32)
+    Sd = torch.from_numpy(S).cuda()
+    for mode in (TCR, ECR, BIDIR):
+        print(f"case adaptive T={T} E={E} k={k} C={C} thr={thr} mode={mode}", flush=True)
+        cfg = B.make_config(_shape(T, E, k, C, mode))
+        slot_of = torch.empty(T, E, dtype=torch.int32, device="cuda")
+        slot_token = torch.empty(E, C, dtype=torch.int32, device="cuda")
+        counts = torch.empty(E, dtype=torch.int32, device="cuda")
+        topk = torch.empty(T, k, dtype=torch.int32, device="cuda")
+        sws = B.alloc_workspace(B.etr_select_workspace_bytes(cfg))
+        B.etr_select_adaptive(cfg, Sd, None, thr, topk, slot_of, slot_token, counts, sws)
+        torch.cuda.synchronize()
+        o_tk, o_so, o_st, o_c = oracle.select_adaptive(S, k, C, mode, thr)
+        np.testing.assert_array_equal(counts.cpu().numpy(), o_c)
+        np.testing.assert_array_equal(slot_of.cpu().numpy(), o_so)
+        np.testing.assert_array_equal(slot_token.cpu().numpy(), o_st)
+        if mode != ECR:
+            np.testing.assert_array_equal(topk.cpu().numpy(), o_tk)

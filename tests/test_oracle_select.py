@@ -185,3 +185,68 @@ def test_rejects_bad_arguments(oracle):
         oracle.select(S, 1, 0, TCR)          # capacity < 1
     # ECR ignores k
     oracle.select(S, 7, 2, ECR)
+
+
+# ---------------------------------------------------------------------------------------
+# adaptive token count: "l is determined by a threshold of the sum of affinity scores"
+# ---------------------------------------------------------------------------------------
+def _fixed(s):
+    """round(clamp(s, -1, 1) * 2^30), ties to even: sums of these integers are order-independent."""
+    return int(np.rint(np.float64(min(1.0, max(-1.0, float(s)))) * 2.0 ** 30))
+
+
+def _adaptive_brute(S, e, cands, C, thr):
+    """Independent statement: sort by (score desc, index asc); l = first prefix whose fixed-point
+    affinity sum reaches the threshold, all candidates if the positive affinities never do."""
+    order = sorted(cands, key=lambda t: (-float(S[t, e]), t))
+    need = int(np.rint(np.float64(np.float32(thr)) * 2.0 ** 30))
+    run, ell = 0, len(order)
+    for m, t in enumerate(order):
+        if not S[t, e] > 0:
+            break
+        run += _fixed(S[t, e])
+        if run >= need:
+            ell = m + 1
+            break
+    return sorted(order[:min(C, ell)])
+
+
+def test_adaptive_worked_example(oracle):
+    g = load_golden("select_worked_example.json")
+    S = np.array(g["score"], np.float32)
+    # ECR, capacity 6 (never binding), threshold 1.6:
+    #   expert 0: .9 + .8 = 1.7 >= 1.6 -> 2 tokens; expert 1: .7 + .6 + .5 = 1.8 -> 3 tokens (ties .5/.5: token 3 first)
+    #   expert 2: .5 + .4 + .3 + .2 + .1 = 1.5 never reaches 1.6 -> all 6
+    _, _, st, c = oracle.select_adaptive(S, 1, 6, ECR, 1.6)
+    assert c.tolist() == [2, 3, 6]
+    assert st[0, :2].tolist() == [0, 1] and st[1, :3].tolist() == [1, 2, 3]
+    # the capacity still binds: with C = 2 expert 1 and 2 keep two
+    _, _, st, c = oracle.select_adaptive(S, 1, 2, ECR, 1.6)
+    assert c.tolist() == [2, 2, 2]
+    # threshold off or unreachable: the plain selection; tiny threshold: one token each
+    for thr in (0.0, -1.0):
+        np.testing.assert_array_equal(oracle.select_adaptive(S, 2, 2, BIDIR, thr)[1], oracle.select(S, 2, 2, BIDIR)[1])
+    assert oracle.select_adaptive(S, 1, 6, ECR, 0.05)[3].tolist() == [1, 1, 1]
+    # token choice keeps by position: the threshold does not apply
+    np.testing.assert_array_equal(oracle.select_adaptive(S, 2, 2, TCR, 0.3)[1], oracle.select(S, 2, 2, TCR)[1])
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_adaptive_brute_force(oracle, seed):
+    rng = np.random.default_rng(300 + seed)
+    T, E = int(rng.integers(5, 40)), int(rng.integers(2, 6))
+    k = int(rng.integers(1, E + 1))
+    C = int(rng.integers(1, T + 2))
+    S = _scores(rng, T, E, 4 if seed % 2 else None)
+    thr = float(rng.uniform(0.2, 3.0))
+    order = np.lexsort((np.arange(E)[None, :].repeat(T, 0), -S.astype(np.float64)), axis=1)
+    chose = np.zeros((T, E), bool)
+    np.put_along_axis(chose, order[:, :k], True, axis=1)
+    for mode in (ECR, BIDIR):
+        _, slot_of, slot_token, counts = oracle.select_adaptive(S, k, C, mode, thr)
+        check_permutation_tables(T, E, C, slot_of, slot_token, counts)
+        plain = oracle.select(S, k, C, mode)[1] >= 0
+        assert np.all((slot_of >= 0) <= plain)                   # a prefix of what the capacity alone would keep
+        for e in range(E):
+            cands = list(range(T)) if mode == ECR else list(np.flatnonzero(chose[:, e]))
+            assert list(slot_token[e, :counts[e]]) == _adaptive_brute(S, e, cands, C, thr), (mode, e)
