@@ -30,6 +30,7 @@
 //   etr_ref_moe_forward the chain of the above
 //   etr_ref_route_stats expert load distribution, mean gate and KL(D_c || D_l) of Sec. Locality Loss
 //   etr_ref_capacity_lower_bound  C_min of the Remark in Sec. Dynamic Lower Bound Module
+//   etr_ref_backward_tokens / _hidden_units   the chain rule through Eqs. 1-6 with the routing tables fixed
 //
 // Readings of points the paper leaves open (all listed in the design notes):
 // ties go to the lowest index; slots inside an expert are in ascending token
@@ -473,6 +474,212 @@ int etr_ref_capacity_lower_bound(int T, int E, int d, const float* score, float*
     *dmax_out = mx;
     *capacity_out = c;
     return 0;
+}
+
+// ---------------------------------------------------------------------------
+// Backward of the layer: the chain rule applied to Eqs. 1-6 with the routing tables held fixed
+// (which tokens an expert keeps is a piecewise-constant function of the input; the gate vectors
+// of Eq. 3 are constants of the method, so there is no gradient for them).  With
+//   out[t] = sum_{e kept t} gate[t][e] * y_te,   y_te = Wd_e h_te,   h_te = SiLU(a_te) .* b_te,
+//   a_te = Wg_e x_t,  b_te = Wu_e x_t,  gate[t][.] = softmax(score[t][.]),  score = Eq. 4,
+// and an upstream gradient dout[T][d]:
+//   dgate[t][e]  = <dout[t], y_te>            (0 for pairs that are not kept)
+//   dscore[t][e] = gate[t][e] * (dgate[t][e] - sum_e' dgate[t][e'] gate[t][e'])
+//   dy_te = gate[t][e] dout[t];  dh = Wd^T dy;  da = dh .* b .* SiLU'(a);  db = dh .* SiLU(a)
+//   dWd_e += dy h^T;  dWg_e += da x^T;  dWu_e += db x^T
+//   dx[t] = sum_e (Wg_e^T da + Wu_e^T db) + sum_e dscore[t][e] * d score[t][e] / d x[t]
+// Everything is evaluated in double from the stored inputs; nothing is rounded.
+// The work is split so that any part can be evaluated on its own for sampled checks at sizes
+// where the whole gradient is out of reach: per token (dx, dgate, dscore) and per hidden unit
+// (row j of dWg_e and dWu_e, column j of dWd_e).
+// ---------------------------------------------------------------------------
+namespace {
+
+struct TokenRoute {          // routing quantities of one token, all in double
+    std::vector<double> g, score, gate;
+    double xx = 0, gg = 0;
+};
+
+void route_token_double(int t, int d, int E, int D, int dtype, int cos_mode, const void* x, const float* w_emb,
+                        const std::vector<double>& wnorm, TokenRoute& r) {
+    const int P = d / D;
+    r.g.assign(P, 0.0); r.score.assign(E, 0.0); r.gate.assign(E, 0.0);
+    r.xx = 0; r.gg = 0;
+    for (int p = 0; p < P; ++p) {
+        double s = 0;
+        for (int j = 0; j < D; ++j) {
+            double v = load_elem(x, dtype, (size_t)t * d + (size_t)p * D + j);
+            s += v; r.xx += v * v;
+        }
+        r.g[p] = s / D;
+        r.gg += r.g[p] * r.g[p];
+    }
+    double mx = -INFINITY;
+    for (int e = 0; e < E; ++e) {
+        double dot = 0;
+        for (int p = 0; p < P; ++p) dot += r.g[p] * double(w_emb[e * (size_t)P + p]);
+        double den = (cos_mode == COS_FULL ? std::sqrt(r.xx) : std::sqrt(r.gg)) * wnorm[e];
+        double num = (cos_mode == COS_FULL) ? std::sqrt((double)D) * dot : dot;
+        r.score[e] = den > 0 ? num / den : 0.0;
+        mx = std::max(mx, r.score[e]);
+    }
+    double z = 0;
+    for (int e = 0; e < E; ++e) z += std::exp(r.score[e] - mx);
+    for (int e = 0; e < E; ++e) r.gate[e] = std::exp(r.score[e] - mx) / z;
+}
+
+std::vector<double> embedding_norms(int E, int P, const float* w_emb) {
+    std::vector<double> wnorm(E);
+    for (int e = 0; e < E; ++e) {
+        double s = 0;
+        for (int p = 0; p < P; ++p) s += double(w_emb[e * (size_t)P + p]) * double(w_emb[e * (size_t)P + p]);
+        wnorm[e] = std::sqrt(s);
+    }
+    return wnorm;
+}
+
+inline double sigmoid(double a) { return 1.0 / (1.0 + std::exp(-a)); }
+
+}  // namespace
+
+// Per-token part of the backward: for each listed token, dx (d values), dgate and dscore (E values each).
+int etr_ref_backward_tokens(int T, int d, int E, int D, int H, int dtype, int cos_mode,
+                            const void* x, const float* w_emb, const void* w_gate, const void* w_up,
+                            const void* w_down, const int32_t* slot_of, const void* dout,
+                            const int32_t* tokens, int n_tokens, double* dx, double* dgate, double* dscore) {
+    if (d <= 0 || E <= 0 || D <= 0 || d % D != 0 || H <= 0) return 2;
+    const int P = d / D;
+    const std::vector<double> wnorm = embedding_norms(E, P, w_emb);
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int i = 0; i < n_tokens; ++i) {
+        const int t = tokens[i];
+        if (t < 0 || t >= T) { bad = 1; continue; }
+        TokenRoute r;
+        route_token_double(t, d, E, D, dtype, cos_mode, x, w_emb, wnorm, r);
+        std::vector<double> xt(d), go(d), acc(d, 0.0), a(H), b(H), h(H), dh(H), dg(E, 0.0);
+        for (int j = 0; j < d; ++j) {
+            xt[j] = load_elem(x, dtype, (size_t)t * d + j);
+            go[j] = load_elem(dout, dtype, (size_t)t * d + j);
+        }
+        for (int e = 0; e < E; ++e) {
+            if (slot_of[(size_t)t * E + e] < 0) continue;
+            for (int u = 0; u < H; ++u) {
+                double sa = 0, sb = 0;
+                const size_t base = ((size_t)e * H + u) * d;
+                for (int j = 0; j < d; ++j) {
+                    sa += load_elem(w_gate, dtype, base + j) * xt[j];
+                    sb += load_elem(w_up, dtype, base + j) * xt[j];
+                }
+                a[u] = sa; b[u] = sb; h[u] = sa * sigmoid(sa) * sb; dh[u] = 0;
+            }
+            double dgte = 0;
+            for (int j = 0; j < d; ++j) {
+                const size_t base = ((size_t)e * d + j) * H;
+                double y = 0;
+                for (int u = 0; u < H; ++u) {
+                    const double w = load_elem(w_down, dtype, base + u);
+                    y += w * h[u];
+                    dh[u] += w * r.gate[e] * go[j];
+                }
+                dgte += go[j] * y;
+            }
+            dg[e] = dgte;
+            for (int u = 0; u < H; ++u) {
+                const double sg = sigmoid(a[u]);
+                const double da = dh[u] * b[u] * (sg * (1.0 + a[u] * (1.0 - sg)));   // d/da [a sigma(a)]
+                const double db = dh[u] * a[u] * sg;
+                const size_t base = ((size_t)e * H + u) * d;
+                for (int j = 0; j < d; ++j)
+                    acc[j] += load_elem(w_gate, dtype, base + j) * da + load_elem(w_up, dtype, base + j) * db;
+            }
+        }
+        // softmax backward, then the affinity's own derivative
+        double mix = 0;
+        for (int e = 0; e < E; ++e) mix += dg[e] * r.gate[e];
+        std::vector<double> ds(E);
+        for (int e = 0; e < E; ++e) ds[e] = r.gate[e] * (dg[e] - mix);
+        const double nx = std::sqrt(r.xx), ng = std::sqrt(r.gg);
+        for (int e = 0; e < E; ++e) {
+            if (ds[e] == 0.0 || wnorm[e] == 0.0) continue;
+            if (cos_mode == COS_FULL) {
+                if (nx == 0.0) continue;
+                // score = sqrt(D) <g,w> / (|x| |w|),  g_p = mean of group p
+                for (int j = 0; j < d; ++j) {
+                    const double w = double(w_emb[e * (size_t)P + j / D]);
+                    acc[j] += ds[e] * (std::sqrt((double)D) * w / (D * nx * wnorm[e]) - r.score[e] * xt[j] / r.xx);
+                }
+            } else {
+                if (ng == 0.0) continue;
+                // score = <g,w> / (|g| |w|); d g_p / d x_j = 1/D inside the group
+                for (int j = 0; j < d; ++j) {
+                    const int p = j / D;
+                    const double w = double(w_emb[e * (size_t)P + p]);
+                    acc[j] += ds[e] * (w / (ng * wnorm[e]) - r.score[e] * r.g[p] / r.gg) / D;
+                }
+            }
+        }
+        for (int j = 0; j < d; ++j) dx[(size_t)i * d + j] = acc[j];
+        if (dgate) for (int e = 0; e < E; ++e) dgate[(size_t)i * E + e] = dg[e];
+        if (dscore) for (int e = 0; e < E; ++e) dscore[(size_t)i * E + e] = ds[e];
+    }
+    return bad ? 2 : 0;
+}
+
+// Per-hidden-unit part of the backward: for unit u = unit_index[i] of expert e = unit_expert[i],
+// row u of dWg_e and of dWu_e (d values each) and column u of dWd_e (d values).
+int etr_ref_backward_hidden_units(int T, int d, int E, int D, int H, int dtype, int cos_mode,
+                                  const void* x, const float* w_emb, const void* w_gate, const void* w_up,
+                                  const void* w_down, const int32_t* slot_of, const void* dout,
+                                  const int32_t* unit_expert, const int32_t* unit_index, int n_units,
+                                  double* dwg_rows, double* dwu_rows, double* dwd_cols) {
+    if (d <= 0 || E <= 0 || D <= 0 || d % D != 0 || H <= 0) return 2;
+    const int P = d / D;
+    const std::vector<double> wnorm = embedding_norms(E, P, w_emb);
+    // gates of every token once (double)
+    std::vector<double> gate((size_t)T * E);
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        TokenRoute r;
+        route_token_double(t, d, E, D, dtype, cos_mode, x, w_emb, wnorm, r);
+        for (int e = 0; e < E; ++e) gate[(size_t)t * E + e] = r.gate[e];
+    }
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic)
+    for (int i = 0; i < n_units; ++i) {
+        const int e = unit_expert[i], u = unit_index[i];
+        if (e < 0 || e >= E || u < 0 || u >= H) { bad = 1; continue; }
+        std::vector<double> gw(d, 0.0), uw(d, 0.0), dw(d, 0.0);
+        const size_t wrow = ((size_t)e * H + u) * d;
+        for (int t = 0; t < T; ++t) {
+            if (slot_of[(size_t)t * E + e] < 0) continue;
+            double a = 0, b = 0, dh = 0;
+            for (int j = 0; j < d; ++j) {
+                const double xv = load_elem(x, dtype, (size_t)t * d + j);
+                a += load_elem(w_gate, dtype, wrow + j) * xv;
+                b += load_elem(w_up, dtype, wrow + j) * xv;
+            }
+            const double gt = gate[(size_t)t * E + e];
+            for (int j = 0; j < d; ++j)
+                dh += load_elem(w_down, dtype, ((size_t)e * d + j) * H + u) * gt * load_elem(dout, dtype, (size_t)t * d + j);
+            const double sg = sigmoid(a);
+            const double h = a * sg * b;
+            const double da = dh * b * (sg * (1.0 + a * (1.0 - sg)));
+            const double db = dh * a * sg;
+            for (int j = 0; j < d; ++j) {
+                const double xv = load_elem(x, dtype, (size_t)t * d + j);
+                gw[j] += da * xv;
+                uw[j] += db * xv;
+                dw[j] += gt * load_elem(dout, dtype, (size_t)t * d + j) * h;
+            }
+        }
+        for (int j = 0; j < d; ++j) {
+            dwg_rows[(size_t)i * d + j] = gw[j];
+            dwu_rows[(size_t)i * d + j] = uw[j];
+            dwd_cols[(size_t)i * d + j] = dw[j];
+        }
+    }
+    return bad ? 2 : 0;
 }
 
 // helpers exposed for the tests

@@ -184,6 +184,50 @@ def capacity_lower_bound(score: np.ndarray, d: int):
     return float(dm[0]), int(c[0])
 
 
+def backward_tokens(x, w_emb, w_gate, w_up, w_down, slot_of, dout, tokens, *, D: int, dtype: int,
+                    cos_mode: int = COS_FULL):
+    """Per-token part of the layer's backward (routing tables fixed): dx[n][d], dgate[n][E], dscore[n][E], float64."""
+    T, d = x.shape
+    E, H = w_gate.shape[0], w_gate.shape[1]
+    tokens = np.ascontiguousarray(tokens, np.int32)
+    n = int(tokens.shape[0])
+    assert slot_of.dtype == np.int32 and slot_of.shape == (T, E) and dout.shape == (T, d) and dout.dtype == x.dtype
+    dx, dg, ds = np.empty((n, d), np.float64), np.empty((n, E), np.float64), np.empty((n, E), np.float64)
+    _check(lib().etr_ref_backward_tokens(T, d, E, D, H, dtype, cos_mode, _p(x), _p(w_emb), _p(w_gate), _p(w_up),
+                                         _p(w_down), _p(slot_of), _p(dout), _p(tokens), n, _p(dx), _p(dg), _p(ds)),
+           "backward_tokens")
+    return dx, dg, ds
+
+
+def backward_hidden_units(x, w_emb, w_gate, w_up, w_down, slot_of, dout, unit_expert, unit_index, *, D: int,
+                          dtype: int, cos_mode: int = COS_FULL):
+    """Per-hidden-unit part of the backward: rows of dWg and dWu and columns of dWd, each [n][d] float64."""
+    T, d = x.shape
+    E, H = w_gate.shape[0], w_gate.shape[1]
+    ue = np.ascontiguousarray(unit_expert, np.int32)
+    ui = np.ascontiguousarray(unit_index, np.int32)
+    n = int(ue.shape[0])
+    assert ui.shape == ue.shape and slot_of.dtype == np.int32 and dout.dtype == x.dtype
+    gw, uw, dw = (np.empty((n, d), np.float64) for _ in range(3))
+    _check(lib().etr_ref_backward_hidden_units(T, d, E, D, H, dtype, cos_mode, _p(x), _p(w_emb), _p(w_gate), _p(w_up),
+                                               _p(w_down), _p(slot_of), _p(dout), _p(ue), _p(ui), n, _p(gw), _p(uw),
+                                               _p(dw)), "backward_hidden_units")
+    return gw, uw, dw
+
+
+def moe_backward(x, w_emb, w_gate, w_up, w_down, slot_of, dout, *, D: int, dtype: int, cos_mode: int = COS_FULL):
+    """Whole gradient (small sizes only): dict dx[T][d], dgate, dscore [T][E], dw_gate, dw_up [E][H][d], dw_down [E][d][H]."""
+    T, d = x.shape
+    E, H = w_gate.shape[0], w_gate.shape[1]
+    dx, dg, ds = backward_tokens(x, w_emb, w_gate, w_up, w_down, slot_of, dout, np.arange(T), D=D, dtype=dtype,
+                                 cos_mode=cos_mode)
+    ue, ui = np.repeat(np.arange(E), H), np.tile(np.arange(H), E)
+    gw, uw, dw = backward_hidden_units(x, w_emb, w_gate, w_up, w_down, slot_of, dout, ue, ui, D=D, dtype=dtype,
+                                       cos_mode=cos_mode)
+    return dict(dx=dx, dgate=dg, dscore=ds, dw_gate=gw.reshape(E, H, d), dw_up=uw.reshape(E, H, d),
+                dw_down=np.ascontiguousarray(dw.reshape(E, H, d).transpose(0, 2, 1)))
+
+
 def bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
     """uint16 bf16 bit patterns -> float64 values (pure bit reinterpretation)."""
     return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
