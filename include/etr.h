@@ -187,6 +187,36 @@ etr_status etr_route_stats(const etr_config* cfg, const float* gate, const int32
 etr_status etr_capacity_lower_bound(const etr_config* cfg, const float* score, float* dmax,
                                     int32_t* capacity, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- backward of the layer ---------------------------------------------------------------- */
+
+/* Scratch of etr_moe_backward (transposed weights, recomputed pre-activations, transposed
+ * per-row gradients, the permuted input gradient). 0 for an invalid config. */
+size_t etr_backward_workspace_bytes(const etr_config* cfg);
+
+/* Gradient of the layer of Eqs. 1-6 for an upstream gradient dout, with the routing tables of the
+ * forward call held fixed (the kept sets are piecewise constant in x; the gate vectors of Eq. 3 are
+ * constants of the method and get no gradient).  With a = Wg x, b = Wu x, h = SiLU(a) .* b,
+ * y = Wd h, out[t] = sum_{e kept t} gate[t][e] y_te:
+ *   dgate[t][e]  = <dout[t], y_te>  (0 where the pair is not kept)
+ *   dscore[t][e] = gate[t][e] (dgate[t][e] - sum_e' dgate[t][e'] gate[t][e'])     (softmax of Eq. 1)
+ *   dw_down[e] = sum_t gate dout[t] h^T;  dw_gate[e] = sum_t da x_t^T;  dw_up[e] = sum_t db x_t^T
+ *   dx[t] = sum_e (Wg^T da + Wu^T db) + sum_e dscore[t][e] d score[t][e] / d x[t]  (Eq. 4 differentiated,
+ *           in the form selected by cfg->cos)
+ * The pre-activations are recomputed from x (nothing but the routing outputs is kept from forward).
+ *   in : x [T][d], w_emb [E][d/D] fp32, w_gate, w_up [E][H][d], w_down [E][d][H], dout [T][d] (dtype);
+ *        score, gate [T][E] fp32, slot_of [T][E], slot_token [E][capacity], counts [E]: outputs of the
+ *        forward call (etr_route + etr_select, or etr_moe_forward) for the same x and cfg
+ *   out: dx [T][d], dw_gate, dw_up [E][H][d], dw_down [E][d][H] in the layer's dtype, overwritten
+ *        (not accumulated); dgate, dscore [T][E] fp32, optional (may be NULL)
+ * bf16: products accumulate in fp32; a, b, W_d^T dout and the per-row gradients are rounded to bf16
+ * once each between the stages.  E * (d/D) * 4 bytes must fit in 120 KiB (ETR_ERR_UNSUPPORTED). */
+etr_status etr_moe_backward(const etr_config* cfg, const void* x, const float* w_emb,
+                            const void* w_gate, const void* w_up, const void* w_down,
+                            const float* score, const float* gate, const int32_t* slot_of,
+                            const int32_t* slot_token, const int32_t* counts, const void* dout,
+                            void* dx, void* dw_gate, void* dw_up, void* dw_down,
+                            float* dgate, float* dscore, void* ws, size_t ws_bytes, void* stream);
+
 /* etr_moe_forward with stage boundaries marked on the stream, for measurement.
  *   events: HOST array of ETR_N_STAGE_EVENTS hipEvent_t handles (as void*), created by the
  *   caller; an entry may be NULL (that boundary is then not marked: each recorded event costs a few

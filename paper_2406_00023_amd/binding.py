@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libetr_hip.so")
 EXPORTS = ("etr_workspace_bytes", "etr_select_workspace_bytes", "etr_ffn_workspace_bytes", "etr_status_string",
            "etr_route", "etr_select", "etr_dispatch", "etr_expert_ffn", "etr_combine", "etr_moe_forward",
            "etr_moe_forward_profiled", "etr_select_adaptive", "etr_stats_workspace_bytes", "etr_route_stats",
-           "etr_capacity_lower_bound")
+           "etr_capacity_lower_bound", "etr_backward_workspace_bytes", "etr_moe_backward")
 N_STAGE_EVENTS = 7
 STAGE_NAMES = ("route", "select", "dispatch", "ffn_gate_up", "ffn_down", "combine")
 
@@ -50,7 +50,7 @@ def load_library():
     lib = ctypes.CDLL(LIB_PATH)
     vp, sz, cp = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(EtrConfig)
     for name in ("etr_workspace_bytes", "etr_select_workspace_bytes", "etr_ffn_workspace_bytes",
-                 "etr_stats_workspace_bytes"):
+                 "etr_stats_workspace_bytes", "etr_backward_workspace_bytes"):
         getattr(lib, name).restype = sz
         getattr(lib, name).argtypes = [cp]
     lib.etr_status_string.restype = ctypes.c_char_p
@@ -65,6 +65,7 @@ def load_library():
         "etr_select_adaptive": [cp, vp, vp, ctypes.c_float, vp, vp, vp, vp, vp, sz, vp],
         "etr_route_stats": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "etr_capacity_lower_bound": [cp, vp, vp, vp, vp, sz, vp],
+        "etr_moe_backward": [cp] + [vp] * 18 + [sz, vp],
         "etr_moe_forward_profiled": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
                                      ctypes.POINTER(ctypes.c_void_p)],
     }
@@ -144,6 +145,18 @@ def etr_route_stats(cfg, gate, slot_of, counts, target, load_frac, mean_gate, kl
 def etr_capacity_lower_bound(cfg, score, dmax, capacity, ws):
     _check("etr_capacity_lower_bound", load_library().etr_capacity_lower_bound(
         ctypes.byref(cfg), _ptr(score), _ptr(dmax), _ptr(capacity), _ptr(ws), _nbytes(ws), _stream()))
+
+
+def etr_backward_workspace_bytes(cfg: EtrConfig) -> int:
+    return int(load_library().etr_backward_workspace_bytes(ctypes.byref(cfg)))
+
+
+def etr_moe_backward(cfg, x, w_emb, w_gate, w_up, w_down, score, gate, slot_of, slot_token, counts, dout, dx, dw_gate,
+                     dw_up, dw_down, ws, dgate=None, dscore=None):
+    _check("etr_moe_backward", load_library().etr_moe_backward(
+        ctypes.byref(cfg), _ptr(x), _ptr(w_emb), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(score), _ptr(gate),
+        _ptr(slot_of), _ptr(slot_token), _ptr(counts), _ptr(dout), _ptr(dx), _ptr(dw_gate), _ptr(dw_up), _ptr(dw_down),
+        _ptr(dgate), _ptr(dscore), _ptr(ws), _nbytes(ws), _stream()))
 
 
 def etr_dispatch(cfg, x, slot_token, counts, xp):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libetr_hip.so")
-SOURCES = ["api.hip", "route.hip", "select.hip", "permute.hip", "ffn.hip", "stats.hip"]
+SOURCES = ["api.hip", "route.hip", "select.hip", "permute.hip", "ffn.hip", "stats.hip", "backward.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

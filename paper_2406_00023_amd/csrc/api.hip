@@ -174,6 +174,30 @@ etr_status etr_capacity_lower_bound(const etr_config* cfg, const float* score, f
     return ETR_OK;
 }
 
+size_t etr_backward_workspace_bytes(const etr_config* cfg) {
+    if (check_config(cfg) != ETR_OK) return 0;
+    return backward_ws_bytes(*cfg);
+}
+
+etr_status etr_moe_backward(const etr_config* cfg, const void* x, const float* w_emb, const void* w_gate,
+                            const void* w_up, const void* w_down, const float* score, const float* gate,
+                            const int32_t* slot_of, const int32_t* slot_token, const int32_t* counts,
+                            const void* dout, void* dx, void* dw_gate, void* dw_up, void* dw_down, float* dgate,
+                            float* dscore, void* ws, size_t ws_bytes, void* stream) {
+    etr_status s = check_config(cfg);
+    if (s != ETR_OK) return s;
+    ETR_REQUIRE_PTR(x); ETR_REQUIRE_PTR(w_emb); ETR_REQUIRE_PTR(w_gate); ETR_REQUIRE_PTR(w_up); ETR_REQUIRE_PTR(w_down);
+    ETR_REQUIRE_PTR(score); ETR_REQUIRE_PTR(gate); ETR_REQUIRE_PTR(slot_of); ETR_REQUIRE_PTR(slot_token);
+    ETR_REQUIRE_PTR(counts); ETR_REQUIRE_PTR(dout); ETR_REQUIRE_PTR(dx); ETR_REQUIRE_PTR(dw_gate);
+    ETR_REQUIRE_PTR(dw_up); ETR_REQUIRE_PTR(dw_down); ETR_REQUIRE_PTR(ws);
+    ETR_OPTIONAL_PTR(dgate); ETR_OPTIONAL_PTR(dscore);
+    if (static_cast<size_t>(cfg->E) * (cfg->d / cfg->D) * 4 > 120 * 1024) return ETR_ERR_UNSUPPORTED;
+    if (ws_bytes < backward_ws_bytes(*cfg)) return ETR_ERR_WORKSPACE;
+    ETR_HIP(launch_moe_backward(*cfg, x, w_emb, w_gate, w_up, w_down, score, gate, slot_of, slot_token, counts, dout, dx,
+                                dw_gate, dw_up, dw_down, dgate, dscore, ws, static_cast<hipStream_t>(stream)));
+    return ETR_OK;
+}
+
 etr_status etr_dispatch(const etr_config* cfg, const void* x, const int32_t* slot_token, const int32_t* counts,
                         void* xp, void* stream) {
     etr_status s = check_config(cfg);

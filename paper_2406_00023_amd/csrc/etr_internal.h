@@ -54,6 +54,31 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
 // (then xp is never materialised by the fused forward).
 bool ffn_can_gather(const etr_config& c);
 
+// General grouped product of ffn.hip, used by the backward pass:
+//   C[g][m][n] = sum_k A[g][m][k] * B[g][n][k]   (both operands contiguous along k)
+// A is [G][M][lda] (or, with row_index[G][M], row row_index[g][m] of one [a_rows][lda] matrix),
+// B0/B1 are [G][N][ldb], C/C2 are [G][M][N], all of the layer's dtype.  m_counts (optional) bounds the
+// rows of each group, k_counts (optional) its contraction length: it is rounded up to a multiple of
+// 64 and the operands must hold zeros in that padding.
+enum GemmEpilogue { GEMM_PLAIN = 0, GEMM_SWIGLU = 1, GEMM_DUAL = 2 };   // C = A B0^T | SiLU(A B0^T) .* (A B1^T) | both products
+struct GroupedGemm {
+    const void* A; const void* B0; const void* B1;
+    void* C; void* C2;
+    const int32_t* m_counts; const int32_t* k_counts; const int32_t* row_index;
+    int G, M, N, K, lda, ldb, a_rows;
+    int epilogue;
+    int dtype;
+};
+hipError_t launch_grouped_gemm(const GroupedGemm& g, hipStream_t st);
+
+// backward.hip
+size_t backward_ws_bytes(const etr_config& c);
+hipError_t launch_moe_backward(const etr_config& c, const void* x, const float* w_emb, const void* w_gate,
+                               const void* w_up, const void* w_down, const float* score, const float* gate,
+                               const int32_t* slot_of, const int32_t* slot_token, const int32_t* counts,
+                               const void* dout, void* dx, void* dw_gate, void* dw_up, void* dw_down,
+                               float* dgate, float* dscore, void* ws, hipStream_t st);
+
 // stats.hip
 size_t stats_ws_bytes(int T, int E);
 hipError_t launch_route_stats(const etr_config& c, const float* gate, const int32_t* slot_of, const int32_t* counts,

@@ -30,7 +30,19 @@ struct GemmParams {
     const int32_t* row_index;   // optional [E][capacity]: A row m of expert e is row row_index[e][m] of A
     int k_stagger;              // pipelined kernels: workgroup j of an XCD starts its K loop (j % 32) * k_stagger tiles in
     int a_rows;                 // rows of A that row_index may name (indices are clamped into [0, a_rows))
+    int lda = 0, ldb = 0;       // row strides of A and B in elements (0: K)
+    const int32_t* k_counts = nullptr;   // optional per-group contraction length; it is rounded up to a multiple
+                                         // of 64 (at most K) and the operands must hold zeros in that padding
+    void* C2 = nullptr;         // DUAL epilogue: the B1 product goes here, the B0 product to C, no activation
 };
+
+// rows of group e (counts may be absent: every group has `capacity` rows) and its contraction length
+__device__ __forceinline__ int group_rows(const GemmParams& p, int e) {
+    return p.counts ? min(p.counts[e], p.capacity) : p.capacity;
+}
+__device__ __forceinline__ int group_k(const GemmParams& p, int e) {
+    return p.k_counts ? min((max(p.k_counts[e], 0) + 63) & ~63, p.K) : p.K;
+}
 
 __device__ __forceinline__ uint32_t f2bf(float f) {            // fp32 -> bf16 bits, round to nearest even
     uint32_t u = __float_as_uint(f);
@@ -75,7 +87,7 @@ inline long long plan_tiles(GemmParams& p, int BM, int BN) {
 // ---------------------------------------------------------------------------------------
 // bf16 MFMA grouped GEMM:  C[e][m][n] = sum_k A[e][m][k] * B[e][n][k]   (+ SwiGLU epilogue)
 // ---------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int WGM, int WGN, bool GLU, int SWZ>
+template <int BM, int BN, int BK, int WGM, int WGN, bool GLU, int SWZ, bool DUAL = false>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) {
     constexpr int NTH = WGM * WGN * 64;
     constexpr int BROWS = GLU ? 2 * BN : BN;       // weight rows staged per tile
@@ -93,16 +105,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
 
     int e, mt, nt;
     if (!decode_tile(p, e, mt, nt)) return;
-    const int count = min(p.counts[e], p.capacity);
+    const int count = group_rows(p, e);
     const int m0 = mt * BM, n0 = nt * BN;
     if (m0 >= count) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WGN) * WTM, wn0 = (wave % WGN) * WTN;
-    const int K = p.K;
-    const uint4* Ag = reinterpret_cast<const uint4*>(p.A) + static_cast<size_t>(e) * p.capacity * (K / 8);
-    const uint4* B0g = reinterpret_cast<const uint4*>(p.B0) + static_cast<size_t>(e) * p.N * (K / 8);
-    const uint4* B1g = GLU ? reinterpret_cast<const uint4*>(p.B1) + static_cast<size_t>(e) * p.N * (K / 8) : nullptr;
+    const int K = group_k(p, e);
+    const int LA = (p.lda ? p.lda : p.K) / 8, LB = (p.ldb ? p.ldb : p.K) / 8;     // 16-byte chunks per operand row
+    const uint4* Ag = reinterpret_cast<const uint4*>(p.A) + (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * LA);
+    const uint4* B0g = reinterpret_cast<const uint4*>(p.B0) + static_cast<size_t>(e) * p.N * LB;
+    const uint4* B1g = GLU ? reinterpret_cast<const uint4*>(p.B1) + static_cast<size_t>(e) * p.N * LB : nullptr;
 
     // per-thread staging slots: chunk q -> (row, ck)
     const uint4* a_src[A_CH];
@@ -113,7 +126,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
         const int q = tid + i * NTH, row = q / CPR, ck = q % CPR;
         int m = m0 + row;
         m = m < p.capacity ? m : p.capacity - 1;                   // stay inside the buffer; such rows are never stored
-        a_src[i] = Ag + static_cast<size_t>(m) * (K / 8) + ck;
+        if (p.row_index) m = min(max(p.row_index[static_cast<size_t>(e) * p.capacity + m], 0), p.a_rows - 1);
+        a_src[i] = Ag + static_cast<size_t>(m) * LA + ck;
         a_dst[i] = row * CPR + (ck ^ ((row >> SWZ) & (CPR - 1)));
         a_ck[i] = ck;
     }
@@ -123,7 +137,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
         const bool up = GLU && row >= BN;
         int n = n0 + (up ? row - BN : row);
         n = n < p.N ? n : p.N - 1;
-        b_src[i] = (up ? B1g : B0g) + static_cast<size_t>(n) * (K / 8) + ck;
+        b_src[i] = (up ? B1g : B0g) + static_cast<size_t>(n) * LB + ck;
         b_dst[i] = row * CPR + (ck ^ ((row >> SWZ) & (CPR - 1)));
         b_ck[i] = ck;
     }
@@ -157,7 +171,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
     };
 
     const int KT = (K + BK - 1) / BK;
-    load_global(0);
+    load_global(0);                                 // (all zeros when K == 0)
     store_lds(0);
     __syncthreads();
 
@@ -199,6 +213,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
 
     // epilogue: lane holds, per 32x32 block, row m = lane%32 and columns (v/4)*8 + (lane/32)*4 + v%4
     uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(e) * p.capacity * p.N;
+    uint16_t* C2g = DUAL ? reinterpret_cast<uint16_t*>(p.C2) + static_cast<size_t>(e) * p.capacity * p.N : nullptr;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int m = m0 + wm0 + i * 32 + r32;
@@ -212,11 +227,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
                 float o[4];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    if constexpr (GLU) o[v] = silu(acc[0][i][j][q * 4 + v]) * acc[1][i][j][q * 4 + v];
+                    if constexpr (GLU && !DUAL) o[v] = silu(acc[0][i][j][q * 4 + v]) * acc[1][i][j][q * 4 + v];
                     else o[v] = acc[0][i][j][q * 4 + v];
                 }
                 uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
                 *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
+                if constexpr (GLU && DUAL) {
+                    const f32x16& u = acc[NB - 1][i][j];
+                    pk = make_uint2(f2bf(u[q * 4]) | (f2bf(u[q * 4 + 1]) << 16), f2bf(u[q * 4 + 2]) | (f2bf(u[q * 4 + 3]) << 16));
+                    *reinterpret_cast<uint2*>(C2g + static_cast<size_t>(m) * p.N + n) = pk;
+                }
             }
     }
 }
@@ -419,7 +439,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_pipe_kernel(GemmParams p, 
 // iterations to land: before barrier(kt) a wave waits only until at most 12 copies are
 // outstanding (s_waitcnt vmcnt(12)), i.e. until its share of tile kt+1 is in LDS.
 // ---------------------------------------------------------------------------------------
-template <bool GLU, int WN = 2, int AUXA = 0, int AUXB = 0>
+template <bool GLU, int WN = 2, int AUXA = 0, int AUXB = 0, bool DUAL = false>
 __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) {
     constexpr int BM = 256, BR = 256, CPR = 4, NBUF = 4;
     constexpr int BN = GLU ? 128 : 256;
@@ -432,7 +452,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
 
     int e, mt, nt, seq;
     if (!decode_tile(p, e, mt, nt, &seq)) return;
-    const int count = min(p.counts[e], p.capacity);
+    const int count = group_rows(p, e);
     const int m0 = mt * BM, n0 = nt * BN;
     if (m0 >= count) return;
 
@@ -440,18 +460,19 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int r32 = lane & 31, half = lane >> 5;
-    const int KC = p.K / 8, KT = p.K / 32;
+    const int KCA = (p.lda ? p.lda : p.K) / 8, KCB = (p.ldb ? p.ldb : p.K) / 8;   // 16-byte chunks per operand row
+    const int KT = group_k(p, e) / 32;
     // staggered start of the K loop (see the ping-pong kernel): turns simultaneous misses on shared
     // tiles into one miss and later L2 hits; accumulation order depends on the tile index only
-    const int kt0 = static_cast<int>((static_cast<long long>(seq & 31) * p.k_stagger) % KT);
+    const int kt0 = KT > 0 ? static_cast<int>((static_cast<long long>(seq & 31) * p.k_stagger) % KT) : 0;
 
     // ---- copy sources: wave w fills row groups w*NCP .. (16 rows x 4 chunks = 1 KiB each)
     // Addresses are a wave-uniform 64-bit base (scalar registers, advanced by 64 bytes per tile)
     // plus a per-lane 32-bit byte offset that never changes (the host checks that it fits).
     const char* Abase = reinterpret_cast<const char*>(p.A) +
-                        (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KC * 16);
+                        (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KCA * 16);
     const char* Bbase = reinterpret_cast<const char*>((GLU && wave >= NW / 2) ? p.B1 : p.B0) +
-                        static_cast<size_t>(e) * p.N * KC * 16;
+                        static_cast<size_t>(e) * p.N * KCB * 16;
     uint32_t off[2 * NCP];                              // first NCP: A groups, then B groups
 #pragma unroll
     for (int i = 0; i < NCP; ++i) {
@@ -460,10 +481,10 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
         int m = m0 + r;
         m = m < count ? m : count - 1;                   // rows past the count replay a valid row; never stored
         const int row = p.row_index ? min(max(p.row_index[static_cast<size_t>(e) * p.capacity + m], 0), p.a_rows - 1) : m;
-        off[i] = (static_cast<uint32_t>(row) * KC + c) * 16u;
+        off[i] = (static_cast<uint32_t>(row) * KCA + c) * 16u;
         int n = n0 + (GLU ? (r & 127) : r);
         n = n < p.N ? n : p.N - 1;
-        off[NCP + i] = (static_cast<uint32_t>(n) * KC + c) * 16u;
+        off[NCP + i] = (static_cast<uint32_t>(n) * KCB + c) * 16u;
     }
     auto issue_copy = [&](int kt, int j) {
         uint4* dst = lds + (kt & (NBUF - 1)) * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
@@ -553,6 +574,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
 
     // ---- epilogue: lane holds, per 32x32 block, row m = lane%32 and columns (v/4)*8 + (lane/32)*4 + v%4
     uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(e) * p.capacity * p.N;
+    uint16_t* C2g = DUAL ? reinterpret_cast<uint16_t*>(p.C2) + static_cast<size_t>(e) * p.capacity * p.N : nullptr;
     constexpr int TO = GLU ? TB / 2 : TB;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -567,11 +589,16 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
                 float o[4];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    if constexpr (GLU) o[v] = silu(acc[i][j][q * 4 + v]) * acc[i][TO + j][q * 4 + v];
+                    if constexpr (GLU && !DUAL) o[v] = silu(acc[i][j][q * 4 + v]) * acc[i][TO + j][q * 4 + v];
                     else o[v] = acc[i][j][q * 4 + v];
                 }
                 uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
                 *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
+                if constexpr (GLU && DUAL) {
+                    const f32x16& u = acc[i][TB - TO + j];
+                    pk = make_uint2(f2bf(u[q * 4]) | (f2bf(u[q * 4 + 1]) << 16), f2bf(u[q * 4 + 2]) | (f2bf(u[q * 4 + 3]) << 16));
+                    *reinterpret_cast<uint2*>(C2g + static_cast<size_t>(m) * p.N + n) = pk;
+                }
             }
     }
 }
@@ -749,33 +776,36 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmParams p) {
 // ---------------------------------------------------------------------------------------
 // fp32 grouped GEMM, 64x64 tile, 4x4 outputs per thread, plain FMA
 // ---------------------------------------------------------------------------------------
-template <bool GLU>
+template <bool GLU, bool DUAL = false>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
     constexpr int BM = 64, BN = 64, BK = 16, LD = BM + 4;
     __shared__ float As[BK][LD];
     __shared__ float Bs[GLU ? 2 : 1][BK][LD];
     int e, mt, nt;
     if (!decode_tile(p, e, mt, nt)) return;
-    const int count = min(p.counts[e], p.capacity);
+    const int count = group_rows(p, e);
     const int m0 = mt * BM, n0 = nt * BN;
     if (m0 >= count) return;
-    const int tid = threadIdx.x, K = p.K;
-    const float* Ag = static_cast<const float*>(p.A) + static_cast<size_t>(e) * p.capacity * K;
-    const float* B0g = static_cast<const float*>(p.B0) + static_cast<size_t>(e) * p.N * K;
-    const float* B1g = GLU ? static_cast<const float*>(p.B1) + static_cast<size_t>(e) * p.N * K : nullptr;
+    const int tid = threadIdx.x, K = group_k(p, e);
+    const int LA = p.lda ? p.lda : p.K, LB = p.ldb ? p.ldb : p.K;
+    const float* Ag = static_cast<const float*>(p.A) + (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * LA);
+    const float* B0g = static_cast<const float*>(p.B0) + static_cast<size_t>(e) * p.N * LB;
+    const float* B1g = GLU ? static_cast<const float*>(p.B1) + static_cast<size_t>(e) * p.N * LB : nullptr;
     const int lr = tid >> 2, lk = (tid & 3) * 4;                  // staging: row, k offset
-    const int am = min(m0 + lr, p.capacity - 1), bn = min(n0 + lr, p.N - 1);
+    int am = min(m0 + lr, p.capacity - 1);
+    if (p.row_index) am = min(max(p.row_index[static_cast<size_t>(e) * p.capacity + am], 0), p.a_rows - 1);
+    const int bn = min(n0 + lr, p.N - 1);
     const int ty = tid >> 4, tx = tid & 15;
     float acc[GLU ? 2 : 1][4][4] = {};
     for (int k0 = 0; k0 < K; k0 += BK) {
         const bool kin = k0 + lk < K;                             // K % 4 == 0: a float4 is all in or all out
         const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-        float4 va = kin ? *reinterpret_cast<const float4*>(Ag + static_cast<size_t>(am) * K + k0 + lk) : z;
-        float4 vb = kin ? *reinterpret_cast<const float4*>(B0g + static_cast<size_t>(bn) * K + k0 + lk) : z;
+        float4 va = kin ? *reinterpret_cast<const float4*>(Ag + static_cast<size_t>(am) * LA + k0 + lk) : z;
+        float4 vb = kin ? *reinterpret_cast<const float4*>(B0g + static_cast<size_t>(bn) * LB + k0 + lk) : z;
         As[lk + 0][lr] = va.x; As[lk + 1][lr] = va.y; As[lk + 2][lr] = va.z; As[lk + 3][lr] = va.w;
         Bs[0][lk + 0][lr] = vb.x; Bs[0][lk + 1][lr] = vb.y; Bs[0][lk + 2][lr] = vb.z; Bs[0][lk + 3][lr] = vb.w;
         if constexpr (GLU) {
-            float4 vc = kin ? *reinterpret_cast<const float4*>(B1g + static_cast<size_t>(bn) * K + k0 + lk) : z;
+            float4 vc = kin ? *reinterpret_cast<const float4*>(B1g + static_cast<size_t>(bn) * LB + k0 + lk) : z;
             Bs[1][lk + 0][lr] = vc.x; Bs[1][lk + 1][lr] = vc.y; Bs[1][lk + 2][lr] = vc.z; Bs[1][lk + 3][lr] = vc.w;
         }
         __syncthreads();
@@ -802,10 +832,15 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
         if (m >= count) continue;
         const int n = n0 + tx * 4;
         if (n >= p.N) continue;                                   // N % 4 == 0
+        if constexpr (GLU && DUAL) {
+            float* C2g = static_cast<float*>(p.C2) + static_cast<size_t>(e) * p.capacity * p.N;
+            *reinterpret_cast<float4*>(C2g + static_cast<size_t>(m) * p.N + n) =
+                make_float4(acc[1][i][0], acc[1][i][1], acc[1][i][2], acc[1][i][3]);
+        }
         float o[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            if constexpr (GLU) {
+            if constexpr (GLU && !DUAL) {
                 const float g = acc[0][i][j];
                 o[j] = g / (1.0f + expf(-g)) * acc[1][i][j];
             } else {
@@ -816,12 +851,12 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
     }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool GLU, int SWZ>
+template <int BM, int BN, int BK, int WGM, int WGN, bool GLU, int SWZ, bool DUAL = false>
 hipError_t launch_bf16(GemmParams p, hipStream_t st) {
     constexpr int BROWS = GLU ? 2 * BN : BN;
     constexpr size_t lds = 2ull * (BM + BROWS) * BK * 2;
     const long long blocks = plan_tiles(p, BM, BN);
-    auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, GLU, SWZ>;
+    auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, GLU, SWZ, DUAL>;
     if (lds > 64 * 1024) {
         hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
@@ -843,11 +878,11 @@ hipError_t launch_bf16_pipe(GemmParams p, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <bool GLU, int WN = 2, int AUXA = 0, int AUXB = 0>
+template <bool GLU, int WN = 2, int AUXA = 0, int AUXB = 0, bool DUAL = false>
 hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
     constexpr size_t lds = 4ull * 512 * 32 * 2;        // four buffers of 256 + 256 rows x 32 bf16
     const long long blocks = plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_ring_kernel<GLU, WN, AUXA, AUXB>;
+    auto kern = gemm_bf16_ring_kernel<GLU, WN, AUXA, AUXB, DUAL>;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (err != hipSuccess) return err;
@@ -867,10 +902,10 @@ hipError_t launch_bf16_pp(GemmParams p, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <bool GLU>
+template <bool GLU, bool DUAL = false>
 hipError_t launch_f32(GemmParams p, hipStream_t st) {
     const long long blocks = plan_tiles(p, 64, 64);
-    hipLaunchKernelGGL(gemm_f32_kernel<GLU>, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((gemm_f32_kernel<GLU, DUAL>), dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
@@ -883,8 +918,34 @@ size_t ffn_ws_bytes(const etr_config& c) {
 // The pipelined kernels need K % 64 == 0 (copies cannot zero-fill a K tail) and 32-bit byte
 // offsets inside one operand; everything else takes the register-staged kernel.
 static bool pipelined_ok(const GemmParams& g, size_t a_rows) {
-    const size_t row_bytes = static_cast<size_t>(g.K) * 2;
-    return g.K % 64 == 0 && a_rows * row_bytes < (1ull << 32) && static_cast<size_t>(g.N) * row_bytes < (1ull << 32);
+    const size_t a_row_bytes = static_cast<size_t>(g.lda ? g.lda : g.K) * 2, b_row_bytes = static_cast<size_t>(g.ldb ? g.ldb : g.K) * 2;
+    return g.K % 64 == 0 && a_row_bytes % 16 == 0 && b_row_bytes % 16 == 0 && a_rows * a_row_bytes < (1ull << 32) &&
+           static_cast<size_t>(g.N) * b_row_bytes < (1ull << 32);
+}
+
+// General entry for the other stages of the library: grouped "NT" product
+//   C[g][m][n] = sum_k A[g][m][k] * B[g][n][k],  g < G, m < m_counts[g] (or M), k < k_counts[g] (or K).
+hipError_t launch_grouped_gemm(const GroupedGemm& q, hipStream_t st) {
+    GemmParams g{q.A, q.B0, q.B1, q.C, q.m_counts, q.G, q.M, q.N, q.K, 0, 0, 0, 0, q.row_index, 0, q.a_rows};
+    g.lda = q.lda; g.ldb = q.ldb; g.k_counts = q.k_counts; g.C2 = q.C2;
+    if (q.N % 4 != 0 || q.K < 0 || q.G < 1 || q.M < 1) return hipErrorInvalidValue;
+    if (q.dtype == ETR_BF16) {
+        if (q.K % 8 != 0 || (q.lda ? q.lda : q.K) % 8 != 0 || (q.ldb ? q.ldb : q.K) % 8 != 0) return hipErrorInvalidValue;
+        const bool ring = pipelined_ok(g, q.row_index ? static_cast<size_t>(q.a_rows) : static_cast<size_t>(q.M));
+        switch (q.epilogue) {
+            case GEMM_PLAIN: return ring ? launch_bf16_ring<false, 4>(g, st) : launch_bf16<128, 128, 64, 2, 2, false, 1>(g, st);
+            case GEMM_SWIGLU: return ring ? launch_bf16_ring<true, 4>(g, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g, st);
+            case GEMM_DUAL: return ring ? launch_bf16_ring<true, 4, 0, 0, true>(g, st) : launch_bf16<128, 64, 64, 2, 2, true, 1, true>(g, st);
+        }
+        return hipErrorInvalidValue;
+    }
+    if (q.K % 4 != 0 || (q.lda ? q.lda : q.K) % 4 != 0 || (q.ldb ? q.ldb : q.K) % 4 != 0) return hipErrorInvalidValue;
+    switch (q.epilogue) {
+        case GEMM_PLAIN: return launch_f32<false>(g, st);
+        case GEMM_SWIGLU: return launch_f32<true>(g, st);
+        case GEMM_DUAL: return launch_f32<true, true>(g, st);
+    }
+    return hipErrorInvalidValue;
 }
 
 bool ffn_can_gather(const etr_config& c) {

@@ -33,7 +33,7 @@ DT_F32, DT_BF16 = 0, 1
 
 BASE_SEED = 2406000230
 
-_STREAMS = {"tokens": 0, "emb": 1, "w_gate": 2, "w_up": 3, "w_down": 4, "bias": 5, "cluster": 6}
+_STREAMS = {"tokens": 0, "emb": 1, "w_gate": 2, "w_up": 3, "w_down": 4, "bias": 5, "cluster": 6, "dout": 7}
 
 
 @dataclass(frozen=True)
@@ -235,6 +235,13 @@ def make_inputs(shape: EtrShape, device="cpu", with_weights: bool = True) -> Dic
         out["w_up"] = ffn_weight(stream_seed(cid, "w_up"), (E, H, d), dt, device)
         out["w_down"] = ffn_weight(stream_seed(cid, "w_down"), (E, d, H), dt, device)
     return out
+
+
+def make_upstream_gradient(shape: EtrShape, device="cpu") -> torch.Tensor:
+    """Upstream gradient d loss / d out for the backward pass: i.i.d. N(0, 1), [T][d] in the workload's dtype
+    (what a following layer's backward hands over has no structure the method relies on)."""
+    g = normal(stream_seed(shape.cfg_id, "dout"), shape.T * shape.d, device)
+    return g.view(shape.T, shape.d).to(shape.torch_dtype)
 
 
 def small_variant(shape: EtrShape, T: int, H: Optional[int] = None, d: Optional[int] = None) -> EtrShape:

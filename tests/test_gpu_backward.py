@@ -1,0 +1,133 @@
+"""GPU parity of the backward pass (through the C ABI) against the CPU oracle on identical bytes.
+
+The routing tables handed to the backward are the GPU's own (already byte-identical to the oracle's
+selection on the GPU's scores); gradients are compared per tensor with max|a-b| / max|b|:
+1e-4 for fp32, 2e-2 for bf16 (the tolerance of the forward output)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2406_00023_amd import binding as B
+from paper_2406_00023_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+TCR, ECR, BIDIR = I.MODE_TCR, I.MODE_ECR, I.MODE_BIDIR
+FULL, POOLED = I.COS_FULL, I.COS_POOLED
+
+
+@pytest.fixture(scope="module")
+def H():
+    import gpu_helpers
+    assert torch.cuda.is_available()
+    B.load_library()
+    return gpu_helpers
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+class Backward:
+    """Runs forward routing + backward on the GPU and keeps the results."""
+
+    def __init__(self, H, shape, mode, cos=None):
+        self.H, self.shape = H, shape
+        self.L = L = H.GpuLayer(shape, mode=mode, cos=cos)
+        L.route(); L.select()
+        dev, dt = "cuda", shape.torch_dtype
+        E, Hh, d, T = shape.E, shape.H, shape.d, shape.T
+        self.dout = I.make_upstream_gradient(shape, dev)
+        # poisoned outputs: everything the call is meant to overwrite must be overwritten
+        self.dx = torch.full((T, d), 7.0, dtype=dt, device=dev)
+        self.dwg = torch.full((E, Hh, d), 7.0, dtype=dt, device=dev)
+        self.dwu = torch.full((E, Hh, d), 7.0, dtype=dt, device=dev)
+        self.dwd = torch.full((E, d, Hh), 7.0, dtype=dt, device=dev)
+        self.dgate = torch.full((T, E), 7.0, dtype=torch.float32, device=dev)
+        self.dscore = torch.full((T, E), 7.0, dtype=torch.float32, device=dev)
+        ws = B.alloc_workspace(B.etr_backward_workspace_bytes(L.cfg))
+        ws.fill_(0xFF)                    # NaN patterns: nothing may be read before it is written
+        t = L.t
+        B.etr_moe_backward(L.cfg, t["x"], t["w_emb"], t["w_gate"], t["w_up"], t["w_down"], L.score, L.gate, L.slot_of,
+                           L.slot_token, L.counts, self.dout, self.dx, self.dwg, self.dwu, self.dwd, ws,
+                           dgate=self.dgate, dscore=self.dscore)
+        torch.cuda.synchronize()
+
+    def host(self):
+        hx = self.L.host_inputs()
+        hx["dout"] = self.H.to_np(self.dout)
+        hx["slot_of"] = self.H.to_np(self.L.slot_of)
+        return hx
+
+
+def _err(H, oracle, got, ref, dtype):
+    a = oracle.to_f64(H.to_np(got), dtype) if got.dtype != torch.float32 or dtype == I.DT_F32 else H.to_np(got).astype(np.float64)
+    return H.scale_rel_err(a, ref)
+
+
+SMALL = {
+    "cfg1": lambda: I.CONFIGS["cfg1"],
+    "cfg2s": lambda: I.small_variant(I.CONFIGS["cfg2"], T=1100, d=512, H=704),
+    "cfg3s": lambda: I.small_variant(I.CONFIGS["cfg3"], T=900, d=1024, H=1032),
+    "cfg4s": lambda: I.small_variant(I.CONFIGS["cfg4"], T=1500, d=1024, H=328),
+    "cfg5s": lambda: I.small_variant(I.CONFIGS["cfg5"], T=700, H=200),
+}
+
+
+@pytest.mark.parametrize("name,mode,cos", [("cfg1", TCR, FULL), ("cfg1", ECR, POOLED), ("cfg1", BIDIR, FULL),
+                                           ("cfg2s", TCR, FULL), ("cfg3s", ECR, FULL), ("cfg4s", BIDIR, POOLED),
+                                           ("cfg5s", BIDIR, FULL)])
+def test_backward_small_all_gradients(H, oracle, name, mode, cos):
+    shape = SMALL[name]()
+    _say(f"backward case {name} mode={mode} cos={cos} T={shape.T} d={shape.d} E={shape.E} C={shape.capacity} H={shape.H}")
+    bw = Backward(H, shape, mode, cos)
+    hx = bw.host()
+    ref = oracle.moe_backward(hx["x"], hx["w_emb"], hx["w_gate"], hx["w_up"], hx["w_down"], hx["slot_of"], hx["dout"],
+                              D=shape.D, dtype=shape.dtype, cos_mode=cos)
+    tol = H.TOL_OUT[shape.dtype]
+    errs = {
+        "dx": _err(H, oracle, bw.dx, ref["dx"], shape.dtype),
+        "dw_gate": _err(H, oracle, bw.dwg, ref["dw_gate"], shape.dtype),
+        "dw_up": _err(H, oracle, bw.dwu, ref["dw_up"], shape.dtype),
+        "dw_down": _err(H, oracle, bw.dwd, ref["dw_down"], shape.dtype),
+        "dgate": H.scale_rel_err(H.to_np(bw.dgate).astype(np.float64), ref["dgate"]),
+        "dscore": H.scale_rel_err(H.to_np(bw.dscore).astype(np.float64), ref["dscore"]),
+    }
+    _say(f"  errors {errs}")
+    for k, v in errs.items():
+        assert v <= tol, (k, v)
+    # a token kept by no expert gets an exactly zero input gradient
+    dropped = (hx["slot_of"] >= 0).sum(1) == 0
+    assert np.all(oracle.to_f64(H.to_np(bw.dx), shape.dtype)[dropped] == 0)
+    # experts that keep nothing get exactly zero weight gradients
+    for e in np.nonzero(H.to_np(bw.L.counts) == 0)[0]:
+        assert not H.to_np(bw.dwg)[e].any() and not H.to_np(bw.dwd)[e].any()
+
+
+@pytest.mark.parametrize("name", ["cfg2"])
+def test_backward_full_size_sampled(H, oracle, name):
+    shape = I.CONFIGS[name]
+    _say(f"backward full size {name}")
+    bw = Backward(H, shape, shape.mode)
+    hx = bw.host()
+    rng = np.random.default_rng(7)
+    tokens = np.sort(rng.choice(shape.T, 24, replace=False)).astype(np.int32)
+    dx, dg, ds = oracle.backward_tokens(hx["x"], hx["w_emb"], hx["w_gate"], hx["w_up"], hx["w_down"], hx["slot_of"],
+                                        hx["dout"], tokens, D=shape.D, dtype=shape.dtype)
+    tol = H.TOL_OUT[shape.dtype]
+    got_dx = oracle.to_f64(H.to_np(bw.dx), shape.dtype)[tokens]
+    e1 = H.scale_rel_err(got_dx, dx)
+    e2 = H.scale_rel_err(H.to_np(bw.dgate).astype(np.float64)[tokens], dg)
+    e3 = H.scale_rel_err(H.to_np(bw.dscore).astype(np.float64)[tokens], ds)
+    _say(f"  dx {e1} dgate {e2} dscore {e3}")
+    assert e1 <= tol and e2 <= tol and e3 <= tol
+    ue = rng.integers(0, shape.E, 12).astype(np.int32)
+    ui = rng.integers(0, shape.H, 12).astype(np.int32)
+    gw, uw, dw = oracle.backward_hidden_units(hx["x"], hx["w_emb"], hx["w_gate"], hx["w_up"], hx["w_down"], hx["slot_of"],
+                                              hx["dout"], ue, ui, D=shape.D, dtype=shape.dtype)
+    g_gw = oracle.to_f64(H.to_np(bw.dwg), shape.dtype)[ue, ui]
+    g_uw = oracle.to_f64(H.to_np(bw.dwu), shape.dtype)[ue, ui]
+    g_dw = oracle.to_f64(H.to_np(bw.dwd), shape.dtype)[ue, :, ui]
+    e4, e5, e6 = H.scale_rel_err(g_gw, gw), H.scale_rel_err(g_uw, uw), H.scale_rel_err(g_dw, dw)
+    _say(f"  dw_gate {e4} dw_up {e5} dw_down {e6}")
+    assert e4 <= tol and e5 <= tol and e6 <= tol
