@@ -60,6 +60,55 @@ def cpu_baseline(shape, cfg, tensors, budget_tokens: int):
                       f"({t_sample - t_routing:.2f} s), extrapolated linearly to {shape.T}"}
 
 
+def bench_backward(args, shape, cfg, t, dev):
+    """K calls of etr_moe_backward on the routing of one forward call; one JSON line."""
+    import torch
+    from paper_2406_00023_amd import binding as B
+    from paper_2406_00023_amd import inputs as I
+    T, E, C, d, H = shape.T, shape.E, cfg.capacity, shape.d, shape.H
+    dt = shape.torch_dtype
+    score = torch.empty(T, E, dtype=torch.float32, device=dev)
+    gate = torch.empty(T, E, dtype=torch.float32, device=dev)
+    slot_of = torch.empty(T, E, dtype=torch.int32, device=dev)
+    slot_token = torch.empty(E, C, dtype=torch.int32, device=dev)
+    topk = torch.empty(T, max(shape.k, 1), dtype=torch.int32, device=dev)
+    counts = torch.zeros(E, dtype=torch.int32, device=dev)
+    B.etr_route(cfg, t["x"], t["w_emb"], score, gate)
+    B.etr_select(cfg, score, topk, slot_of, slot_token, counts, B.alloc_workspace(B.etr_select_workspace_bytes(cfg), dev))
+    dout = I.make_upstream_gradient(shape, dev)
+    dx = torch.empty(T, d, dtype=dt, device=dev)
+    dwg, dwu = torch.empty(E, H, d, dtype=dt, device=dev), torch.empty(E, H, d, dtype=dt, device=dev)
+    dwd = torch.empty(E, d, H, dtype=dt, device=dev)
+    ws = B.alloc_workspace(B.etr_backward_workspace_bytes(cfg), dev)
+
+    def step():
+        B.etr_moe_backward(cfg, t["x"], t["w_emb"], t["w_gate"], t["w_up"], t["w_down"], score, gate, slot_of,
+                           slot_token, counts, dout, dx, dwg, dwu, dwd, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = (time.perf_counter() - t0) / args.steps
+    rows = int(counts.sum().item())
+    flop = 16.0 * rows * d * H       # recompute 4dH + W_d^T dout 2dH + input gradient 4dH + weight gradients 6dH per kept row
+    peak = PEAK_BF16_TFLOPS if shape.dtype == I.DT_BF16 else PEAK_F32_TFLOPS
+    print(json.dumps({
+        "metric": "MoE-layer backward tokens/sec on 1 MI355X", "value": T / elapsed, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * elapsed, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if shape.dtype == I.DT_BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{shape.name} backward: T={T} d={d} E={E} capacity={C} H={H}", "kept_rows": rows},
+        "roofline": {"kernel": "all products of the backward pass together (grouped GEMM kernel)",
+                     "bound": "mfma" if shape.dtype == I.DT_BF16 else "alu", "achieved": flop / elapsed / 1e12,
+                     "peak": peak, "unit": "TFLOP/s", "frac": flop / elapsed / 1e12 / peak, "traffic": None,
+                     "algorithmic_flop": flop},
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,6 +118,8 @@ def main():
     ap.add_argument("--capacity", type=int, default=None, help="override the capacity (cfg4's schedule)")
     ap.add_argument("--cpu-tokens", type=int, default=8192, help="tokens of the oracle's FFN sample")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--backward", action="store_true",
+                    help="time etr_moe_backward instead of the forward (not the headline metric; no cpu_baseline)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -89,6 +140,8 @@ def main():
     t = I.make_inputs(shape, dev)
     out = torch.empty(shape.T, shape.d, dtype=shape.torch_dtype, device=dev)
     counts = torch.zeros(shape.E, dtype=torch.int32, device=dev)
+    if args.backward:
+        return bench_backward(args, shape, cfg, t, dev)
     ws = B.alloc_workspace(B.etr_workspace_bytes(cfg), dev)
 
     def step(events=None):

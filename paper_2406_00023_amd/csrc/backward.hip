@@ -21,35 +21,85 @@ constexpr int kTileThreads = 256;
 
 template <typename T> struct Elt;
 template <> struct Elt<float> {
+    static constexpr int kVec = 4;           // elements per 16 bytes
+    static constexpr int kPad = 1;           // LDS tile padding (elements): odd dword stride
     __device__ static float load(const float* p, size_t i) { return p[i]; }
     __device__ static void store(float* p, size_t i, float v) { p[i] = v; }
-};
-template <> struct Elt<uint16_t> {          // bf16 bit patterns
-    __device__ static float load(const uint16_t* p, size_t i) { return __uint_as_float(static_cast<uint32_t>(p[i]) << 16); }
-    __device__ static void store(uint16_t* p, size_t i, float v) {
-        uint32_t u = __float_as_uint(v);
-        p[i] = static_cast<uint16_t>((u & 0x7FFFFFFFu) > 0x7F800000u ? 0x7FC0u : (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+    __device__ static void load_vec(const float* p, float* f) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
     }
+    __device__ static void store_vec(float* p, const float* f) { *reinterpret_cast<float4*>(p) = make_float4(f[0], f[1], f[2], f[3]); }
+    __device__ static float widen(float v) { return v; }
+    __device__ static float narrow(float v) { return v; }
+};
+__device__ __forceinline__ uint16_t bf16_bits(float v) {     // round to nearest even
+    const uint32_t u = __float_as_uint(v);
+    return static_cast<uint16_t>((u & 0x7FFFFFFFu) > 0x7F800000u ? 0x7FC0u : (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+template <> struct Elt<uint16_t> {          // bf16 bit patterns
+    static constexpr int kVec = 8;
+    static constexpr int kPad = 2;
+    __device__ static float load(const uint16_t* p, size_t i) { return __uint_as_float(static_cast<uint32_t>(p[i]) << 16); }
+    __device__ static void store(uint16_t* p, size_t i, float v) { p[i] = bf16_bits(v); }
+    __device__ static void load_vec(const uint16_t* p, float* f) {
+        const uint4 v = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { f[2 * i] = __uint_as_float(w[i] << 16); f[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
+    }
+    __device__ static void store_vec(uint16_t* p, const float* f) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = bf16_bits(f[2 * i]) | (static_cast<uint32_t>(bf16_bits(f[2 * i + 1])) << 16);
+        *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    __device__ static float widen(uint16_t v) { return __uint_as_float(static_cast<uint32_t>(v) << 16); }
+    __device__ static uint16_t narrow(float v) { return bf16_bits(v); }
 };
 
 __device__ __forceinline__ int round_up64(int v) { return (v + 63) & ~63; }
 
-// dst[b][c][col0 + r] = src[b][r][c]   for r < R, c < Cc   (dst rows have ld_dst elements)
+// A 64 x 64 tile in LDS, stored [row][col] in the tensor's own element type.
+template <typename T> struct Tile { T v[kTile][kTile + Elt<T>::kPad]; };
+
+// Writes the transpose of the tile: dst[(c0 + c) * ld + r0 + r] = tile[r][c], 16 bytes per store,
+// eight consecutive lanes on one output row.  Bounds: c0 + c < c_end, r0 + r < r_end (both multiples
+// of the vector width away from the tile origin, so a vector is all in or all out).
+template <typename T>
+__device__ __forceinline__ void store_transposed(const Tile<T>& t, T* dst, size_t ld, int c0, int c_end, int r0, int r_end) {
+    constexpr int V = Elt<T>::kVec, CH = kTile / V;            // chunks per output row
+    for (int q = threadIdx.x; q < kTile * CH; q += kTileThreads) {
+        const int c = q / CH, rc = (q % CH) * V;
+        if (c0 + c >= c_end || r0 + rc >= r_end) continue;
+        alignas(16) T out[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) out[i] = t.v[rc + i][c];
+        *reinterpret_cast<uint4*>(dst + static_cast<size_t>(c0 + c) * ld + r0 + rc) = *reinterpret_cast<const uint4*>(out);
+    }
+}
+
+// dst[b][c][col0 + r] = src[b][r][c]   for r < R, c < Cc   (dst rows have ld_dst elements; R, Cc, col0,
+// ld_dst multiples of the 16-byte vector width)
 template <typename T>
 __global__ __launch_bounds__(kTileThreads) void transpose_kernel(const T* __restrict__ src, T* __restrict__ dst, int R,
                                                                  int Cc, int ld_dst, int col0) {
-    __shared__ T tile[kTile][kTile + 2];
+    __shared__ __attribute__((aligned(16))) Tile<T> tile;
+    constexpr int V = Elt<T>::kVec, CH = kTile / V;
     const int b = blockIdx.z, r0 = blockIdx.y * kTile, c0 = blockIdx.x * kTile;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const T* s = src + static_cast<size_t>(b) * R * Cc;
-    T* d = dst + static_cast<size_t>(b) * Cc * ld_dst;
-#pragma unroll 4
-    for (int i = ty; i < kTile; i += 4)
-        if (r0 + i < R && c0 + tx < Cc) tile[i][tx] = s[static_cast<size_t>(r0 + i) * Cc + c0 + tx];
+    T* d = dst + static_cast<size_t>(b) * Cc * ld_dst + col0;
+    for (int q = threadIdx.x; q < kTile * CH; q += kTileThreads) {
+        const int r = q / CH, cc = (q % CH) * V;
+        if (r0 + r < R && c0 + cc < Cc) {
+            const uint4 v = *reinterpret_cast<const uint4*>(s + static_cast<size_t>(r0 + r) * Cc + c0 + cc);
+            const T* e = reinterpret_cast<const T*>(&v);
+#pragma unroll
+            for (int i = 0; i < V; ++i) tile.v[r][cc + i] = e[i];
+        }
+    }
     __syncthreads();
-#pragma unroll 4
-    for (int i = ty; i < kTile; i += 4)
-        if (c0 + i < Cc && r0 + tx < R) d[static_cast<size_t>(c0 + i) * ld_dst + col0 + r0 + tx] = tile[tx][i];
+    store_transposed<T>(tile, d, ld_dst, c0, Cc, r0, R);
 }
 
 // dst[e][j][s] = src[slot_token[e][s]][j] (* gate[slot_token[e][s]][e])  for s < counts[e];
@@ -60,100 +110,88 @@ __global__ __launch_bounds__(kTileThreads) void gather_transpose_kernel(const T*
                                                                         const int32_t* __restrict__ counts,
                                                                         const float* __restrict__ gate, T* __restrict__ dst,
                                                                         int T_, int d, int E, int C, int Cp) {
-    __shared__ float tile[kTile][kTile + 1];
+    __shared__ __attribute__((aligned(16))) Tile<T> tile;
+    constexpr int V = Elt<T>::kVec, CH = kTile / V;
     const int e = blockIdx.z, s0 = blockIdx.y * kTile, j0 = blockIdx.x * kTile;
     const int count = min(counts[e], C);
     if (s0 >= round_up64(count)) return;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-#pragma unroll 4
-    for (int i = ty; i < kTile; i += 4) {
-        const int s = s0 + i;
-        float v = 0.f;
-        if (s < count && j0 + tx < d) {
+    for (int q = threadIdx.x; q < kTile * CH; q += kTileThreads) {
+        const int r = q / CH, cc = (q % CH) * V, s = s0 + r;
+        float f[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) f[i] = 0.f;
+        if (s < count && j0 + cc < d) {
             const int t = slot_token[static_cast<size_t>(e) * C + s];
             if (t >= 0 && t < T_) {
-                v = Elt<T>::load(src, static_cast<size_t>(t) * d + j0 + tx);
-                if (SCALE) v *= gate[static_cast<size_t>(t) * E + e];
+                Elt<T>::load_vec(src + static_cast<size_t>(t) * d + j0 + cc, f);
+                if (SCALE) {
+                    const float gt = gate[static_cast<size_t>(t) * E + e];
+#pragma unroll
+                    for (int i = 0; i < V; ++i) f[i] *= gt;
+                }
             }
         }
-        tile[i][tx] = v;
+#pragma unroll
+        for (int i = 0; i < V; ++i) tile.v[r][cc + i] = Elt<T>::narrow(f[i]);
     }
     __syncthreads();
-    T* de = dst + static_cast<size_t>(e) * d * Cp;
-#pragma unroll 4
-    for (int i = ty; i < kTile; i += 4)
-        if (j0 + i < d && s0 + tx < Cp) Elt<T>::store(de, static_cast<size_t>(j0 + i) * Cp + s0 + tx, tile[tx][i]);
+    store_transposed<T>(tile, dst + static_cast<size_t>(e) * d * Cp, Cp, j0, d, s0, Cp);
 }
 
-// Element-wise middle of the FFN backward for one block of 64 buffer rows of one expert.
+// Element-wise middle of the FFN backward for one 64 x 64 tile (buffer rows x hidden units) of one expert.
 //   in : u, a, b [E][C][H];  gate through slot_token
-//   out: dab [E][C][2H] = (da | db);  daT, dbT, hT [E][H][Cp];  dgate_slot [E][C] = <u, h>
+//   out: dab [E][C][2H] = (da | db);  daT, dbT, hT [E][H][Cp];
+//        dgate_part [H/64][E][C]: this tile's share of <u, h> per row (summed by dx_kernel in tile order)
 template <typename T>
 __global__ __launch_bounds__(kTileThreads) void swiglu_backward_kernel(
     const T* __restrict__ u, const T* __restrict__ a, const T* __restrict__ b, const float* __restrict__ gate,
     const int32_t* __restrict__ slot_token, const int32_t* __restrict__ counts, T* __restrict__ dab, T* __restrict__ daT,
-    T* __restrict__ dbT, T* __restrict__ hT, float* __restrict__ dgate_slot, int T_, int E, int C, int Cp, int H) {
-    __shared__ float th[kTile][kTile + 1], ta[kTile][kTile + 1], tb[kTile][kTile + 1];
-    const int e = blockIdx.y, s0 = blockIdx.x * kTile;
+    T* __restrict__ dbT, T* __restrict__ hT, float* __restrict__ dgate_part, int T_, int E, int C, int Cp, int H) {
+    __shared__ __attribute__((aligned(16))) Tile<T> th, ta, tb;
+    constexpr int V = Elt<T>::kVec, CH = kTile / V;
+    const int e = blockIdx.z, s0 = blockIdx.y * kTile, n0 = blockIdx.x * kTile;
     const int count = min(counts[e], C);
     if (s0 >= round_up64(count)) return;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    constexpr int R = kTile / 4;                     // rows per thread: ty, ty + 4, ...
-    float g_row[R], dot[R];
-#pragma unroll
-    for (int i = 0; i < R; ++i) {
-        const int s = s0 + ty + 4 * i;
-        g_row[i] = 0.f; dot[i] = 0.f;
-        if (s < count) {
-            const int t = slot_token[static_cast<size_t>(e) * C + s];
-            if (t >= 0 && t < T_) g_row[i] = gate[static_cast<size_t>(t) * E + e];
-        }
-    }
     const size_t ebase = static_cast<size_t>(e) * C;
-    for (int n0 = 0; n0 < H; n0 += kTile) {
-        const int n = n0 + tx;
+    for (int q = threadIdx.x; q < kTile * CH; q += kTileThreads) {
+        const int r = q / CH, cc = (q % CH) * V, s = s0 + r, n = n0 + cc;
+        float hv[V], dav[V], dbv[V], dot = 0.f;
 #pragma unroll
-        for (int i = 0; i < R; ++i) {
-            const int r = ty + 4 * i, s = s0 + r;
-            float hv = 0.f, dav = 0.f, dbv = 0.f;
-            if (s < count && n < H) {
-                const size_t idx = (ebase + s) * H + n;
-                const float uv = Elt<T>::load(u, idx), av = Elt<T>::load(a, idx), bv = Elt<T>::load(b, idx);
-                const float sg = 1.0f / (1.0f + __expf(-av));
-                const float sl = av * sg;
-                hv = sl * bv;
-                const float dh = g_row[i] * uv;
-                dav = dh * bv * (sg * (1.0f + av * (1.0f - sg)));
-                dbv = dh * sl;
-                dot[i] += uv * hv;
-                Elt<T>::store(dab, (ebase + s) * 2 * H + n, dav);
-                Elt<T>::store(dab, (ebase + s) * 2 * H + H + n, dbv);
+        for (int i = 0; i < V; ++i) { hv[i] = 0.f; dav[i] = 0.f; dbv[i] = 0.f; }
+        if (s < count && n < H) {
+            const int t = slot_token[ebase + s];
+            const float g_row = (t >= 0 && t < T_) ? gate[static_cast<size_t>(t) * E + e] : 0.f;
+            const size_t idx = (ebase + s) * H + n;
+            float uv[V], av[V], bv[V];
+            Elt<T>::load_vec(u + idx, uv); Elt<T>::load_vec(a + idx, av); Elt<T>::load_vec(b + idx, bv);
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                const float sg = 1.0f / (1.0f + __expf(-av[i]));
+                const float sl = av[i] * sg;
+                hv[i] = sl * bv[i];
+                const float dh = g_row * uv[i];
+                dav[i] = dh * bv[i] * (sg * (1.0f + av[i] * (1.0f - sg)));
+                dbv[i] = dh * sl;
+                dot += uv[i] * hv[i];
             }
-            th[r][tx] = hv; ta[r][tx] = dav; tb[r][tx] = dbv;
+            Elt<T>::store_vec(dab + (ebase + s) * 2 * H + n, dav);
+            Elt<T>::store_vec(dab + (ebase + s) * 2 * H + H + n, dbv);
         }
-        __syncthreads();
-        if (s0 + tx < Cp) {
 #pragma unroll
-            for (int i = 0; i < R; ++i) {
-                const int c = ty + 4 * i;
-                if (n0 + c < H) {
-                    const size_t o = (static_cast<size_t>(e) * H + n0 + c) * Cp + s0 + tx;
-                    Elt<T>::store(hT, o, th[tx][c]);
-                    Elt<T>::store(daT, o, ta[tx][c]);
-                    Elt<T>::store(dbT, o, tb[tx][c]);
-                }
-            }
+        for (int i = 0; i < V; ++i) {
+            th.v[r][cc + i] = Elt<T>::narrow(hv[i]); ta.v[r][cc + i] = Elt<T>::narrow(dav[i]); tb.v[r][cc + i] = Elt<T>::narrow(dbv[i]);
         }
-        __syncthreads();
-    }
+        // the CH consecutive lanes of one row add up their shares (fixed order)
 #pragma unroll
-    for (int i = 0; i < R; ++i) {
-        float v = dot[i];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-        const int s = s0 + ty + 4 * i;
-        if (tx == 0 && s < count) dgate_slot[ebase + s] = v;
+        for (int o = CH / 2; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+        if ((q % CH) == 0 && s < count)
+            dgate_part[(static_cast<size_t>(blockIdx.x) * E + e) * C + s] = dot;
     }
+    __syncthreads();
+    const size_t tb_off = static_cast<size_t>(e) * H * Cp;
+    store_transposed<T>(th, hT + tb_off, Cp, n0, H, s0, Cp);
+    store_transposed<T>(ta, daT + tb_off, Cp, n0, H, s0, Cp);
+    store_transposed<T>(tb, dbT + tb_off, Cp, n0, H, s0, Cp);
 }
 
 // dx[t] = sum_e dXp[e][slot_of[t][e]] + router term; one wavefront per token.
@@ -163,7 +201,7 @@ __global__ __launch_bounds__(kTileThreads) void swiglu_backward_kernel(
 template <typename T>
 __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const float* __restrict__ w_emb,
                                                  const float* __restrict__ score, const float* __restrict__ gate,
-                                                 const int32_t* __restrict__ slot_of, const float* __restrict__ dgate_slot,
+                                                 const int32_t* __restrict__ slot_of, const float* __restrict__ dgate_part, int n_part,
                                                  const T* __restrict__ dxp, T* __restrict__ dx, float* __restrict__ dgate_out,
                                                  float* __restrict__ dscore_out, int T_, int d, int E, int D, int C,
                                                  int cos_mode) {
@@ -191,9 +229,18 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
     float xx = 0.f, gg = 0.f;
     for (int p = lane; p < P; p += 64) {
         float s = 0.f;
-        for (int j = 0; j < D; ++j) {
-            const float xv = Elt<T>::load(xr, static_cast<size_t>(p) * D + j);
-            s += xv; xx += xv * xv;
+        if (D % Elt<T>::kVec == 0) {
+            for (int j = 0; j < D; j += Elt<T>::kVec) {
+                float f[Elt<T>::kVec];
+                Elt<T>::load_vec(xr + static_cast<size_t>(p) * D + j, f);
+#pragma unroll
+                for (int i = 0; i < Elt<T>::kVec; ++i) { s += f[i]; xx += f[i] * f[i]; }
+            }
+        } else {
+            for (int j = 0; j < D; ++j) {
+                const float xv = Elt<T>::load(xr, static_cast<size_t>(p) * D + j);
+                s += xv; xx += xv * xv;
+            }
         }
         s /= D;
         g[p] = s; gg += s * s;
@@ -207,7 +254,11 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
         slot = slot_of[static_cast<size_t>(t) * E + lane];
         gt = gate[static_cast<size_t>(t) * E + lane];
         sc = score[static_cast<size_t>(t) * E + lane];
-        if (slot >= 0 && slot < C) dg = dgate_slot[static_cast<size_t>(lane) * C + slot]; else slot = -1;
+        if (slot >= 0 && slot < C) {
+            for (int i = 0; i < n_part; ++i) dg += dgate_part[(static_cast<size_t>(i) * E + lane) * C + slot];
+        } else {
+            slot = -1;
+        }
     }
     float mix = dg * gt;
 #pragma unroll
@@ -238,19 +289,29 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
     // FULL: - beta x_j / |x|^2 ; POOLED: - beta g_p / (D |g|^2)
     const float cb = nrm2 > 0.f ? beta / nrm2 * (full ? 1.0f : 1.0f / D) : 0.f;
     T* out = dx + static_cast<size_t>(t) * d;
-    for (int j = lane; j < d; j += 64) {
-        const int p = j / D;
-        float acc = v[p] - cb * (full ? Elt<T>::load(xr, j) : g[p]);
-        for (int e = 0; e < E; ++e) {
-            const int s = sl[e];
-            if (s >= 0) acc += Elt<T>::load(dxp, (static_cast<size_t>(e) * C + s) * d + j);
+    constexpr int V = Elt<T>::kVec;
+    for (int j = lane * V; j < d; j += 64 * V) {
+        float acc[V], f[V];
+        if (full) Elt<T>::load_vec(xr + j, f);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const int p = (j + i) / D;
+            acc[i] = v[p] - cb * (full ? f[i] : g[p]);
         }
-        Elt<T>::store(out, j, acc);
+        for (int e = 0; e < E; ++e) {              // ascending expert order, as in the forward sum
+            const int s = sl[e];
+            if (s >= 0) {
+                Elt<T>::load_vec(dxp + (static_cast<size_t>(e) * C + s) * d + j, f);
+#pragma unroll
+                for (int i = 0; i < V; ++i) acc[i] += f[i];
+            }
+        }
+        Elt<T>::store_vec(out + j, acc);
     }
 }
 
 struct BackwardWs {
-    size_t wdT, wguT, a, b, u, dab, daT, dbT, hT, xpT, dypT, dxp, dgate_slot, total;
+    size_t wdT, wguT, a, b, u, dab, daT, dbT, hT, xpT, dypT, dxp, dgate_part, total;
 };
 
 BackwardWs backward_layout(const etr_config& c) {
@@ -271,7 +332,7 @@ BackwardWs backward_layout(const etr_config& c) {
     w.xpT = take(E * d * Cp * es);
     w.dypT = take(E * d * Cp * es);
     w.dxp = take(E * C * d * es);
-    w.dgate_slot = take(E * C * 4);
+    w.dgate_part = take((H + kTile - 1) / kTile * E * C * 4);
     w.total = off;
     return w;
 }
@@ -302,9 +363,9 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
     ETR_BW(launch_grouped_gemm(g1, st));
     GroupedGemm g2{dout, at(L.wdT), nullptr, at(L.u), nullptr, counts, nullptr, slot_token, E, C, H, d, 0, 0, Tn, GEMM_PLAIN, c.dtype};
     ETR_BW(launch_grouped_gemm(g2, st));
-    hipLaunchKernelGGL(swiglu_backward_kernel<T>, dim3(cC, E), dim3(kTileThreads), 0, st, at(L.u), at(L.a), at(L.b), gate,
+    hipLaunchKernelGGL(swiglu_backward_kernel<T>, dim3(cH, cC, E), dim3(kTileThreads), 0, st, at(L.u), at(L.a), at(L.b), gate,
                        slot_token, counts, at(L.dab), at(L.daT), at(L.dbT), at(L.hT),
-                       reinterpret_cast<float*>(base + L.dgate_slot), Tn, E, C, Cp, H);
+                       reinterpret_cast<float*>(base + L.dgate_part), Tn, E, C, Cp, H);
     hipLaunchKernelGGL((gather_transpose_kernel<T, false>), dim3(cd, cC, E), dim3(kTileThreads), 0, st,
                        static_cast<const T*>(x), slot_token, counts, gate, at(L.xpT), Tn, d, E, C, Cp);
     hipLaunchKernelGGL((gather_transpose_kernel<T, true>), dim3(cd, cC, E), dim3(kTileThreads), 0, st,
@@ -327,7 +388,7 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
         ETR_BW(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                    static_cast<int>(lds)));
     hipLaunchKernelGGL(kern, dim3((Tn + 3) / 4), dim3(256), lds, st, static_cast<const T*>(x), w_emb, score, gate, slot_of,
-                       reinterpret_cast<const float*>(base + L.dgate_slot), at(L.dxp), static_cast<T*>(dx), dgate, dscore,
+                       reinterpret_cast<const float*>(base + L.dgate_part), static_cast<int>(cH), at(L.dxp), static_cast<T*>(dx), dgate, dscore,
                        Tn, d, E, c.D, C, static_cast<int>(c.cos));
 #undef ETR_BW
     return hipGetLastError();
