@@ -55,7 +55,7 @@
 namespace {
 
 enum { DT_F32 = 0, DT_BF16 = 1 };
-enum { MODE_TCR = 0, MODE_ECR = 1, MODE_BIDIR = 2 };
+enum { MODE_TCR = 0, MODE_ECR = 1, MODE_BIDIR = 2, MODE_TCR_RANK = 3, MODE_BIDIR_STRICT = 4 };
 enum { COS_FULL = 0, COS_POOLED = 1 };
 
 inline float bf16_to_float(uint16_t b) {
@@ -199,10 +199,12 @@ int etr_ref_select_adaptive(int T, int E, int k, int capacity, int mode, const f
                             int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts) {
     if (T < 0 || E <= 0 || capacity < 1) return 2;
     if (mode != MODE_ECR && (k < 1 || k > E)) return 2;
-    if (mode < 0 || mode > 2) return 3;
+    if (mode < 0 || mode > 4) return 3;
+    if (sum_threshold > 0.0f && mode == MODE_BIDIR_STRICT) return 3;
 
     // Eq. 5: every token lists its k best experts.
     std::vector<std::vector<int>> candidates(E);     // per expert, ascending token index
+    std::vector<std::vector<int>> cand_rank(E);      // position of the expert in that token's list
     if (mode == MODE_ECR) {
         for (int e = 0; e < E; ++e) {
             candidates[e].resize(T);
@@ -216,6 +218,7 @@ int etr_ref_select_adaptive(int T, int E, int k, int capacity, int mode, const f
             for (int j = 0; j < k; ++j) {
                 if (topk_expert) topk_expert[(size_t)t * k + j] = order[j];
                 candidates[order[j]].push_back(t);
+                cand_rank[order[j]].push_back(j);
             }
         }
     }
@@ -230,6 +233,28 @@ int etr_ref_select_adaptive(int T, int E, int k, int capacity, int mode, const f
         if (mode == MODE_TCR) {
             // position priority: the first C tokens (in token order) that chose e
             kept.assign(cand.begin(), cand.begin() + n_keep);
+        } else if (mode == MODE_TCR_RANK) {
+            // Variant of the position priority for Top-l with l > 1 (the paper states the rule for one
+            // choice per token only): every token's first choice is served before any second choice,
+            // and so on; inside one rank, token order.  An expert keeps the first C of its choosers in
+            // the order (rank, token index).
+            std::vector<int> idx(cand.size());
+            std::iota(idx.begin(), idx.end(), 0);
+            const std::vector<int>& rk = cand_rank[e];
+            std::stable_sort(idx.begin(), idx.end(), [&](int a, int b) { return rk[a] < rk[b]; });
+            for (int m = 0; m < n_keep; ++m) kept.push_back(cand[idx[m]]);
+            std::sort(kept.begin(), kept.end());
+        } else if (mode == MODE_BIDIR_STRICT) {
+            // Variant of the bidirectional rule: the pair (t, e) survives iff t lists e (Eq. 5) and t is
+            // among e's top-min(C, T) tokens taken over ALL tokens (pure expert choice), i.e. the
+            // intersection of the two pure phases.  A subset of what Eq. 6 keeps.
+            std::vector<int> all(T);
+            std::iota(all.begin(), all.end(), 0);
+            std::stable_sort(all.begin(), all.end(), ByScoreThenIndex{score + e, (size_t)E});
+            std::vector<char> top(T, 0);
+            for (int m = 0; m < std::min(capacity, T); ++m) top[all[m]] = 1;
+            for (int t : cand) if (top[t]) kept.push_back(t);     // cand is in ascending token order
+            n_keep = (int)kept.size();
         } else {
             // Eq. 6 / pure ECR: the C candidates with the highest affinity to e
             std::stable_sort(cand.begin(), cand.end(), ByScoreThenIndex{score + e, (size_t)E});
@@ -326,16 +351,33 @@ int etr_ref_expert_ffn(int d, int E, int capacity, int H, int dtype, const void*
 // ---------------------------------------------------------------------------
 // Combine (Eq. 1): out[t][:] = sum over experts e (ascending) that kept t of
 // gate[t][e] * yp[e][slot_of[t][e]][:]; accumulated in double, rounded once.
+// gate_norm = 1 is the variant in which the gate weights of a token are renormalised over the
+// experts that kept it (they then sum to one, as in Top-l gating of the sparse baselines);
+// gate_norm = 0 uses the softmax over all experts as it is.
 // ---------------------------------------------------------------------------
+}  // extern "C"
+namespace {
+template <typename G>
+double kept_gate_sum(const G* gate_row, const int32_t* slot_row, int E, int gate_norm) {
+    if (!gate_norm) return 1.0;
+    double s = 0;
+    for (int e = 0; e < E; ++e)
+        if (slot_row[e] >= 0) s += double(gate_row[e]);
+    return s > 0 ? s : 1.0;
+}
+}  // namespace
+extern "C" {
+
 int etr_ref_combine(int T, int d, int E, int capacity, int dtype, const double* yp, const float* gate,
-                    const int32_t* slot_of, void* out) {
+                    const int32_t* slot_of, void* out, int gate_norm) {
 #pragma omp parallel for schedule(static)
     for (int t = 0; t < T; ++t) {
         std::vector<double> acc(d, 0.0);
+        const double norm = kept_gate_sum(gate + (size_t)t * E, slot_of + (size_t)t * E, E, gate_norm);
         for (int e = 0; e < E; ++e) {
             int s = slot_of[(size_t)t * E + e];
             if (s < 0) continue;
-            const double gt = gate[(size_t)t * E + e];
+            const double gt = gate[(size_t)t * E + e] / norm;
             const double* yr = yp + ((size_t)e * capacity + s) * d;
             for (int j = 0; j < d; ++j) acc[j] += gt * yr[j];
         }
@@ -357,7 +399,7 @@ int etr_ref_moe_forward(int T, int d, int E, int D, int k, int capacity, int H, 
                         const void* x, const float* w_emb, const void* w_gate, const void* w_up,
                         const void* w_down, const float* score_in, const int32_t* tokens, int n_tokens,
                         void* out, float* score_out, float* gate_out, int32_t* topk_out, int32_t* slot_of_out,
-                        int32_t* slot_token_out, int32_t* counts_out) {
+                        int32_t* slot_token_out, int32_t* counts_out, int gate_norm) {
     std::vector<float> score((size_t)T * E), gate((size_t)T * E);
     int rc = 0;
     if (!score_in) {
@@ -406,7 +448,8 @@ int etr_ref_moe_forward(int T, int d, int E, int D, int k, int capacity, int H, 
     std::vector<double> acc((size_t)n_tokens * d, 0.0);
     for (int r = 0; r < n_pairs; ++r) {          // pairs are listed token-major, experts ascending
         int i = pair_token_pos[r];
-        double gt = gate[(size_t)tokens[i] * E + pair_expert[r]];
+        double gt = gate[(size_t)tokens[i] * E + pair_expert[r]] /
+                    kept_gate_sum(gate.data() + (size_t)tokens[i] * E, slot_of.data() + (size_t)tokens[i] * E, E, gate_norm);
         for (int j = 0; j < d; ++j) acc[(size_t)i * d + j] += gt * y[(size_t)r * d + j];
     }
     for (size_t i = 0; i < (size_t)n_tokens * d; ++i) store_elem(out, dtype, i, acc[i]);
@@ -546,7 +589,8 @@ inline double sigmoid(double a) { return 1.0 / (1.0 + std::exp(-a)); }
 int etr_ref_backward_tokens(int T, int d, int E, int D, int H, int dtype, int cos_mode,
                             const void* x, const float* w_emb, const void* w_gate, const void* w_up,
                             const void* w_down, const int32_t* slot_of, const void* dout,
-                            const int32_t* tokens, int n_tokens, double* dx, double* dgate, double* dscore) {
+                            const int32_t* tokens, int n_tokens, double* dx, double* dgate, double* dscore,
+                            int gate_norm) {
     if (d <= 0 || E <= 0 || D <= 0 || d % D != 0 || H <= 0) return 2;
     const int P = d / D;
     const std::vector<double> wnorm = embedding_norms(E, P, w_emb);
@@ -558,6 +602,8 @@ int etr_ref_backward_tokens(int T, int d, int E, int D, int H, int dtype, int co
         TokenRoute r;
         route_token_double(t, d, E, D, dtype, cos_mode, x, w_emb, wnorm, r);
         std::vector<double> xt(d), go(d), acc(d, 0.0), a(H), b(H), h(H), dh(H), dg(E, 0.0);
+        // effective weights: the softmax gate, or (variant) renormalised over the experts that kept the token
+        const double norm = kept_gate_sum(r.gate.data(), slot_of + (size_t)t * E, E, gate_norm);
         for (int j = 0; j < d; ++j) {
             xt[j] = load_elem(x, dtype, (size_t)t * d + j);
             go[j] = load_elem(dout, dtype, (size_t)t * d + j);
@@ -580,7 +626,7 @@ int etr_ref_backward_tokens(int T, int d, int E, int D, int H, int dtype, int co
                 for (int u = 0; u < H; ++u) {
                     const double w = load_elem(w_down, dtype, base + u);
                     y += w * h[u];
-                    dh[u] += w * r.gate[e] * go[j];
+                    dh[u] += w * (r.gate[e] / norm) * go[j];
                 }
                 dgte += go[j] * y;
             }
@@ -593,6 +639,13 @@ int etr_ref_backward_tokens(int T, int d, int E, int D, int H, int dtype, int co
                 for (int j = 0; j < d; ++j)
                     acc[j] += load_elem(w_gate, dtype, base + j) * da + load_elem(w_up, dtype, base + j) * db;
             }
+        }
+        // dg holds d out / d (effective weight); with renormalised weights g'_e = g_e / S, S = sum over the
+        // kept experts: d / d g_e = (dg'_e - sum_kept dg'_i g'_i) / S for kept e, 0 otherwise
+        if (gate_norm) {
+            double m2 = 0;
+            for (int e = 0; e < E; ++e) if (slot_of[(size_t)t * E + e] >= 0) m2 += dg[e] * r.gate[e] / norm;
+            for (int e = 0; e < E; ++e) dg[e] = slot_of[(size_t)t * E + e] >= 0 ? (dg[e] - m2) / norm : 0.0;
         }
         // softmax backward, then the affinity's own derivative
         double mix = 0;
@@ -632,7 +685,7 @@ int etr_ref_backward_hidden_units(int T, int d, int E, int D, int H, int dtype, 
                                   const void* x, const float* w_emb, const void* w_gate, const void* w_up,
                                   const void* w_down, const int32_t* slot_of, const void* dout,
                                   const int32_t* unit_expert, const int32_t* unit_index, int n_units,
-                                  double* dwg_rows, double* dwu_rows, double* dwd_cols) {
+                                  double* dwg_rows, double* dwu_rows, double* dwd_cols, int gate_norm) {
     if (d <= 0 || E <= 0 || D <= 0 || d % D != 0 || H <= 0) return 2;
     const int P = d / D;
     const std::vector<double> wnorm = embedding_norms(E, P, w_emb);
@@ -642,7 +695,8 @@ int etr_ref_backward_hidden_units(int T, int d, int E, int D, int H, int dtype, 
     for (int t = 0; t < T; ++t) {
         TokenRoute r;
         route_token_double(t, d, E, D, dtype, cos_mode, x, w_emb, wnorm, r);
-        for (int e = 0; e < E; ++e) gate[(size_t)t * E + e] = r.gate[e];
+        const double norm = kept_gate_sum(r.gate.data(), slot_of + (size_t)t * E, E, gate_norm);
+        for (int e = 0; e < E; ++e) gate[(size_t)t * E + e] = r.gate[e] / norm;      // effective weights
     }
     int bad = 0;
 #pragma omp parallel for schedule(dynamic)

@@ -18,7 +18,7 @@ _SRC = os.path.join(_HERE, "etr_ref.cpp")
 _LIB = os.path.join(_HERE, "libetr_ref.so")
 
 DT_F32, DT_BF16 = 0, 1
-MODE_TCR, MODE_ECR, MODE_BIDIR = 0, 1, 2
+MODE_TCR, MODE_ECR, MODE_BIDIR, MODE_TCR_RANK, MODE_BIDIR_STRICT = 0, 1, 2, 3, 4
 COS_FULL, COS_POOLED = 0, 1
 
 
@@ -128,18 +128,18 @@ def expert_ffn(xp: np.ndarray, counts: np.ndarray, w_gate, w_up, w_down, dtype: 
     return yp
 
 
-def combine(yp: np.ndarray, gate: np.ndarray, slot_of: np.ndarray, dtype: int):
+def combine(yp: np.ndarray, gate: np.ndarray, slot_of: np.ndarray, dtype: int, gate_norm: int = 0):
     E, C, d = yp.shape
     T = gate.shape[0]
     assert yp.dtype == np.float64
     out = np.empty((T, d), _elem(dtype))
-    _check(lib().etr_ref_combine(T, d, E, C, dtype, _p(yp), _p(gate), _p(slot_of), _p(out)), "combine")
+    _check(lib().etr_ref_combine(T, d, E, C, dtype, _p(yp), _p(gate), _p(slot_of), _p(out), gate_norm), "combine")
     return out
 
 
 def moe_forward(x, w_emb, w_gate, w_up, w_down, *, D: int, k: int, capacity: int, dtype: int, mode: int,
                 cos_mode: int = COS_FULL, score_in: Optional[np.ndarray] = None,
-                tokens: Optional[np.ndarray] = None):
+                tokens: Optional[np.ndarray] = None, gate_norm: int = 0):
     """Returns a dict: out (rows for `tokens`, or all T), score, gate, topk, slot_of, slot_token, counts."""
     T, d = x.shape
     E = w_emb.shape[0]
@@ -160,7 +160,7 @@ def moe_forward(x, w_emb, w_gate, w_up, w_down, *, D: int, k: int, capacity: int
     _check(lib().etr_ref_moe_forward(
         T, d, E, D, k, capacity, H, dtype, mode, cos_mode, _p(x), _p(w_emb), _p(w_gate), _p(w_up), _p(w_down),
         _p(score_in), _p(tokens), n_tok, _p(res["out"]), _p(res["score"]), _p(res["gate"]), _p(res["topk"]),
-        _p(res["slot_of"]), _p(res["slot_token"]), _p(res["counts"])), "moe_forward")
+        _p(res["slot_of"]), _p(res["slot_token"]), _p(res["counts"]), gate_norm), "moe_forward")
     return res
 
 
@@ -185,7 +185,7 @@ def capacity_lower_bound(score: np.ndarray, d: int):
 
 
 def backward_tokens(x, w_emb, w_gate, w_up, w_down, slot_of, dout, tokens, *, D: int, dtype: int,
-                    cos_mode: int = COS_FULL):
+                    cos_mode: int = COS_FULL, gate_norm: int = 0):
     """Per-token part of the layer's backward (routing tables fixed): dx[n][d], dgate[n][E], dscore[n][E], float64."""
     T, d = x.shape
     E, H = w_gate.shape[0], w_gate.shape[1]
@@ -194,13 +194,14 @@ def backward_tokens(x, w_emb, w_gate, w_up, w_down, slot_of, dout, tokens, *, D:
     assert slot_of.dtype == np.int32 and slot_of.shape == (T, E) and dout.shape == (T, d) and dout.dtype == x.dtype
     dx, dg, ds = np.empty((n, d), np.float64), np.empty((n, E), np.float64), np.empty((n, E), np.float64)
     _check(lib().etr_ref_backward_tokens(T, d, E, D, H, dtype, cos_mode, _p(x), _p(w_emb), _p(w_gate), _p(w_up),
-                                         _p(w_down), _p(slot_of), _p(dout), _p(tokens), n, _p(dx), _p(dg), _p(ds)),
+                                         _p(w_down), _p(slot_of), _p(dout), _p(tokens), n, _p(dx), _p(dg), _p(ds),
+                                         gate_norm),
            "backward_tokens")
     return dx, dg, ds
 
 
 def backward_hidden_units(x, w_emb, w_gate, w_up, w_down, slot_of, dout, unit_expert, unit_index, *, D: int,
-                          dtype: int, cos_mode: int = COS_FULL):
+                          dtype: int, cos_mode: int = COS_FULL, gate_norm: int = 0):
     """Per-hidden-unit part of the backward: rows of dWg and dWu and columns of dWd, each [n][d] float64."""
     T, d = x.shape
     E, H = w_gate.shape[0], w_gate.shape[1]
@@ -211,19 +212,20 @@ def backward_hidden_units(x, w_emb, w_gate, w_up, w_down, slot_of, dout, unit_ex
     gw, uw, dw = (np.empty((n, d), np.float64) for _ in range(3))
     _check(lib().etr_ref_backward_hidden_units(T, d, E, D, H, dtype, cos_mode, _p(x), _p(w_emb), _p(w_gate), _p(w_up),
                                                _p(w_down), _p(slot_of), _p(dout), _p(ue), _p(ui), n, _p(gw), _p(uw),
-                                               _p(dw)), "backward_hidden_units")
+                                               _p(dw), gate_norm), "backward_hidden_units")
     return gw, uw, dw
 
 
-def moe_backward(x, w_emb, w_gate, w_up, w_down, slot_of, dout, *, D: int, dtype: int, cos_mode: int = COS_FULL):
+def moe_backward(x, w_emb, w_gate, w_up, w_down, slot_of, dout, *, D: int, dtype: int, cos_mode: int = COS_FULL,
+                 gate_norm: int = 0):
     """Whole gradient (small sizes only): dict dx[T][d], dgate, dscore [T][E], dw_gate, dw_up [E][H][d], dw_down [E][d][H]."""
     T, d = x.shape
     E, H = w_gate.shape[0], w_gate.shape[1]
     dx, dg, ds = backward_tokens(x, w_emb, w_gate, w_up, w_down, slot_of, dout, np.arange(T), D=D, dtype=dtype,
-                                 cos_mode=cos_mode)
+                                 cos_mode=cos_mode, gate_norm=gate_norm)
     ue, ui = np.repeat(np.arange(E), H), np.tile(np.arange(H), E)
     gw, uw, dw = backward_hidden_units(x, w_emb, w_gate, w_up, w_down, slot_of, dout, ue, ui, D=D, dtype=dtype,
-                                       cos_mode=cos_mode)
+                                       cos_mode=cos_mode, gate_norm=gate_norm)
     return dict(dx=dx, dgate=dg, dscore=ds, dw_gate=gw.reshape(E, H, d), dw_up=uw.reshape(E, H, d),
                 dw_down=np.ascontiguousarray(dw.reshape(E, H, d).transpose(0, 2, 1)))
 

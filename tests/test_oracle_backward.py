@@ -24,7 +24,7 @@ def _layer(seed, T=24, d=16, E=4, D=2, H=12, std=0.3):
     return x, w_emb, wg, wu, wd, dout
 
 
-def _torch_forward(x, w_emb, wg, wu, wd, slot_of, D, cos):
+def _torch_forward(x, w_emb, wg, wu, wd, slot_of, D, cos, gate_norm=0):
     """Layer forward with library ops in float64; routing tables are constants."""
     T, d = x.shape
     E, P = w_emb.shape
@@ -35,10 +35,14 @@ def _torch_forward(x, w_emb, wg, wu, wd, slot_of, D, cos):
         score = (g @ w_emb.T) / (g.norm(dim=1, keepdim=True) * w_emb.norm(dim=1)[None, :])
     gate = torch.softmax(score, dim=1)
     keep = torch.from_numpy(slot_of >= 0)
+    weight = gate * keep
+    if gate_norm:
+        total = weight.sum(dim=1, keepdim=True)
+        weight = weight / torch.where(total > 0, total, torch.ones_like(total))
     out = torch.zeros_like(x)
     for e in range(E):
         y = (torch.nn.functional.silu(x @ wg[e].T) * (x @ wu[e].T)) @ wd[e].T
-        out = out + (gate[:, e] * keep[:, e])[:, None] * y
+        out = out + weight[:, e][:, None] * y
     return out, score, gate
 
 
@@ -73,6 +77,27 @@ def test_backward_matches_reverse_mode_differentiation(oracle, mode, cos):
     np.testing.assert_allclose(r["dw_down"], twd.grad.numpy(), rtol=1e-9, atol=1e-11)
     np.testing.assert_allclose(r["dgate"], tgate.grad.numpy(), rtol=1e-9, atol=1e-11)
     np.testing.assert_allclose(r["dscore"], tscore.grad.numpy(), rtol=1e-9, atol=1e-11)
+
+
+@pytest.mark.parametrize("mode,cos", [(TCR, FULL), (BIDIR, POOLED)])
+def test_backward_with_renormalised_gate(oracle, mode, cos):
+    D, k, C = 2, 2, 8
+    x, w_emb, wg, wu, wd, dout = _layer(80 + mode)
+    score, gate, slot_of, slot_token, counts = _tables(oracle, x, w_emb, D, k, C, mode, cos)
+    tx, twg, twu, twd = (torch.from_numpy(a.astype(np.float64)).requires_grad_(True) for a in (x, wg, wu, wd))
+    out, tscore, tgate = _torch_forward(tx, torch.from_numpy(w_emb.astype(np.float64)), twg, twu, twd, slot_of, D, cos, 1)
+    ref = oracle.moe_forward(x, w_emb, wg, wu, wd, D=D, k=k, capacity=C, dtype=oracle.DT_F32, mode=mode, cos_mode=cos,
+                             gate_norm=1)
+    np.testing.assert_array_equal(ref["slot_of"], slot_of)
+    np.testing.assert_allclose(out.detach().numpy(), ref["out"], rtol=2e-6, atol=2e-6)
+    tgate.retain_grad(); tscore.retain_grad()
+    out.backward(torch.from_numpy(dout.astype(np.float64)))
+    r = oracle.moe_backward(x, w_emb, wg, wu, wd, slot_of, dout, D=D, dtype=oracle.DT_F32, cos_mode=cos, gate_norm=1)
+    for name, t in (("dx", tx), ("dw_gate", twg), ("dw_up", twu), ("dw_down", twd), ("dgate", tgate), ("dscore", tscore)):
+        np.testing.assert_allclose(r[name], t.grad.numpy(), rtol=1e-9, atol=1e-11, err_msg=name)
+    # and it is a different gradient from the plain gate's
+    r0 = oracle.moe_backward(x, w_emb, wg, wu, wd, slot_of, dout, D=D, dtype=oracle.DT_F32, cos_mode=cos)
+    assert np.max(np.abs(r0["dx"] - r["dx"])) > 1e-3
 
 
 def _oracle_out_f64(oracle, x, w_emb, wg, wu, wd, slot_of, slot_token, counts, D, cos):

@@ -171,3 +171,25 @@ def test_layer_bf16_path(oracle):
     # the bf16 output is the fp32-path output rounded once more (double -> bf16 vs double -> fp32)
     np.testing.assert_allclose(oracle.bf16_bits_to_f64(rb["out"]), rf["out"].astype(np.float64), rtol=2 ** -8, atol=1e-30)
     assert ((rf["slot_of"] >= 0).sum(1) == 0).any() and np.all(rb["out"][(rf["slot_of"] >= 0).sum(1) == 0] == 0)
+
+
+def test_renormalised_gate_variant(oracle):
+    """gate_norm = 1: a token's weights are renormalised over the experts that kept it, so they sum to one and
+    equal experts give out = FFN(x) for every token that is kept at all, whatever subset kept it."""
+    rng = np.random.default_rng(21)
+    T, d, E, H, D = 40, 16, 4, 12, 2
+    x, w_emb, wg, wu, wd = _rand_layer(rng, T, d, E, H, d // D)
+    wg[:] = wg[0]; wu[:] = wu[0]; wd[:] = wd[0]
+    r = oracle.moe_forward(x, w_emb, wg, wu, wd, D=D, k=2, capacity=9, dtype=oracle.DT_F32, mode=BIDIR, gate_norm=1)
+    kept = (r["slot_of"] >= 0).sum(1)
+    assert 0 < (kept == 0).sum() and (kept == 1).any() and (kept == 2).any()
+    ffn = _swiglu_torch(x, wg[0], wu[0], wd[0])
+    np.testing.assert_allclose(r["out"][kept > 0], ffn[kept > 0], rtol=2e-6, atol=2e-6)
+    assert not r["out"][kept == 0].any()
+    # the stage function agrees with the chain, and differs from the plain gate exactly by the per-token factor
+    xp = oracle.dispatch(x, r["slot_token"], r["counts"], oracle.DT_F32)
+    yp = oracle.expert_ffn(xp, r["counts"], wg, wu, wd, oracle.DT_F32)
+    np.testing.assert_array_equal(oracle.combine(yp, r["gate"], r["slot_of"], oracle.DT_F32, gate_norm=1), r["out"])
+    plain = oracle.combine(yp, r["gate"], r["slot_of"], oracle.DT_F32).astype(np.float64)
+    s = np.where(r["slot_of"] >= 0, r["gate"].astype(np.float64), 0).sum(1)
+    np.testing.assert_allclose(plain[kept > 0] / s[kept > 0, None], r["out"][kept > 0], rtol=3e-6, atol=1e-7)

@@ -250,3 +250,77 @@ def test_adaptive_brute_force(oracle, seed):
         for e in range(E):
             cands = list(range(T)) if mode == ECR else list(np.flatnonzero(chose[:, e]))
             assert list(slot_token[e, :counts[e]]) == _adaptive_brute(S, e, cands, C, thr), (mode, e)
+
+
+# ---------------------------------------------------------------------------------------
+# variant readings: rank-major token choice, strict intersection of the two pure phases
+# ---------------------------------------------------------------------------------------
+TCR_RANK, STRICT = 3, 4
+
+
+def test_variants_worked_example(oracle):
+    g = load_golden("select_worked_example.json")
+    S = np.array(g["score"], np.float32)
+    C = g["capacity"]
+    for kname, k in (("k1", 1), ("k2", 2)):
+        for mname, mode in (("tcr_rank", TCR_RANK), ("strict", STRICT)):
+            topk, slot_of, slot_token, counts = oracle.select(S, k, C, mode)
+            assert topk.tolist() == g[kname]["topk"]
+            assert [list(map(int, s)) for s in kept_sets(slot_token, counts)] == g[kname][mname]["kept"], (kname, mname)
+            check_permutation_tables(6, 3, C, slot_of, slot_token, counts)
+
+
+def _rank_major_sequential(topk, E, C):
+    """The classic sequential statement: walk the choice ranks in turn, inside a rank the tokens in
+    order; a choice is granted while the expert still has room."""
+    T, k = topk.shape
+    used = [0] * E
+    kept = [[] for _ in range(E)]
+    for r in range(k):
+        for t in range(T):
+            e = int(topk[t, r])
+            if used[e] < C:
+                used[e] += 1
+                kept[e].append(t)
+    return [sorted(s) for s in kept]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_variants_brute_force(oracle, seed):
+    rng = np.random.default_rng(500 + seed)
+    T, E = int(rng.integers(5, 60)), int(rng.integers(2, 7))
+    k = int(rng.integers(1, E + 1))
+    C = int(rng.integers(1, T + 2))
+    S = _scores(rng, T, E, 3 if seed % 2 else None)
+    topk, slot_of, slot_token, counts = oracle.select(S, k, C, TCR_RANK)
+    check_permutation_tables(T, E, C, slot_of, slot_token, counts)
+    assert [list(map(int, s)) for s in kept_sets(slot_token, counts)] == _rank_major_sequential(topk, E, C)
+    # strict: choosers (Eq. 5) intersected with the top-min(C, T) of all tokens under (score desc, index asc)
+    topk2, slot_of, slot_token, counts = oracle.select(S, k, C, STRICT)
+    np.testing.assert_array_equal(topk2, topk)
+    check_permutation_tables(T, E, C, slot_of, slot_token, counts)
+    for e in range(E):
+        top = set(sorted(range(T), key=lambda t: (-float(S[t, e]), t))[:min(C, T)])
+        want = sorted(t for t in range(T) if e in topk[t] and t in top)
+        assert list(map(int, slot_token[e, :counts[e]])) == want
+
+
+def test_variants_reduce_to_the_plain_modes(oracle):
+    rng = np.random.default_rng(77)
+    T, E, C = 50, 5, 7
+    S = _scores(rng, T, E)
+    # one choice per token: rank-major priority is the position priority
+    for a, b in zip(oracle.select(S, 1, C, TCR_RANK), oracle.select(S, 1, C, TCR)):
+        np.testing.assert_array_equal(a, b)
+    # every token lists every expert: the intersection is pure expert choice
+    for a, b in zip(oracle.select(S, E, C, STRICT)[1:], oracle.select(S, E, C, ECR)[1:]):
+        np.testing.assert_array_equal(a, b)
+    # capacity never binds: both variants keep every chooser, like Eq. 6
+    for mode in (TCR_RANK, STRICT):
+        for a, b in zip(oracle.select(S, 2, T, mode), oracle.select(S, 2, T, BIDIR)):
+            np.testing.assert_array_equal(a, b)
+    # strict is a subset of Eq. 6's keep set
+    strict, bidir = oracle.select(S, 2, C, STRICT)[1], oracle.select(S, 2, C, BIDIR)[1]
+    assert np.all((strict < 0) | (bidir >= 0))
+    with pytest.raises(RuntimeError):
+        oracle.select_adaptive(S, 2, C, STRICT, 0.5)     # the affinity-sum threshold is not defined for it
