@@ -48,7 +48,11 @@ typedef enum { ETR_F32 = 0, ETR_BF16 = 1 } etr_dtype;
 
 /* Which half of the bidirectional selection is active; a host-side choice
  * (Sec. Training Strategy: token choice early in training, expert choice late). */
-typedef enum { ETR_MODE_TCR = 0, ETR_MODE_ECR = 1, ETR_MODE_BIDIR = 2 } etr_mode;
+typedef enum {
+    ETR_MODE_TCR = 0, ETR_MODE_ECR = 1, ETR_MODE_BIDIR = 2,
+    /* variant readings (see etr_select) */
+    ETR_MODE_TCR_RANK = 3, ETR_MODE_BIDIR_STRICT = 4
+} etr_mode;
 
 /* Norm used in the cosine of Eq. 4 once the pooled width P may differ from E:
  * FULL   cos(x_t, lift(w_e)) in R^d, lift = every pooled coordinate spread evenly
@@ -61,6 +65,8 @@ typedef struct {
     int32_t dtype;      /* etr_dtype    */
     int32_t mode;       /* etr_mode     */
     int32_t cos;        /* etr_cos_mode */
+    int32_t gate_norm;  /* 0: weights of Eq. 1 = softmax over all experts, as it is;
+                           1 (variant): renormalised over the experts that kept the token */
 } etr_config;
 
 /* Bytes of device workspace for this config: etr_workspace_bytes is what
@@ -92,6 +98,13 @@ etr_status etr_route(const etr_config* cfg, const void* x, const float* w_emb,
  *         lowest-index tokens among those that listed it
  *   ECR   expert e keeps its min(capacity, T) highest-score tokens of all T; k ignored
  *   BIDIR expert e keeps its `capacity` highest-score tokens among those that listed it
+ *   TCR_RANK (variant of TCR for k > 1, where the paper's rule is stated for one choice only):
+ *         every token's first choice is served before any second choice, and so on; expert e
+ *         keeps the first `capacity` of its choosers in the order (position in the token's list,
+ *         token index)
+ *   BIDIR_STRICT (variant of BIDIR): the pair survives iff the token lists the expert and is among
+ *         the expert's min(capacity, T) highest-score tokens of ALL T: the intersection of the two
+ *         pure phases, a subset of BIDIR's keep set
  *   score        [T][E]        fp32  in
  *   topk_expert  [T][k]        int32 out  token's experts by descending score; may be NULL;
  *                                         not written in ECR mode
@@ -128,6 +141,8 @@ etr_status etr_expert_ffn(const etr_config* cfg, const void* xp, const int32_t* 
 
 /* Gate-weighted sum of Eq. 1 over the experts that kept the token, ascending e, fp32
  * accumulation, one rounding to dtype.  A token kept by no expert gives a zero row.
+ * With cfg->gate_norm = 1 the weights gate[t][e] of a token are divided by their sum over the
+ * experts that kept it.
  *   yp [E][capacity][d] in; gate [T][E], slot_of [T][E] in; out [T][d] dtype out
  */
 etr_status etr_combine(const etr_config* cfg, const void* yp, const float* gate,
@@ -158,7 +173,8 @@ etr_status etr_moe_forward(const etr_config* cfg, const void* x, const float* w_
  *    reaches the threshold (all candidates if the positive affinities never get there); it keeps
  *    min(capacity, that prefix length).  Affinities are summed as integers round(clamp(s,-1,1)*2^30),
  *    so the decision does not depend on the order of summation.  Ignored in TCR mode (position
- *    priority); T must be <= 2^22 when it is on.
+ *    priority, also TCR_RANK); not defined for BIDIR_STRICT (ETR_ERR_UNSUPPORTED); T must be
+ *    <= 2^22 when it is on.
  * Everything else as etr_select. */
 etr_status etr_select_adaptive(const etr_config* cfg, const float* score, const int32_t* capacity_dev,
                                float affinity_sum_threshold, int32_t* topk_expert, int32_t* slot_of,

@@ -27,7 +27,8 @@ STAGE_NAMES = ("route", "select", "dispatch", "ffn_gate_up", "ffn_down", "combin
 
 
 class EtrConfig(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("T", "d", "E", "D", "k", "capacity", "H", "dtype", "mode", "cos")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("T", "d", "E", "D", "k", "capacity", "H", "dtype", "mode", "cos",
+                                             "gate_norm")]
 
 
 class EtrError(RuntimeError):
@@ -77,10 +78,10 @@ def load_library():
 
 
 def make_config(shape: EtrShape, mode: Optional[int] = None, capacity: Optional[int] = None,
-                cos: Optional[int] = None) -> EtrConfig:
+                cos: Optional[int] = None, gate_norm: int = 0) -> EtrConfig:
     return EtrConfig(shape.T, shape.d, shape.E, shape.D, shape.k,
                      shape.capacity if capacity is None else capacity, shape.H, shape.dtype,
-                     shape.mode if mode is None else mode, shape.cos if cos is None else cos)
+                     shape.mode if mode is None else mode, shape.cos if cos is None else cos, gate_norm)
 
 
 def _ptr(t: Optional[torch.Tensor]) -> ctypes.c_void_p:

@@ -16,7 +16,8 @@ etr_status check_config(const etr_config* c) {
     if (!c) return ETR_ERR_NULL;
     if (c->T <= 0 || c->d <= 0 || c->E <= 0 || c->D <= 0 || c->H <= 0) return ETR_ERR_SHAPE;
     if (c->d % c->D != 0 || c->capacity < 1) return ETR_ERR_SHAPE;
-    if (c->mode != ETR_MODE_TCR && c->mode != ETR_MODE_ECR && c->mode != ETR_MODE_BIDIR) return ETR_ERR_UNSUPPORTED;
+    if (c->mode < ETR_MODE_TCR || c->mode > ETR_MODE_BIDIR_STRICT) return ETR_ERR_UNSUPPORTED;
+    if (c->gate_norm != 0 && c->gate_norm != 1) return ETR_ERR_UNSUPPORTED;
     if (c->mode != ETR_MODE_ECR && (c->k < 1 || c->k > c->E)) return ETR_ERR_SHAPE;
     if (c->dtype != ETR_F32 && c->dtype != ETR_BF16) return ETR_ERR_UNSUPPORTED;
     if (c->cos != ETR_COS_FULL && c->cos != ETR_COS_POOLED) return ETR_ERR_UNSUPPORTED;
@@ -131,6 +132,7 @@ etr_status etr_select_adaptive(const etr_config* cfg, const float* score, const 
     if (capacity_dev && (reinterpret_cast<uintptr_t>(capacity_dev) & 3u)) return ETR_ERR_ALIGN;
     if (!(affinity_sum_threshold == affinity_sum_threshold)) return ETR_ERR_SHAPE;           // NaN
     if (cfg->T > (1 << 22) && affinity_sum_threshold > 0.f) return ETR_ERR_UNSUPPORTED;       // fixed-point sum headroom
+    if (cfg->mode == ETR_MODE_BIDIR_STRICT && affinity_sum_threshold > 0.f) return ETR_ERR_UNSUPPORTED;
     if (ws_bytes < select_ws_bytes(cfg->T, cfg->E)) return ETR_ERR_WORKSPACE;
     const SelectWs w = select_ws_carve(ws, cfg->T, cfg->E);
     long long need = 0;

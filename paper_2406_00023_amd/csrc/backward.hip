@@ -194,6 +194,21 @@ __global__ __launch_bounds__(kTileThreads) void swiglu_backward_kernel(
     store_transposed<T>(tb, dbT + tb_off, Cp, n0, H, s0, Cp);
 }
 
+// Variant with renormalised weights: gate_eff[t][e] = gate[t][e] / (sum of gate[t][.] over the experts that kept t)
+// for kept pairs, 0 otherwise.  One thread per token.
+__global__ __launch_bounds__(256) void gate_eff_kernel(const float* __restrict__ gate, const int32_t* __restrict__ slot_of,
+                                                       float* __restrict__ gate_eff, int T_, int E) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= T_) return;
+    float sum = 0.f;
+    for (int e = 0; e < E; ++e)
+        if (slot_of[static_cast<size_t>(t) * E + e] >= 0) sum += gate[static_cast<size_t>(t) * E + e];
+    const float inv = sum > 0.f ? 1.0f / sum : 0.f;
+    for (int e = 0; e < E; ++e)
+        gate_eff[static_cast<size_t>(t) * E + e] =
+            slot_of[static_cast<size_t>(t) * E + e] >= 0 ? gate[static_cast<size_t>(t) * E + e] * inv : 0.f;
+}
+
 // dx[t] = sum_e dXp[e][slot_of[t][e]] + router term; one wavefront per token.
 // Router term: dscore[e] = gate[e] (dgate[e] - sum_e' dgate[e'] gate[e']); with Eq. 4 in the form
 //   FULL:   score = sqrt(D) <g, w> / (|x| |w|)  ->  d score / d x_j = sqrt(D) w[p(j)] / (D |x| |w|) - score x_j / |x|^2
@@ -204,7 +219,7 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
                                                  const int32_t* __restrict__ slot_of, const float* __restrict__ dgate_part, int n_part,
                                                  const T* __restrict__ dxp, T* __restrict__ dx, float* __restrict__ dgate_out,
                                                  float* __restrict__ dscore_out, int T_, int d, int E, int D, int C,
-                                                 int cos_mode) {
+                                                 int cos_mode, int gate_norm) {
     extern __shared__ float sm[];
     const int P = d / D;
     float* w = sm;                       // [E][P]
@@ -260,6 +275,18 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
             slot = -1;
         }
     }
+    if (gate_norm) {
+        // dg is the gradient of the renormalised weight g' = g / S (S = sum of g over the kept experts);
+        // d / d g_e = (dg'_e - sum_kept dg'_i g'_i) / S for kept e, 0 otherwise
+        float S = slot >= 0 ? gt : 0.f;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) S += __shfl_xor(S, o, 64);
+        const float inv = S > 0.f ? 1.0f / S : 0.f;
+        float m2 = slot >= 0 ? dg * gt * inv : 0.f;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) m2 += __shfl_xor(m2, o, 64);
+        dg = slot >= 0 ? (dg - m2) * inv : 0.f;
+    }
     float mix = dg * gt;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) mix += __shfl_xor(mix, o, 64);
@@ -311,7 +338,7 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
 }
 
 struct BackwardWs {
-    size_t wdT, wguT, a, b, u, dab, daT, dbT, hT, xpT, dypT, dxp, dgate_part, total;
+    size_t wdT, wguT, a, b, u, dab, daT, dbT, hT, xpT, dypT, dxp, dgate_part, gate_eff, total;
 };
 
 BackwardWs backward_layout(const etr_config& c) {
@@ -333,6 +360,7 @@ BackwardWs backward_layout(const etr_config& c) {
     w.dypT = take(E * d * Cp * es);
     w.dxp = take(E * C * d * es);
     w.dgate_part = take((H + kTile - 1) / kTile * E * C * 4);
+    w.gate_eff = take(static_cast<size_t>(c.T) * E * 4);
     w.total = off;
     return w;
 }
@@ -358,18 +386,25 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
     hipLaunchKernelGGL(transpose_kernel<T>, dim3(cd, cH, E), dim3(kTileThreads), 0, st, static_cast<const T*>(w_up),
                        at(L.wguT), H, d, 2 * H, H);
     ETR_BW(hipGetLastError());
+    // weights of Eq. 1 as the forward applied them
+    const float* gate_w = gate;
+    if (c.gate_norm) {
+        float* ge = reinterpret_cast<float*>(base + L.gate_eff);
+        hipLaunchKernelGGL(gate_eff_kernel, dim3((Tn + 255) / 256), dim3(256), 0, st, gate, slot_of, ge, Tn, E);
+        gate_w = ge;
+    }
     // a, b recomputed from the gathered token rows; u = gathered upstream gradient times Wd
     GroupedGemm g1{x, w_gate, w_up, at(L.a), at(L.b), counts, nullptr, slot_token, E, C, H, d, 0, 0, Tn, GEMM_DUAL, c.dtype};
     ETR_BW(launch_grouped_gemm(g1, st));
     GroupedGemm g2{dout, at(L.wdT), nullptr, at(L.u), nullptr, counts, nullptr, slot_token, E, C, H, d, 0, 0, Tn, GEMM_PLAIN, c.dtype};
     ETR_BW(launch_grouped_gemm(g2, st));
-    hipLaunchKernelGGL(swiglu_backward_kernel<T>, dim3(cH, cC, E), dim3(kTileThreads), 0, st, at(L.u), at(L.a), at(L.b), gate,
+    hipLaunchKernelGGL(swiglu_backward_kernel<T>, dim3(cH, cC, E), dim3(kTileThreads), 0, st, at(L.u), at(L.a), at(L.b), gate_w,
                        slot_token, counts, at(L.dab), at(L.daT), at(L.dbT), at(L.hT),
                        reinterpret_cast<float*>(base + L.dgate_part), Tn, E, C, Cp, H);
     hipLaunchKernelGGL((gather_transpose_kernel<T, false>), dim3(cd, cC, E), dim3(kTileThreads), 0, st,
                        static_cast<const T*>(x), slot_token, counts, gate, at(L.xpT), Tn, d, E, C, Cp);
     hipLaunchKernelGGL((gather_transpose_kernel<T, true>), dim3(cd, cC, E), dim3(kTileThreads), 0, st,
-                       static_cast<const T*>(dout), slot_token, counts, gate, at(L.dypT), Tn, d, E, C, Cp);
+                       static_cast<const T*>(dout), slot_token, counts, gate_w, at(L.dypT), Tn, d, E, C, Cp);
     ETR_BW(hipGetLastError());
     // dXp = (da | db) (Wg^T | Wu^T)^T
     GroupedGemm g3{at(L.dab), at(L.wguT), nullptr, at(L.dxp), nullptr, counts, nullptr, nullptr, E, C, d, 2 * H, 0, 0, C, GEMM_PLAIN, c.dtype};
@@ -389,7 +424,7 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
                                    static_cast<int>(lds)));
     hipLaunchKernelGGL(kern, dim3((Tn + 3) / 4), dim3(256), lds, st, static_cast<const T*>(x), w_emb, score, gate, slot_of,
                        reinterpret_cast<const float*>(base + L.dgate_part), static_cast<int>(cH), at(L.dxp), static_cast<T*>(dx), dgate, dscore,
-                       Tn, d, E, c.D, C, static_cast<int>(c.cos));
+                       Tn, d, E, c.D, C, static_cast<int>(c.cos), static_cast<int>(c.gate_norm));
 #undef ETR_BW
     return hipGetLastError();
 }

@@ -22,6 +22,7 @@ struct SelectWs {
     int32_t*  need_eq;   // [E]          how many candidates with key == tau are kept (lowest token first)
     int32_t*  pre_gt;    // [E][kMaxChunks] kept-for-sure (key > tau) tokens before the chunk
     int32_t*  pre_eq;    // [E][kMaxChunks] key == tau tokens before the chunk
+    int32_t*  pre_kept;  // [E][kMaxChunks] strict-intersection variant: surviving tokens before the chunk
     int       Tpad;      // row stride of keyT
     int       ipt;       // tokens per chunk (= per thread of the per-expert kernel)
     int       nchunks;

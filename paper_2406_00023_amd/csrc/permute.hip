@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kRowThreads) void combine_kernel(const uint4* __res
                                                               const float* __restrict__ gate,
                                                               const int32_t* __restrict__ slot_of,
                                                               uint4* __restrict__ out, int T, int E, int capacity,
-                                                              int row_vecs) {
+                                                              int row_vecs, int gate_norm) {
     using R = Row<BF16>;
     constexpr int V = R::kVec;
     const int lane = threadIdx.x & (kWave - 1);
@@ -110,6 +110,12 @@ __global__ __launch_bounds__(kRowThreads) void combine_kernel(const uint4* __res
         my_gate = gate[static_cast<size_t>(t) * E + lane];
     }
     const uint64_t kept = __ballot(my_slot >= 0 && my_slot < capacity);
+    if (gate_norm) {                                             // variant: weights renormalised over the kept experts
+        float sum = (my_slot >= 0 && my_slot < capacity) ? my_gate : 0.f;
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, kWave);
+        if (sum > 0.f) my_gate /= sum;
+    }
     constexpr int U = 4;
     for (int c0 = 0; c0 < row_vecs; c0 += kWave * U) {
         float acc[U][V];
@@ -169,10 +175,10 @@ hipError_t launch_combine(const etr_config& c, const void* yp, const float* gate
     const int blocks = (c.T + kRowWaves - 1) / kRowWaves;
     if (c.dtype == ETR_BF16)
         hipLaunchKernelGGL(combine_kernel<true>, dim3(blocks), dim3(kRowThreads), 0, st, static_cast<const uint4*>(yp),
-                           gate, slot_of, static_cast<uint4*>(out), c.T, c.E, c.capacity, row_vecs);
+                           gate, slot_of, static_cast<uint4*>(out), c.T, c.E, c.capacity, row_vecs, c.gate_norm);
     else
         hipLaunchKernelGGL(combine_kernel<false>, dim3(blocks), dim3(kRowThreads), 0, st, static_cast<const uint4*>(yp),
-                           gate, slot_of, static_cast<uint4*>(out), c.T, c.E, c.capacity, row_vecs);
+                           gate, slot_of, static_cast<uint4*>(out), c.T, c.E, c.capacity, row_vecs, c.gate_norm);
     return hipGetLastError();
 }
 

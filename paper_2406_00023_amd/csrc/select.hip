@@ -27,9 +27,17 @@ __device__ __forceinline__ uint32_t order_key(float s) {
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__device__ __forceinline__ uint32_t selection_key(float s, bool cand, int mode) {
+// Key under which expert e ranks token t ("the C best keys, lowest token first among equals"):
+//   TCR        1 for every chooser (position priority)
+//   ECR/BIDIR  the affinity, for all tokens / for the choosers
+//   TCR_RANK   k - (position of e in the token's list): first choices before second choices (variant)
+//   STRICT     the affinity for ALL tokens; the chooser set is intersected afterwards (variant)
+__device__ __forceinline__ uint32_t selection_key(float s, bool cand, int mode, int k = 0, int rank = 0) {
+    if (mode == ETR_MODE_BIDIR_STRICT) return order_key(s);
     if (!cand) return 0u;
-    return mode == ETR_MODE_TCR ? 1u : order_key(s);
+    if (mode == ETR_MODE_TCR) return 1u;
+    if (mode == ETR_MODE_TCR_RANK) return static_cast<uint32_t>(k - rank);
+    return order_key(s);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -45,6 +53,7 @@ __global__ __launch_bounds__(256) void token_choice_kernel(const float* __restri
     const bool valid = t < T && e < E;
     const float val = valid ? score[static_cast<size_t>(t) * E + e] : 0.f;
     uint64_t mask = 0;
+    int my_rank = 0;
     if (mode != ETR_MODE_ECR) {
         int taken = valid ? 0 : 1;
         for (int r = 0; r < k; ++r) {
@@ -57,14 +66,14 @@ __global__ __launch_bounds__(256) void token_choice_kernel(const float* __restri
                 bool better = (ot < bt) || (ot == bt && (ov > bv || (ov == bv && oi < bi)));
                 if (better) { bv = ov; bi = oi; bt = ot; }
             }
-            if (bi == e) taken = 1;
+            if (bi == e && !taken) { taken = 1; my_rank = r; }
             mask |= 1ull << bi;
             if (e == 0 && t < T && topk) topk[static_cast<size_t>(t) * k + r] = bi;
         }
     } else {
         mask = E >= 64 ? ~0ull : ((1ull << E) - 1ull);
     }
-    if (valid) keyT[static_cast<size_t>(e) * Tpad + t] = selection_key(val, (mask >> e) & 1ull, mode);
+    if (valid) keyT[static_cast<size_t>(e) * Tpad + t] = selection_key(val, (mask >> e) & 1ull, mode, k, my_rank);
     if (e == 0 && t < T) cmask[t] = mask;
 }
 
@@ -147,7 +156,7 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
     // prefix whose affinity sum reaches the threshold.  Affinities are summed as fixed-point
     // integers round(clamp(s,-1,1) * 2^30), so the sum of "all candidates with key >= theta" is
     // exact and order-free, and the prefix length follows from a bisection over theta.
-    if (sum_need > 0 && mode != ETR_MODE_TCR && n_keep > 0) {
+    if (sum_need > 0 && (mode == ETR_MODE_ECR || mode == ETR_MODE_BIDIR) && n_keep > 0) {
         __shared__ long long red_sum[kSelThreads / kWave];
         __shared__ int red_cnt[kSelThreads / kWave];
         // sum and count over the candidates with key >= thr (thr >= key(+0): positive affinities only)
@@ -246,6 +255,49 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
 }
 
 // ---------------------------------------------------------------------------------------
+// 2b. strict intersection (variant): expert_choice_kernel has ranked ALL tokens; a pair survives
+// only if the token also lists the expert.  One workgroup per expert, thread = chunk: count the
+// survivors of the chunk, scan, and replace counts[e] by the number of survivors.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kSelThreads) void strict_filter_kernel(const uint32_t* __restrict__ keyT, int Tpad, int T,
+                                                                    int ipt, const uint64_t* __restrict__ cmask,
+                                                                    const uint32_t* __restrict__ tau_in,
+                                                                    const int32_t* __restrict__ need_eq_in,
+                                                                    const int32_t* __restrict__ pre_eq,
+                                                                    int32_t* __restrict__ pre_kept,
+                                                                    int32_t* __restrict__ counts) {
+    __shared__ int wave_tot[kSelThreads / kWave];
+    const int e = blockIdx.x, tid = threadIdx.x;
+    const uint32_t tau = tau_in[e];
+    const int need = need_eq_in[e];
+    int eq = pre_eq[e * kSelThreads + tid], n = 0;
+    const int t_end = min(T, (tid + 1) * ipt);
+    for (int t = tid * ipt; t < t_end; ++t) {
+        const uint32_t key = keyT[static_cast<size_t>(e) * Tpad + t];
+        bool member = key > tau;
+        if (key == tau && key != 0u) { member = eq < need; ++eq; }
+        n += member && ((cmask[t] >> e) & 1ull);
+    }
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    int inc = n;
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) {
+        int a = __shfl_up(inc, m, kWave);
+        if (lane >= m) inc += a;
+    }
+    if (lane == kWave - 1) wave_tot[wave] = inc;
+    __syncthreads();
+    int off = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kSelThreads / kWave; ++w) {
+        if (w < wave) off += wave_tot[w];
+        tot += wave_tot[w];
+    }
+    pre_kept[e * kSelThreads + tid] = off + inc - n;
+    if (tid == 0) counts[e] = tot;
+}
+
+// ---------------------------------------------------------------------------------------
 // 3. slots
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void slot_kernel(const float* __restrict__ score, const uint64_t* __restrict__ cmask,
@@ -255,17 +307,22 @@ __global__ __launch_bounds__(256) void slot_kernel(const float* __restrict__ sco
                                                    const int32_t* __restrict__ pre_gt,
                                                    const int32_t* __restrict__ pre_eq,
                                                    const int32_t* __restrict__ counts, int32_t* __restrict__ slot_of,
-                                                   int32_t* __restrict__ slot_token) {
+                                                   int32_t* __restrict__ slot_token,
+                                                   const uint32_t* __restrict__ keyT, int Tpad,     // TCR_RANK: keys as stored
+                                                   const int32_t* __restrict__ pre_kept) {          // STRICT: see strict_filter_kernel
     const int gid = blockIdx.x * 256 + threadIdx.x;
     const int c = gid / E, e = gid - c * E;
     if (c < nchunks) {
         const uint32_t tau = tau_in[e];
         const int need = need_eq_in[e];
         int gt = pre_gt[e * kSelThreads + c], eq = pre_eq[e * kSelThreads + c];
+        int kept = mode == ETR_MODE_BIDIR_STRICT ? pre_kept[e * kSelThreads + c] : 0;
         const int t_end = min(T, (c + 1) * ipt);
         for (int t = c * ipt; t < t_end; ++t) {
             const float s = score[static_cast<size_t>(t) * E + e];
-            const uint32_t key = selection_key(s, (cmask[t] >> e) & 1ull, mode);
+            const bool cand = (cmask[t] >> e) & 1ull;
+            const uint32_t key = mode == ETR_MODE_TCR_RANK ? keyT[static_cast<size_t>(e) * Tpad + t]
+                                                           : selection_key(s, cand, mode);
             int slot = -1;
             if (key > tau) {
                 slot = gt + min(eq, need);
@@ -274,6 +331,7 @@ __global__ __launch_bounds__(256) void slot_kernel(const float* __restrict__ sco
                 if (eq < need) slot = gt + eq;
                 ++eq;
             }
+            if (mode == ETR_MODE_BIDIR_STRICT) slot = (slot >= 0 && cand) ? kept++ : -1;   // renumber inside the chooser set
             slot_of[static_cast<size_t>(t) * E + e] = slot;
             if (slot >= 0) slot_token[static_cast<size_t>(e) * capacity + slot] = t;
         }
@@ -297,7 +355,7 @@ static int chunk_tokens(int T) {
 size_t select_ws_bytes(int T, int E) {
     const size_t Tpad = align_up(static_cast<size_t>(T), 64);
     return align_up(sizeof(uint64_t) * T) + align_up(sizeof(uint32_t) * E * Tpad) + 2 * align_up(sizeof(int32_t) * E) +
-           2 * align_up(sizeof(int32_t) * E * kSelThreads);
+           3 * align_up(sizeof(int32_t) * E * kSelThreads);
 }
 
 SelectWs select_ws_carve(void* ws, int T, int E) {
@@ -309,7 +367,8 @@ SelectWs select_ws_carve(void* ws, int T, int E) {
     w.tau = reinterpret_cast<uint32_t*>(p);    p += align_up(sizeof(int32_t) * E);
     w.need_eq = reinterpret_cast<int32_t*>(p); p += align_up(sizeof(int32_t) * E);
     w.pre_gt = reinterpret_cast<int32_t*>(p);  p += align_up(sizeof(int32_t) * E * kSelThreads);
-    w.pre_eq = reinterpret_cast<int32_t*>(p);
+    w.pre_eq = reinterpret_cast<int32_t*>(p);  p += align_up(sizeof(int32_t) * E * kSelThreads);
+    w.pre_kept = reinterpret_cast<int32_t*>(p);
     w.ipt = chunk_tokens(T);
     w.nchunks = (T + w.ipt - 1) / w.ipt;
     return w;
@@ -349,10 +408,17 @@ hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_
     err = hipGetLastError();
     if (err != hipSuccess) return err;
 
+    if (c.mode == ETR_MODE_BIDIR_STRICT) {
+        hipLaunchKernelGGL(strict_filter_kernel, dim3(c.E), dim3(kSelThreads), 0, st, w.keyT, w.Tpad, c.T, w.ipt, w.cmask,
+                           w.tau, w.need_eq, w.pre_eq, w.pre_kept, counts);
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
     const long long pairs = static_cast<long long>(w.nchunks) * c.E;
     const int blocks3 = static_cast<int>((pairs + 255) / 256);
     hipLaunchKernelGGL(slot_kernel, dim3(blocks3), dim3(256), 0, st, score, w.cmask, c.T, c.E, c.capacity, c.mode, w.ipt,
-                       w.nchunks, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts, slot_of, slot_token);
+                       w.nchunks, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts, slot_of, slot_token, w.keyT, w.Tpad,
+                       w.pre_kept);
     return hipGetLastError();
 }
 

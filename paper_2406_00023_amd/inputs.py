@@ -27,7 +27,7 @@ from typing import Dict, Optional, Tuple
 
 import torch
 
-MODE_TCR, MODE_ECR, MODE_BIDIR = 0, 1, 2
+MODE_TCR, MODE_ECR, MODE_BIDIR, MODE_TCR_RANK, MODE_BIDIR_STRICT = 0, 1, 2, 3, 4
 COS_FULL, COS_POOLED = 0, 1
 DT_F32, DT_BF16 = 0, 1
 

@@ -31,9 +31,9 @@ def scale_rel_err(a: np.ndarray, b: np.ndarray) -> float:
 class GpuLayer:
     """Owns the device tensors of one layer call and runs stages through the C ABI."""
 
-    def __init__(self, shape: I.EtrShape, tensors=None, mode=None, capacity=None, cos=None):
+    def __init__(self, shape: I.EtrShape, tensors=None, mode=None, capacity=None, cos=None, gate_norm=0):
         self.shape = shape
-        self.cfg = B.make_config(shape, mode=mode, capacity=capacity, cos=cos)
+        self.cfg = B.make_config(shape, mode=mode, capacity=capacity, cos=cos, gate_norm=gate_norm)
         dev = "cuda"
         t = tensors if tensors is not None else I.make_inputs(shape, dev)
         self.t = {k: v.to(dev) for k, v in t.items()}
@@ -109,7 +109,7 @@ def check_output_against_oracle(oracle, layer: GpuLayer, hx: dict, g_score: np.n
     s, cfg = layer.shape, layer.cfg
     ref = oracle.moe_forward(hx["x"], hx["w_emb"], hx["w_gate"], hx["w_up"], hx["w_down"], D=s.D, k=s.k,
                              capacity=cfg.capacity, dtype=s.dtype, mode=cfg.mode, cos_mode=cfg.cos, score_in=g_score,
-                             tokens=tokens)
+                             tokens=tokens, gate_norm=cfg.gate_norm)
     got = to_np(layer.out)
     if tokens is not None:
         got = got[np.asarray(tokens)]

@@ -31,8 +31,9 @@ def test_header_symbols_are_exported(lib):
 
 
 def test_config_struct_matches_header():
-    assert ctypes.sizeof(B.EtrConfig) == 40
-    assert [f[0] for f in B.EtrConfig._fields_] == ["T", "d", "E", "D", "k", "capacity", "H", "dtype", "mode", "cos"]
+    assert ctypes.sizeof(B.EtrConfig) == 44
+    assert [f[0] for f in B.EtrConfig._fields_] == ["T", "d", "E", "D", "k", "capacity", "H", "dtype", "mode", "cos",
+                                                    "gate_norm"]
 
 
 def test_status_strings(lib):
@@ -58,7 +59,7 @@ def _bad(**kw):
 
 @pytest.mark.parametrize("cfg,status", [
     (_bad(T=0), 2), (_bad(D=7), 2), (_bad(k=0), 2), (_bad(k=9), 2), (_bad(capacity=0), 2), (_bad(H=-8), 2),
-    (_bad(E=65, d=65 * 8), 3), (_bad(d=260, D=4), 3), (_bad(H=508), 3), (_bad(dtype=2), 3), (_bad(mode=3), 3),
+    (_bad(E=65, d=65 * 8), 3), (_bad(d=260, D=4), 3), (_bad(H=508), 3), (_bad(dtype=2), 3), (_bad(mode=5), 3), (_bad(mode=-1), 3),
     (_bad(cos=2), 3), (_bad(d=32768, D=1, E=64), 3),
 ])
 def test_invalid_configs(lib, cfg, status):

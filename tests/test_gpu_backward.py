@@ -31,9 +31,9 @@ def _say(msg):
 class Backward:
     """Runs forward routing + backward on the GPU and keeps the results."""
 
-    def __init__(self, H, shape, mode, cos=None):
+    def __init__(self, H, shape, mode, cos=None, gate_norm=0):
         self.H, self.shape = H, shape
-        self.L = L = H.GpuLayer(shape, mode=mode, cos=cos)
+        self.L = L = H.GpuLayer(shape, mode=mode, cos=cos, gate_norm=gate_norm)
         L.route(); L.select()
         dev, dt = "cuda", shape.torch_dtype
         E, Hh, d, T = shape.E, shape.H, shape.d, shape.T
