@@ -439,9 +439,12 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_pipe_kernel(GemmParams p, 
 // iterations to land: before barrier(kt) a wave waits only until at most 12 copies are
 // outstanding (s_waitcnt vmcnt(12)), i.e. until its share of tile kt+1 is in LDS.
 // ---------------------------------------------------------------------------------------
-template <bool GLU, int WN = 2, int AUXA = 0, int AUXB = 0, bool DUAL = false>
+// s_waitcnt immediate: vmcnt(n) (6 bits, split 3:0 and 15:14), expcnt untouched, lgkmcnt(0) or untouched
+constexpr int waitcnt_imm(int vm, bool lgkm0) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm0 ? 0 : 0x0F00); }
+
+template <bool GLU, int WN = 2, int AUXA = 0, int AUXB = 0, bool DUAL = false, int NBUF = 4>
 __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) {
-    constexpr int BM = 256, BR = 256, CPR = 4, NBUF = 4;
+    constexpr int BM = 256, BR = 256, CPR = 4;
     constexpr int BN = GLU ? 128 : 256;
     constexpr int STAGE = (BM + BR) * CPR;              // uint4 per LDS buffer (32 KiB)
     constexpr int NW = 2 * WN;                          // waves: 2 row groups x WN column groups
@@ -487,7 +490,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
         off[NCP + i] = (static_cast<uint32_t>(n) * KCB + c) * 16u;
     }
     auto issue_copy = [&](int kt, int j) {
-        uint4* dst = lds + (kt & (NBUF - 1)) * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
+        uint4* dst = lds + (kt % NBUF) * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
         // re-materialise the tile base as a scalar every time, so that the address stays
         // "scalar base + 32-bit lane offset" instead of a per-lane 64-bit pointer
         int tk = kt + kt0;
@@ -521,7 +524,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
 
     bf16x8 fa[2][4], fb[2][TB];
     auto load_frags = [&](int set, int kt, int ck) {
-        const uint4* base = lds + (kt & (NBUF - 1)) * STAGE + ck;
+        const uint4* base = lds + (kt % NBUF) * STAGE + ck;
 #pragma unroll
         for (int i = 0; i < 4; ++i) fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
 #pragma unroll
@@ -539,27 +542,30 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
         }
     };
 
-    // ---- prologue: three tiles in flight, wait for the first
-    const int pre = KT < 3 ? KT : 3;
+    // ---- prologue: NBUF - 1 tiles in flight, wait for the first
+    constexpr int AHEAD = NBUF - 1;
+    const int pre = KT < AHEAD ? KT : AHEAD;
     for (int t = 0; t < pre; ++t)
 #pragma unroll
         for (int j = 0; j < 2 * NCP; ++j) issue_copy(t, j);
-    if (pre == 3) __builtin_amdgcn_s_waitcnt(NCP == 4 ? 0x4F70 : 0x0F78);        // vmcnt(4*NCP)
-    else if (pre == 2) __builtin_amdgcn_s_waitcnt(NCP == 4 ? 0x0F78 : 0x0F74);   // vmcnt(2*NCP)
-    else __builtin_amdgcn_s_waitcnt(0x0F70);                                     // vmcnt(0)
+    if (pre == AHEAD) __builtin_amdgcn_s_waitcnt(waitcnt_imm((AHEAD - 1) * 2 * NCP, false));
+    else if (pre == 3) __builtin_amdgcn_s_waitcnt(waitcnt_imm(4 * NCP, false));
+    else if (pre == 2) __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * NCP, false));
+    else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, false));
     __builtin_amdgcn_s_barrier();
     load_frags(0, 0, ck0);
 
     int kt = 0;
-    for (; kt + 3 < KT; ++kt) {                              // steady state: tile kt+3 is being fetched
+    for (; kt + AHEAD < KT; ++kt) {                          // steady state: tile kt+AHEAD is being fetched
         __builtin_amdgcn_sched_barrier(0);
         load_frags(1, kt, ck1);
-        mfma_step(0, true, kt + 3, 0);
-        __builtin_amdgcn_s_waitcnt(0x0070 | (3 * NCP));      // vmcnt(3*NCP) lgkmcnt(0): tile kt+1 is in LDS
+        mfma_step(0, true, kt + AHEAD, 0);
+        // tile kt+1 is in LDS once at most tiles kt+2 .. kt+AHEAD-1 and half of kt+AHEAD are outstanding
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm((2 * (AHEAD - 2) + 1) * NCP, true));
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         load_frags(0, kt + 1, ck0);
-        mfma_step(1, true, kt + 3, NCP);
+        mfma_step(1, true, kt + AHEAD, NCP);
     }
     for (; kt < KT; ++kt) {                                  // drain: nothing left to fetch
         __builtin_amdgcn_sched_barrier(0);
@@ -878,11 +884,11 @@ hipError_t launch_bf16_pipe(GemmParams p, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <bool GLU, int WN = 2, int AUXA = 0, int AUXB = 0, bool DUAL = false>
+template <bool GLU, int WN = 2, int AUXA = 0, int AUXB = 0, bool DUAL = false, int NBUF = 4>
 hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
-    constexpr size_t lds = 4ull * 512 * 32 * 2;        // four buffers of 256 + 256 rows x 32 bf16
+    constexpr size_t lds = static_cast<size_t>(NBUF) * 512 * 32 * 2;        // NBUF buffers of 256 + 256 rows x 32 bf16
     const long long blocks = plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_ring_kernel<GLU, WN, AUXA, AUXB, DUAL>;
+    auto kern = gemm_bf16_ring_kernel<GLU, WN, AUXA, AUXB, DUAL, NBUF>;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (err != hipSuccess) return err;
