@@ -142,7 +142,7 @@ def _scores(seed, T, E, levels):
 ])
 def test_select_external_scores(H, oracle, T, E, k, C, levels):
     S = _scores(T * 31 + E, T, E, levels)
-    for mode in (TCR, ECR, BIDIR):
+    for mode in (TCR, ECR, BIDIR, I.MODE_TCR_RANK, I.MODE_BIDIR_STRICT):
         _say(f"case select T={T} E={E} k={k} C={C} levels={levels} mode={mode}")
         shape = I.EtrShape("s", 1, T=T, d=8 * E, E=E, D=8, k=k, capacity=C, H=8, dtype=I.DT_F32, mode=mode, recipe="iso")
         L = H.GpuLayer(shape, tensors={})
