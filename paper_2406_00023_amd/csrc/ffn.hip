@@ -10,6 +10,8 @@
 // crosses HBM once, in bf16.  The grid is sized for `capacity`; a workgroup whose row
 // tile starts past counts[e] exits at once, so counts never leave the device.
 // fp32: plain LDS-tiled FMA kernels (parity path for small layers).
+#include <type_traits>
+
 #include "etr_internal.h"
 
 namespace etr {
@@ -610,6 +612,277 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
 }
 
 // ---------------------------------------------------------------------------------------
+// Persistent form of the ring kernel: one workgroup per CU walks a list of tiles, and the ring
+// of copies runs on across tile boundaries: while the last k-tiles of one tile are multiplied
+// the first k-tiles of the next are already being fetched, and the stores of the epilogue
+// overlap with them.  (A workgroup per tile pays launch, address set-up, the first-tile latency
+// and the epilogue with the matrix pipe idle: about 5 us per tile, 5-10 % at K = 2048.)
+//
+// Tile list: only tiles that hold rows (m0 < counts[e]) are enumerated, super-tile by super-tile
+// (see decode_tile), from an exclusive prefix over the super-tiles that every workgroup builds in
+// LDS at start.  Consecutive groups of gridDim.x / 8 tiles go round-robin to the 8 XCDs, so the
+// tiles that run together on one XCD are still (pieces of) one super-tile and share operand
+// slices through its L2, and every workgroup gets the same number of tiles +- 1.
+// No atomics, no flags: the schedule is a pure function of counts[].
+//
+// Waits: copies and stores complete in issue order, so "at most 3*NCP operations outstanding"
+// always implies that everything older than the newest 3*NCP has landed; operations that are not
+// copies of the ring (the epilogue's stores) only make that wait conservative, never unsafe.
+// ---------------------------------------------------------------------------------------
+constexpr int kMaxSuper = 4096;          // super-tiles the LDS prefix can hold (16 KiB)
+
+template <bool GLU, bool DUAL = false>
+__global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
+    constexpr int BM = 256, BR = 256, CPR = 4, NBUF = 4, AHEAD = NBUF - 1;
+    constexpr int BN = GLU ? 128 : 256;
+    constexpr int STAGE = (BM + BR) * CPR;
+    constexpr int WN = 4, NW = 8, TB = 2, NCP = 2;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    uint4* lds = reinterpret_cast<uint4*>(lds_raw);
+    __shared__ int pre[kMaxSuper + 1];
+    __shared__ int wave_tot[NW];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int r32 = lane & 31, half = lane >> 5;
+    const int KCA = (p.lda ? p.lda : p.K) / 8, KCB = (p.ldb ? p.ldb : p.K) / 8;
+
+    // ---- exclusive prefix of the number of live tiles per super-tile
+    const int MG = (p.MT + p.SM - 1) / p.SM, NG = (p.NT + p.SN - 1) / p.SN;
+    const int S = p.E * MG * NG;
+    auto live_rows = [&](int e, int mg) {                // live row tiles of super-tile row mg of expert e
+        const int mtv = (group_rows(p, e) + BM - 1) / BM;
+        return min(max(mtv - mg * p.SM, 0), p.SM);
+    };
+    auto live_cols = [&](int ng) { return min(p.NT - ng * p.SN, p.SN); };
+    {
+        const int CH = (S + 511) / 512;
+        int sum = 0;
+        for (int i = 0; i < CH; ++i) {
+            const int s = tid * CH + i;
+            if (s < S) {
+                const int e = s / (MG * NG), r = s - e * (MG * NG);
+                sum += live_rows(e, r % MG) * live_cols(r / MG);
+            }
+        }
+        int inc = sum;
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) {
+            const int o = __shfl_up(inc, m, 64);
+            if (lane >= m) inc += o;
+        }
+        if (lane == 63) wave_tot[wave] = inc;
+        __syncthreads();
+        int run = inc - sum;
+        for (int w = 0; w < wave; ++w) run += wave_tot[w];
+        for (int i = 0; i < CH; ++i) {
+            const int s = tid * CH + i;
+            if (s < S) {
+                pre[s] = run;
+                const int e = s / (MG * NG), r = s - e * (MG * NG);
+                run += live_rows(e, r % MG) * live_cols(r / MG);
+            }
+        }
+        if (tid == 511) pre[S] = run;                    // thread 511 owns the last chunk (or nothing): run = total
+        __syncthreads();
+    }
+    const int total = pre[S];
+    const int GS = gridDim.x >> 3;                       // tiles per group = workgroups per XCD
+    const int xcd = blockIdx.x & 7, slot_l = blockIdx.x >> 3;
+
+    struct Tile {
+        int e, m0, n0, count, KT;
+        const char* Abase;
+        const char* Bbase;
+        uint32_t off[2 * NCP];
+    };
+    // the tile with list index q (q < total)
+    auto setup = [&](int q, Tile& t) {
+        int lo = 0, hi = S;                              // largest s with pre[s] <= q
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (pre[mid] <= q) lo = mid; else hi = mid;
+        }
+        const int s = __builtin_amdgcn_readfirstlane(lo);
+        const int u = __builtin_amdgcn_readfirstlane(q - pre[s]);
+        const int e = s / (MG * NG), r = s - e * (MG * NG);
+        const int mg = r % MG, ng = r / MG;
+        const int vm = live_rows(e, mg);
+        const int mt = mg * p.SM + u % vm, nt = ng * p.SN + u / vm;
+        t.e = e; t.m0 = mt * BM; t.n0 = nt * BN;
+        t.count = group_rows(p, e);
+        t.KT = group_k(p, e) / 32;
+        t.Abase = reinterpret_cast<const char*>(p.A) + (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KCA * 16);
+        t.Bbase = reinterpret_cast<const char*>((GLU && wave >= NW / 2) ? p.B1 : p.B0) + static_cast<size_t>(e) * p.N * KCB * 16;
+#pragma unroll
+        for (int i = 0; i < NCP; ++i) {
+            const int rr = (wave * NCP + i) * 16 + (lane >> 2);
+            const int c = (lane & 3) ^ ((rr >> 2) & 3);
+            int m = t.m0 + rr;
+            m = m < t.count ? m : t.count - 1;
+            const int row = p.row_index ? min(max(p.row_index[static_cast<size_t>(e) * p.capacity + m], 0), p.a_rows - 1) : m;
+            t.off[i] = (static_cast<uint32_t>(row) * KCA + c) * 16u;
+            int n = t.n0 + (GLU ? (rr & 127) : rr);
+            n = n < p.N ? n : p.N - 1;
+            t.off[NCP + i] = (static_cast<uint32_t>(n) * KCB + c) * 16u;
+        }
+    };
+    // copy j (0..NCP-1: A row groups, NCP..2NCP-1: B row groups) of k-tile k of tile t into the ring slot of step g
+    auto issue_copy = [&](const Tile& t, int k, int g, int j) {
+        uint4* dst = lds + (g & (NBUF - 1)) * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
+        const uint64_t b64 = reinterpret_cast<uint64_t>(j < NCP ? t.Abase : t.Bbase) + static_cast<uint64_t>(k) * (CPR * 16);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
+        const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
+        const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+        __builtin_amdgcn_global_load_lds((global_cptr)(base + t.off[j]), (lds_ptr)dst, 16, 0, 0);
+    };
+
+    const int sw = (r32 >> 2) & 3;
+    int a_row[4], b_row[TB];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a_row[i] = (wm * 128 + i * 32 + r32) * CPR;
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+        const int br = GLU ? ((j / (TB / 2)) * 128 + wn * (16 * TB) + (j % (TB / 2)) * 32) : (wn * (32 * TB) + j * 32);
+        b_row[j] = BM * CPR + (br + r32) * CPR;
+    }
+    const int ck0 = half ^ sw, ck1 = (2 + half) ^ sw;
+
+    f32x16 acc[4][TB];
+    bf16x8 fa[2][4], fb[2][TB];
+    auto load_frags = [&](int set, int g, int ck) {
+        const uint4* base = lds + (g & (NBUF - 1)) * STAGE + ck;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
+#pragma unroll
+        for (int j = 0; j < TB; ++j) fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
+    };
+
+    int q = xcd * GS + slot_l;                           // round 0
+    if (q >= total) return;                              // uniform: nothing for this workgroup
+    Tile cur, nxt;
+    setup(q, cur);
+    int g = 0;                                           // global step (ring position) of the next k-tile to multiply
+    for (int t = 0; t < AHEAD; ++t)                      // KT >= AHEAD is a launch condition
+#pragma unroll
+        for (int j = 0; j < 2 * NCP; ++j) issue_copy(cur, t, t, j);
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm((AHEAD - 1) * 2 * NCP, false));
+    __builtin_amdgcn_s_barrier();
+    load_frags(0, 0, ck0);
+
+    for (;;) {
+        const int qn = q + 8 * GS;                       // same XCD, next round
+        const bool has_next = qn < total;
+        if (has_next) setup(qn, nxt);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < TB; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        const int KT = cur.KT;
+        // Fetching part: k-tile kt + AHEAD, which past KT is a k-tile of the next tile.  The source is
+        // chosen with selects outside the unrolled MFMA sequences, which carry no branches.
+        const int kt_fetch = has_next ? KT : KT - AHEAD;
+        int kt = 0;
+        for (; kt < kt_fetch; ++kt, ++g) {
+            const bool in_cur = kt + AHEAD < KT;
+            const int kf = in_cur ? kt + AHEAD : kt + AHEAD - KT;
+            const char* baseA = in_cur ? cur.Abase : nxt.Abase;
+            const char* baseB = in_cur ? cur.Bbase : nxt.Bbase;
+            uint32_t offs[2 * NCP];
+#pragma unroll
+            for (int j = 0; j < 2 * NCP; ++j) offs[j] = in_cur ? cur.off[j] : nxt.off[j];
+            auto copy = [&](int j) {
+                uint4* dst = lds + ((g + AHEAD) & (NBUF - 1)) * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
+                const uint64_t b64 = reinterpret_cast<uint64_t>(j < NCP ? baseA : baseB) + static_cast<uint64_t>(kf) * (CPR * 16);
+                const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
+                const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
+                const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+                __builtin_amdgcn_global_load_lds((global_cptr)(base + offs[j]), (lds_ptr)dst, 16, 0, 0);
+            };
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(1, g, ck1);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int j = 0; j < TB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[0][j], fa[0][i], acc[i][j], 0, 0, 0);
+                if (i & 1) copy(i >> 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(3 * NCP, true));      // step g+1 is in LDS
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(0, g + 1, ck0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int j = 0; j < TB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][j], fa[1][i], acc[i][j], 0, 0, 0);
+                if (i & 1) copy(NCP + (i >> 1));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        for (; kt < KT; ++kt, ++g) {                                 // tail of this workgroup's last tile: nothing to fetch
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(1, g, ck1);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int j = 0; j < TB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[0][j], fa[0][i], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            if (kt + 1 < KT) load_frags(0, g + 1, ck0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int j = 0; j < TB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][j], fa[1][i], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // ---- epilogue of cur (the copies of the next tile are in flight)
+        uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(cur.e) * p.capacity * p.N;
+        uint16_t* C2g = DUAL ? reinterpret_cast<uint16_t*>(p.C2) + static_cast<size_t>(cur.e) * p.capacity * p.N : nullptr;
+        constexpr int TO = GLU ? TB / 2 : TB;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = cur.m0 + wm * 128 + i * 32 + r32;
+            if (m >= cur.count) continue;
+#pragma unroll
+            for (int j = 0; j < TO; ++j)
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                    const int n = cur.n0 + wn * (32 * TO) + j * 32 + qq * 8 + half * 4;
+                    if (n >= p.N) continue;
+                    float o[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        if constexpr (GLU && !DUAL) o[v] = silu(acc[i][j][qq * 4 + v]) * acc[i][TO + j][qq * 4 + v];
+                        else o[v] = acc[i][j][qq * 4 + v];
+                    }
+                    uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
+                    *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
+                    if constexpr (GLU && DUAL) {
+                        const f32x16& u2 = acc[i][TB - TO + j];
+                        pk = make_uint2(f2bf(u2[qq * 4]) | (f2bf(u2[qq * 4 + 1]) << 16), f2bf(u2[qq * 4 + 2]) | (f2bf(u2[qq * 4 + 3]) << 16));
+                        *reinterpret_cast<uint2*>(C2g + static_cast<size_t>(m) * p.N + n) = pk;
+                    }
+                }
+        }
+        if (!has_next) break;
+        cur = nxt;
+        q = qn;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // Ping-pong variant: eight waves, two per SIMD.  A wave alternates between a MEMORY slot
 // (ds_read all MFMA operands of its next k-tile, issue its share of the asynchronous copies
 // of tile t+3) and a COMPUTE slot (16 MFMAs on a 128 x 64 slice).  The two waves of a SIMD
@@ -896,6 +1169,26 @@ hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
     return hipGetLastError();
 }
 
+// Persistent ring kernel: needs every group's contraction length >= 96 (three k-tiles to prefetch) -- callers
+// use it only with a fixed K -- and the super-tile prefix to fit in LDS.
+template <bool GLU, bool DUAL = false>
+hipError_t launch_bf16_persist(GemmParams p, hipStream_t st, int n_cu) {
+    constexpr size_t lds = 4ull * 512 * 32 * 2;
+    plan_tiles(p, 256, GLU ? 128 : 256);
+    auto kern = gemm_bf16_persist_kernel<GLU, DUAL>;
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(512), lds, st, p);
+    return hipGetLastError();
+}
+inline bool persist_ok(const GemmParams& g) {
+    GemmParams t = g;
+    plan_tiles(t, 256, 256);
+    const long long MG = (t.MT + t.SM - 1) / t.SM;
+    return g.k_counts == nullptr && g.K >= 96 && static_cast<long long>(g.E) * MG * ((g.N + 127) / 128) <= kMaxSuper;
+}
+
 template <bool GLU, int GROUPING, int DEBUG_SKIP = 0>
 hipError_t launch_bf16_pp(GemmParams p, hipStream_t st) {
     constexpr size_t lds = 4ull * 512 * 32 * 2;
@@ -923,6 +1216,13 @@ size_t ffn_ws_bytes(const etr_config& c) {
 
 // The pipelined kernels need K % 64 == 0 (copies cannot zero-fill a K tail) and 32-bit byte
 // offsets inside one operand; everything else takes the register-staged kernel.
+static int cu_count() {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8)
+        return 256;
+    return n;
+}
+
 static bool pipelined_ok(const GemmParams& g, size_t a_rows) {
     const size_t a_row_bytes = static_cast<size_t>(g.lda ? g.lda : g.K) * 2, b_row_bytes = static_cast<size_t>(g.ldb ? g.ldb : g.K) * 2;
     return g.K % 64 == 0 && a_row_bytes % 16 == 0 && b_row_bytes % 16 == 0 && a_rows * a_row_bytes < (1ull << 32) &&
@@ -938,6 +1238,14 @@ hipError_t launch_grouped_gemm(const GroupedGemm& q, hipStream_t st) {
     if (q.dtype == ETR_BF16) {
         if (q.K % 8 != 0 || (q.lda ? q.lda : q.K) % 8 != 0 || (q.ldb ? q.ldb : q.K) % 8 != 0) return hipErrorInvalidValue;
         const bool ring = pipelined_ok(g, q.row_index ? static_cast<size_t>(q.a_rows) : static_cast<size_t>(q.M));
+        if (ring && persist_ok(g)) {
+            const int n_cu = cu_count();
+            switch (q.epilogue) {
+                case GEMM_PLAIN: return launch_bf16_persist<false>(g, st, n_cu);
+                case GEMM_SWIGLU: return launch_bf16_persist<true>(g, st, n_cu);
+                case GEMM_DUAL: return launch_bf16_persist<true, true>(g, st, n_cu);
+            }
+        }
         switch (q.epilogue) {
             case GEMM_PLAIN: return ring ? launch_bf16_ring<false, 4>(g, st) : launch_bf16<128, 128, 64, 2, 2, false, 1>(g, st);
             case GEMM_SWIGLU: return ring ? launch_bf16_ring<true, 4>(g, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g, st);
@@ -971,11 +1279,16 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
     if (c.dtype == ETR_BF16) {
         if (gather_rows && !ffn_can_gather(c)) return hipErrorInvalidValue;
         const bool pipe1 = pipelined_ok(g1, gather_rows ? static_cast<size_t>(c.T) : static_cast<size_t>(c.capacity));
-        err = pipe1 ? launch_bf16_ring<true, 4>(g1, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g1, st);
+        const int n_cu = cu_count();
+        if (pipe1 && persist_ok(g1)) err = launch_bf16_persist<true>(g1, st, n_cu);
+        else err = pipe1 ? launch_bf16_ring<true, 4>(g1, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g1, st);
         if (err != hipSuccess) return err;
         if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
-        return pipelined_ok(g2, c.capacity) ? launch_bf16_pipe<false, 1, 4>(g2, st)
-                                            : launch_bf16<128, 128, 64, 2, 2, false, 1>(g2, st);
+        if (!pipelined_ok(g2, c.capacity)) return launch_bf16<128, 128, 64, 2, 2, false, 1>(g2, st);
+        // short contractions gain more from the persistent kernel's overlap of tile boundaries than from
+        // the 64-wide k-tiles of the two-stage kernel
+        if (g2.K < 4096 && persist_ok(g2)) return launch_bf16_persist<false>(g2, st, n_cu);
+        return launch_bf16_pipe<false, 1, 4>(g2, st);
     }
     if (gather_rows) return hipErrorInvalidValue;
     err = launch_f32<true>(g1, st);
