@@ -58,7 +58,9 @@ template <> struct Elt<uint16_t> {          // bf16 bit patterns
     __device__ static uint16_t narrow(float v) { return bf16_bits(v); }
 };
 
-__device__ __forceinline__ int round_up64(int v) { return (v + 63) & ~63; }
+// Columns of the transposed per-expert buffers that the weight-gradient products read: the kept rows rounded up
+// to a multiple of 64, at least 128 (the grouped product's rule for per-group contraction lengths), at most Cp.
+__device__ __forceinline__ int padded_rows(int count, int Cp) { return min(max((count + 63) & ~63, 128), Cp); }
 
 // A 64 x 64 tile in LDS, stored [row][col] in the tensor's own element type.
 template <typename T> struct Tile { T v[kTile][kTile + Elt<T>::kPad]; };
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(kTileThreads) void transpose_kernel(const T* __rest
 }
 
 // dst[e][j][s] = src[slot_token[e][s]][j] (* gate[slot_token[e][s]][e])  for s < counts[e];
-// zeros for counts[e] <= s < round_up64(counts[e]); nothing beyond.
+// zeros for counts[e] <= s < padded_rows(counts[e]); nothing beyond.
 template <typename T, bool SCALE>
 __global__ __launch_bounds__(kTileThreads) void gather_transpose_kernel(const T* __restrict__ src,
                                                                         const int32_t* __restrict__ slot_token,
@@ -114,7 +116,7 @@ __global__ __launch_bounds__(kTileThreads) void gather_transpose_kernel(const T*
     constexpr int V = Elt<T>::kVec, CH = kTile / V;
     const int e = blockIdx.z, s0 = blockIdx.y * kTile, j0 = blockIdx.x * kTile;
     const int count = min(counts[e], C);
-    if (s0 >= round_up64(count)) return;
+    if (s0 >= padded_rows(count, Cp)) return;
     for (int q = threadIdx.x; q < kTile * CH; q += kTileThreads) {
         const int r = q / CH, cc = (q % CH) * V, s = s0 + r;
         float f[V];
@@ -151,7 +153,7 @@ __global__ __launch_bounds__(kTileThreads) void swiglu_backward_kernel(
     constexpr int V = Elt<T>::kVec, CH = kTile / V;
     const int e = blockIdx.z, s0 = blockIdx.y * kTile, n0 = blockIdx.x * kTile;
     const int count = min(counts[e], C);
-    if (s0 >= round_up64(count)) return;
+    if (s0 >= padded_rows(count, Cp)) return;
     const size_t ebase = static_cast<size_t>(e) * C;
     for (int q = threadIdx.x; q < kTile * CH; q += kTileThreads) {
         const int r = q / CH, cc = (q % CH) * V, s = s0 + r, n = n0 + cc;

@@ -60,7 +60,7 @@ bool ffn_can_gather(const etr_config& c);
 // A is [G][M][lda] (or, with row_index[G][M], row row_index[g][m] of one [a_rows][lda] matrix),
 // B0/B1 are [G][N][ldb], C/C2 are [G][M][N], all of the layer's dtype.  m_counts (optional) bounds the
 // rows of each group, k_counts (optional) its contraction length: it is rounded up to a multiple of
-// 64 and the operands must hold zeros in that padding.
+// 64, at least 128 (at most K), and the operands must hold zeros in that padding.
 enum GemmEpilogue { GEMM_PLAIN = 0, GEMM_SWIGLU = 1, GEMM_DUAL = 2 };   // C = A B0^T | SiLU(A B0^T) .* (A B1^T) | both products
 struct GroupedGemm {
     const void* A; const void* B0; const void* B1;

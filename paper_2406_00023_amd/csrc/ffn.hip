@@ -34,7 +34,8 @@ struct GemmParams {
     int a_rows;                 // rows of A that row_index may name (indices are clamped into [0, a_rows))
     int lda = 0, ldb = 0;       // row strides of A and B in elements (0: K)
     const int32_t* k_counts = nullptr;   // optional per-group contraction length; it is rounded up to a multiple
-                                         // of 64 (at most K) and the operands must hold zeros in that padding
+                                         // of 64, at least 128 (at most K), and the operands must hold zeros in
+                                         // that padding
     void* C2 = nullptr;         // DUAL epilogue: the B1 product goes here, the B0 product to C, no activation
 };
 
@@ -43,7 +44,7 @@ __device__ __forceinline__ int group_rows(const GemmParams& p, int e) {
     return p.counts ? min(p.counts[e], p.capacity) : p.capacity;
 }
 __device__ __forceinline__ int group_k(const GemmParams& p, int e) {
-    return p.k_counts ? min((max(p.k_counts[e], 0) + 63) & ~63, p.K) : p.K;
+    return p.k_counts ? min(max((max(p.k_counts[e], 0) + 63) & ~63, 128), p.K) : p.K;
 }
 
 __device__ __forceinline__ uint32_t f2bf(float f) {            // fp32 -> bf16 bits, round to nearest even
@@ -1169,8 +1170,8 @@ hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
     return hipGetLastError();
 }
 
-// Persistent ring kernel: needs every group's contraction length >= 96 (three k-tiles to prefetch) -- callers
-// use it only with a fixed K -- and the super-tile prefix to fit in LDS.
+// Persistent ring kernel: needs every group's contraction length >= 96 (three k-tiles to prefetch)
+// and the super-tile prefix to fit in LDS.
 template <bool GLU, bool DUAL = false>
 hipError_t launch_bf16_persist(GemmParams p, hipStream_t st, int n_cu) {
     constexpr size_t lds = 4ull * 512 * 32 * 2;
@@ -1186,7 +1187,8 @@ inline bool persist_ok(const GemmParams& g) {
     GemmParams t = g;
     plan_tiles(t, 256, 256);
     const long long MG = (t.MT + t.SM - 1) / t.SM;
-    return g.k_counts == nullptr && g.K >= 96 && static_cast<long long>(g.E) * MG * ((g.N + 127) / 128) <= kMaxSuper;
+    // (with k_counts the contraction is at least min(128, K) long: four k-tiles)
+    return g.K >= 128 && static_cast<long long>(g.E) * MG * ((g.N + 127) / 128) <= kMaxSuper;
 }
 
 template <bool GLU, int GROUPING, int DEBUG_SKIP = 0>
@@ -1285,9 +1287,11 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
         if (err != hipSuccess) return err;
         if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
         if (!pipelined_ok(g2, c.capacity)) return launch_bf16<128, 128, 64, 2, 2, false, 1>(g2, st);
-        // short contractions gain more from the persistent kernel's overlap of tile boundaries than from
-        // the 64-wide k-tiles of the two-stage kernel
-        if (g2.K < 4096 && persist_ok(g2)) return launch_bf16_persist<false>(g2, st, n_cu);
+        // With at most two tiles per CU the makespan is two tile times whatever the schedule, and the
+        // two-stage kernel with 64-wide k-tiles is the faster one per tile; otherwise the persistent kernel
+        // wins through its overlap of tile boundaries and its even split of the live tiles.
+        const long long tiles = static_cast<long long>(c.E) * ((c.capacity + 255) / 256) * ((c.d + 255) / 256);
+        if (persist_ok(g2) && tiles > 2ll * n_cu) return launch_bf16_persist<false>(g2, st, n_cu);
         return launch_bf16_pipe<false, 1, 4>(g2, st);
     }
     if (gather_rows) return hipErrorInvalidValue;
