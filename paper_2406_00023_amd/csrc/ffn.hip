@@ -1183,12 +1183,12 @@ hipError_t launch_bf16_persist(GemmParams p, hipStream_t st, int n_cu) {
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(512), lds, st, p);
     return hipGetLastError();
 }
-inline bool persist_ok(const GemmParams& g) {
+inline bool persist_ok(const GemmParams& g, bool glu) {
     GemmParams t = g;
-    plan_tiles(t, 256, 256);
-    const long long MG = (t.MT + t.SM - 1) / t.SM;
+    plan_tiles(t, 256, glu ? 128 : 256);
+    const long long MG = (t.MT + t.SM - 1) / t.SM, NG = (t.NT + t.SN - 1) / t.SN;
     // (with k_counts the contraction is at least min(128, K) long: four k-tiles)
-    return g.K >= 128 && static_cast<long long>(g.E) * MG * ((g.N + 127) / 128) <= kMaxSuper;
+    return g.K >= 128 && static_cast<long long>(g.E) * MG * NG <= kMaxSuper;
 }
 
 template <bool GLU, int GROUPING, int DEBUG_SKIP = 0>
@@ -1240,7 +1240,7 @@ hipError_t launch_grouped_gemm(const GroupedGemm& q, hipStream_t st) {
     if (q.dtype == ETR_BF16) {
         if (q.K % 8 != 0 || (q.lda ? q.lda : q.K) % 8 != 0 || (q.ldb ? q.ldb : q.K) % 8 != 0) return hipErrorInvalidValue;
         const bool ring = pipelined_ok(g, q.row_index ? static_cast<size_t>(q.a_rows) : static_cast<size_t>(q.M));
-        if (ring && persist_ok(g)) {
+        if (ring && persist_ok(g, q.epilogue != GEMM_PLAIN)) {
             const int n_cu = cu_count();
             switch (q.epilogue) {
                 case GEMM_PLAIN: return launch_bf16_persist<false>(g, st, n_cu);
@@ -1282,7 +1282,7 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
         if (gather_rows && !ffn_can_gather(c)) return hipErrorInvalidValue;
         const bool pipe1 = pipelined_ok(g1, gather_rows ? static_cast<size_t>(c.T) : static_cast<size_t>(c.capacity));
         const int n_cu = cu_count();
-        if (pipe1 && persist_ok(g1)) err = launch_bf16_persist<true>(g1, st, n_cu);
+        if (pipe1 && persist_ok(g1, true)) err = launch_bf16_persist<true>(g1, st, n_cu);
         else err = pipe1 ? launch_bf16_ring<true, 4>(g1, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g1, st);
         if (err != hipSuccess) return err;
         if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
@@ -1291,7 +1291,7 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
         // two-stage kernel with 64-wide k-tiles is the faster one per tile; otherwise the persistent kernel
         // wins through its overlap of tile boundaries and its even split of the live tiles.
         const long long tiles = static_cast<long long>(c.E) * ((c.capacity + 255) / 256) * ((c.d + 255) / 256);
-        if (persist_ok(g2) && tiles > 2ll * n_cu) return launch_bf16_persist<false>(g2, st, n_cu);
+        if (persist_ok(g2, false) && tiles > 2ll * n_cu) return launch_bf16_persist<false>(g2, st, n_cu);
         return launch_bf16_pipe<false, 1, 4>(g2, st);
     }
     if (gather_rows) return hipErrorInvalidValue;
