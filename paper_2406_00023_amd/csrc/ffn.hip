@@ -7,10 +7,11 @@
 // accumulation.  Both operands are K-contiguous, staged through LDS in 16-byte chunks
 // with an XOR swizzle, double-buffered.  GEMM-1 computes the gate and the up projection
 // of the same output tile so that SiLU(g)*u is its epilogue and the hidden activation
-// crosses HBM once, in bf16.  The grid is sized for `capacity`; a workgroup whose row
-// tile starts past counts[e] exits at once, so counts never leave the device.
+// crosses HBM once, in bf16.  The kernel the layer launches is the persistent one
+// (gemm_bf16_persist_kernel: one workgroup per CU walks the live tiles, the copy ring runs
+// across tile boundaries); the per-tile kernels size the grid for `capacity` and a workgroup
+// whose row tile starts past counts[e] exits at once.  Either way counts never leave the device.
 // fp32: plain LDS-tiled FMA kernels (parity path for small layers).
-#include <type_traits>
 
 #include "etr_internal.h"
 
