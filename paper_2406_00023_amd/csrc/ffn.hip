@@ -31,7 +31,6 @@ struct GemmParams {
     int MT, NT;           // row tiles per expert, column tiles
     int SM, SN;           // super-tile shape (see decode_tile)
     const int32_t* row_index;   // optional [E][capacity]: A row m of expert e is row row_index[e][m] of A
-    int k_stagger;              // pipelined kernels: workgroup j of an XCD starts its K loop (j % 32) * k_stagger tiles in
     int a_rows;                 // rows of A that row_index may name (indices are clamped into [0, a_rows))
     int lda = 0, ldb = 0;       // row strides of A and B in elements (0: K)
     const int32_t* k_counts = nullptr;   // optional per-group contraction length; it is rounded up to a multiple
@@ -61,10 +60,9 @@ __device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a));
 // SM row tiles x SN column tiles (SM*SN = 32 = the workgroups that run together on one XCD); a whole
 // super-tile goes to one XCD, so while its 32 workgroups stream along K together every token-row
 // slice is shared by SN of them and every weight slice by SM of them through that XCD's L2.
-__device__ __forceinline__ bool decode_tile(const GemmParams& p, int& e, int& mt, int& nt, int* seq = nullptr) {
+__device__ __forceinline__ bool decode_tile(const GemmParams& p, int& e, int& mt, int& nt) {
     const int pid = blockIdx.x;
     const int xcd = pid & 7, j = pid >> 3;
-    if (seq) *seq = j;
     const int per = p.SM * p.SN;
     const int sidx = (j / per) * 8 + xcd, l = j % per;
     const int MG = (p.MT + p.SM - 1) / p.SM, NG = (p.NT + p.SN - 1) / p.SN;
@@ -271,8 +269,8 @@ __device__ __forceinline__ void wg_barrier() {
 typedef const __attribute__((address_space(1))) void* global_cptr;
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
-template <bool GLU, int SWZ, bool PROF = false, int WN = 2>
-__global__ __launch_bounds__(128 * WN) void gemm_bf16_pipe_kernel(GemmParams p, long long* prof = nullptr) {
+template <bool GLU, int SWZ, int WN = 2>
+__global__ __launch_bounds__(128 * WN) void gemm_bf16_pipe_kernel(GemmParams p) {
     constexpr int BM = 256, BR = 256, CPR = 8;
     constexpr int NW = 2 * WN;                          // waves: 2 row groups x WN column groups
     constexpr int TB = 4 / (WN / 2);                    // weight fragments per wave and k-substep (4 or 2)
@@ -374,8 +372,6 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_pipe_kernel(GemmParams p, 
     __builtin_amdgcn_s_barrier();
     load_frags(0, 0, 0);
 
-    long long t_wait = 0, t_bar = 0, t_loop0 = 0;
-    if constexpr (PROF) t_loop0 = clock64();
     for (int kt = 0; kt < KT; ++kt) {
         const int cur = kt & 1;
         __builtin_amdgcn_sched_barrier(0);
@@ -389,28 +385,14 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_pipe_kernel(GemmParams p, 
         mfma_step(0);
         __builtin_amdgcn_sched_barrier(0);
         // tile kt+1 has landed for every wave and nobody reads buffer `cur` any more
-        long long c0 = 0, c1 = 0;
-        if constexpr (PROF) { c0 = clock64(); __builtin_amdgcn_sched_barrier(0); }
         __builtin_amdgcn_s_waitcnt(0x0070);             // vmcnt(0) lgkmcnt(0)
-        if constexpr (PROF) { __builtin_amdgcn_sched_barrier(0); c1 = clock64(); __builtin_amdgcn_sched_barrier(0); }
         __builtin_amdgcn_s_barrier();
-        if constexpr (PROF) {
-            __builtin_amdgcn_sched_barrier(0);
-            long long c2 = clock64();
-            t_wait += c1 - c0; t_bar += c2 - c1;
-        }
         __builtin_amdgcn_sched_barrier(0);
         if (kt + 2 < KT) issue_copies(kt + 2, cur);
         if (kt + 1 < KT) load_frags(0, cur ^ 1, 0);
         mfma_step(1);
     }
 
-    if constexpr (PROF) {
-        if (lane == 0 && prof) {
-            long long* o = prof + (static_cast<size_t>(blockIdx.x) * NW + wave) * 4;
-            o[0] = clock64() - t_loop0; o[1] = t_wait; o[2] = t_bar; o[3] = KT;
-        }
-    }
     // ---- epilogue: lane holds, per 32x32 block, row m = lane%32 and columns (v/4)*8 + (lane/32)*4 + v%4
     uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(e) * p.capacity * p.N;
     constexpr int TO = GLU ? TB / 2 : TB;              // output blocks per wave row
@@ -446,7 +428,7 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_pipe_kernel(GemmParams p, 
 // s_waitcnt immediate: vmcnt(n) (6 bits, split 3:0 and 15:14), expcnt untouched, lgkmcnt(0) or untouched
 constexpr int waitcnt_imm(int vm, bool lgkm0) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm0 ? 0 : 0x0F00); }
 
-template <bool GLU, int WN = 2, int AUXA = 0, int AUXB = 0, bool DUAL = false, int NBUF = 4>
+template <bool GLU, int WN = 2, bool DUAL = false, int NBUF = 4>
 __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) {
     constexpr int BM = 256, BR = 256, CPR = 4;
     constexpr int BN = GLU ? 128 : 256;
@@ -457,8 +439,8 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     uint4* lds = reinterpret_cast<uint4*>(lds_raw);
 
-    int e, mt, nt, seq;
-    if (!decode_tile(p, e, mt, nt, &seq)) return;
+    int e, mt, nt;
+    if (!decode_tile(p, e, mt, nt)) return;
     const int count = group_rows(p, e);
     const int m0 = mt * BM, n0 = nt * BN;
     if (m0 >= count) return;
@@ -469,9 +451,6 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
     const int r32 = lane & 31, half = lane >> 5;
     const int KCA = (p.lda ? p.lda : p.K) / 8, KCB = (p.ldb ? p.ldb : p.K) / 8;   // 16-byte chunks per operand row
     const int KT = group_k(p, e) / 32;
-    // staggered start of the K loop (see the ping-pong kernel): turns simultaneous misses on shared
-    // tiles into one miss and later L2 hits; accumulation order depends on the tile index only
-    const int kt0 = KT > 0 ? static_cast<int>((static_cast<long long>(seq & 31) * p.k_stagger) % KT) : 0;
 
     // ---- copy sources: wave w fills row groups w*NCP .. (16 rows x 4 chunks = 1 KiB each)
     // Addresses are a wave-uniform 64-bit base (scalar registers, advanced by 64 bytes per tile)
@@ -497,14 +476,11 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
         uint4* dst = lds + (kt % NBUF) * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
         // re-materialise the tile base as a scalar every time, so that the address stays
         // "scalar base + 32-bit lane offset" instead of a per-lane 64-bit pointer
-        int tk = kt + kt0;
-        tk = tk >= KT ? tk - KT : tk;
-        const uint64_t b64 = reinterpret_cast<uint64_t>(j < NCP ? Abase : Bbase) + static_cast<uint64_t>(tk) * (CPR * 16);
+        const uint64_t b64 = reinterpret_cast<uint64_t>(j < NCP ? Abase : Bbase) + static_cast<uint64_t>(kt) * (CPR * 16);
         const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
         const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
         const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
-        if (j < NCP) __builtin_amdgcn_global_load_lds((global_cptr)(base + off[j]), (lds_ptr)dst, 16, 0, AUXA);
-        else __builtin_amdgcn_global_load_lds((global_cptr)(base + off[j]), (lds_ptr)dst, 16, 0, AUXB);
+        __builtin_amdgcn_global_load_lds((global_cptr)(base + off[j]), (lds_ptr)dst, 16, 0, 0);
     };
 
     const int sw = (r32 >> 2) & 3;
@@ -885,176 +861,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Ping-pong variant: eight waves, two per SIMD.  A wave alternates between a MEMORY slot
-// (ds_read all MFMA operands of its next k-tile, issue its share of the asynchronous copies
-// of tile t+3) and a COMPUTE slot (16 MFMAs on a 128 x 64 slice).  The two waves of a SIMD
-// are one slot apart, so while one is held up issuing memory instructions the other feeds
-// the MFMA unit.  Every slot ends with a workgroup barrier; group 1 takes one extra barrier
-// before its loop and group 0 one after, which creates the offset with equal barrier counts.
-//   BK = 32, ring of four 32 KiB LDS buffers; tile t lives in buffer t % 4; it is read by
-//   group 0 in slot 2t and by group 1 in slot 2t+1, and overwritten by tile t+4 whose copies
-//   are issued in slots 2t+2 / 2t+3.  A wave makes sure its own copies of tile t+1 have
-//   landed (s_waitcnt vmcnt) before the barrier that ends slot 2t+1.
-// ---------------------------------------------------------------------------------------
-template <bool GLU, int GROUPING, int DEBUG_SKIP = 0>   // DEBUG_SKIP 1: no MFMAs, 2: no copies after the prologue (measurement only)
-__global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmParams p) {
-    constexpr int BM = 256, BR = 256, CPR = 4, NBUF = 4;
-    constexpr int BN = GLU ? 128 : 256;
-    constexpr int STAGE = (BM + BR) * CPR;              // uint4 per LDS buffer (32 KiB)
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    uint4* lds = reinterpret_cast<uint4*>(lds_raw);
-
-    int e, mt, nt, seq;
-    if (!decode_tile(p, e, mt, nt, &seq)) return;
-    const int count = min(p.counts[e], p.capacity);
-    const int m0 = mt * BM, n0 = nt * BN;
-    if (m0 >= count) return;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int grp = GROUPING == 0 ? (wave >> 2) : (wave & 1);      // ping-pong group
-    const int q = GROUPING == 0 ? (wave & 3) : (wave >> 1);        // wave within the group
-    const int wm = q >> 1, wn = q & 1;
-    const int r32 = lane & 31, half = lane >> 5;
-    const int KC = p.K / 8, KT = p.K / 32;
-    // The ~32 workgroups that run together on an XCD share weight tiles (same band) and token tiles
-    // (same row tile).  Starting each one at a different k-tile (and wrapping around) makes one of
-    // them fetch a line from HBM while the others find it in L2 later, instead of all of them
-    // waiting on the same fill.  The order of the fp32 accumulation then depends on the tile index
-    // only, so results stay bit-reproducible.
-    const int kt0 = static_cast<int>((static_cast<long long>(seq & 31) * p.k_stagger) % KT);
-
-    // ---- copy sources: wave w fills A row groups 2w, 2w+1 and weight row groups 2w, 2w+1
-    // (16 rows x 4 chunks = 1 KiB each); address = scalar base + constant 32-bit lane offset
-    const char* Abase = reinterpret_cast<const char*>(p.A) +
-                        (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KC * 16);
-    const char* Bbase = reinterpret_cast<const char*>((GLU && wave >= 4) ? p.B1 : p.B0) +
-                        static_cast<size_t>(e) * p.N * KC * 16;
-    uint32_t off[4];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int r = (wave * 2 + i) * 16 + (lane >> 2);
-        const int c = (lane & 3) ^ ((r >> 2) & 3);
-        int m = m0 + r;
-        m = m < count ? m : count - 1;                   // rows past the count replay a valid row; never stored
-        const int row = p.row_index ? min(max(p.row_index[static_cast<size_t>(e) * p.capacity + m], 0), p.a_rows - 1) : m;
-        off[i] = (static_cast<uint32_t>(row) * KC + c) * 16u;
-        int n = n0 + (GLU ? (r & 127) : r);
-        n = n < p.N ? n : p.N - 1;
-        off[2 + i] = (static_cast<uint32_t>(n) * KC + c) * 16u;
-    }
-    auto issue_copies = [&](int t) {
-        uint4* dst = lds + (t & (NBUF - 1)) * STAGE + wave * 128;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            int tk = t + kt0;
-            tk = tk >= KT ? tk - KT : tk;
-            const char* src = (j < 2 ? Abase : Bbase) + static_cast<size_t>(tk) * (CPR * 16) + off[j];
-            __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(dst + (j >> 1) * (BM * CPR) + (j & 1) * 64), 16, 0, 0);
-        }
-    };
-
-    // ---- MFMA operand addressing
-    const int sw = (r32 >> 2) & 3;
-    int a_row[4], b_row[2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a_row[i] = (wm * 128 + i * 32 + r32) * CPR;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        // GLU: fragment 0 = gate rows, fragment 1 = up rows of the same 32 output columns
-        const int br = GLU ? (j * 128 + grp * 64 + wn * 32) : (grp * 128 + wn * 64 + j * 32);
-        b_row[j] = BM * CPR + (br + r32) * CPR;
-    }
-    const int ck[2] = {half ^ sw, (2 + half) ^ sw};
-
-    f32x16 acc[4][2];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    bf16x8 fa[2][4], fb[2][2];
-    auto memory_slot = [&](int t) {
-        const uint4* base = lds + (t & (NBUF - 1)) * STAGE;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) fa[ks][i] = __builtin_bit_cast(bf16x8, base[a_row[i] + ck[ks]]);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) fb[ks][j] = __builtin_bit_cast(bf16x8, base[b_row[j] + ck[ks]]);
-        }
-        if (DEBUG_SKIP != 2 && t >= 1 && t + 3 < KT) issue_copies(t + 3);
-    };
-    auto compute_slot = [&]() {
-        if (DEBUG_SKIP == 1) return;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks][j], fa[ks][i], acc[i][j], 0, 0, 0);
-    };
-    // own copies of tile t+1 have landed: at most the copies of tiles t+2 and t+3 may be outstanding
-    auto wait_tile_after = [&](int t) {
-        const int later = KT - 2 - t;                    // tiles after t+1 that have been issued (capped at 2)
-        if (later >= 2) __builtin_amdgcn_s_waitcnt(0x0F78);        // vmcnt(8)
-        else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
-        else __builtin_amdgcn_s_waitcnt(0x0F70);                   // vmcnt(0)
-    };
-
-    // ---- prologue: up to four tiles in flight; tile 0 must be in LDS for everybody
-    const int pre = KT < 4 ? KT : 4;
-    for (int t = 0; t < pre; ++t) issue_copies(t);
-    if (pre == 4) __builtin_amdgcn_s_waitcnt(0x0F7C);        // vmcnt(12)
-    else if (pre == 3) __builtin_amdgcn_s_waitcnt(0x0F78);   // vmcnt(8)
-    else if (pre == 2) __builtin_amdgcn_s_waitcnt(0x0F74);   // vmcnt(4)
-    else __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0)
-    wg_barrier();
-
-    if (grp == 1) wg_barrier();              // one slot behind group 0
-    for (int t = 0; t < KT; ++t) {
-        __builtin_amdgcn_sched_barrier(0);
-        memory_slot(t);
-        if (grp == 1) wait_tile_after(t);
-        __builtin_amdgcn_s_waitcnt(0xC07F);                  // lgkmcnt(0): operands are in registers, buffer may be recycled
-        wg_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        compute_slot();
-        __builtin_amdgcn_sched_barrier(0);
-        if (grp == 0) wait_tile_after(t);
-        wg_barrier();
-    }
-    if (grp == 0) wg_barrier();
-
-    // ---- epilogue: lane holds, per 32x32 block, row m = lane%32 and columns (v/4)*8 + (lane/32)*4 + v%4
-    uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(e) * p.capacity * p.N;
-    constexpr int TO = GLU ? 1 : 2;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + wm * 128 + i * 32 + r32;
-        if (m >= count) continue;
-#pragma unroll
-        for (int j = 0; j < TO; ++j)
-#pragma unroll
-            for (int qq = 0; qq < 4; ++qq) {
-                const int n = n0 + (GLU ? grp * 64 + wn * 32 : grp * 128 + wn * 64 + j * 32) + qq * 8 + half * 4;
-                if (n >= p.N) continue;
-                float o[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    if constexpr (GLU) o[v] = silu(acc[i][0][qq * 4 + v]) * acc[i][1][qq * 4 + v];
-                    else o[v] = acc[i][j][qq * 4 + v];
-                }
-                uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
-                *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
-            }
-    }
-}
-
-// ---------------------------------------------------------------------------------------
 // fp32 grouped GEMM, 64x64 tile, 4x4 outputs per thread, plain FMA
 // ---------------------------------------------------------------------------------------
 template <bool GLU, bool DUAL = false>
@@ -1151,19 +957,19 @@ template <bool GLU, int SWZ, int WN = 2>
 hipError_t launch_bf16_pipe(GemmParams p, hipStream_t st) {
     constexpr size_t lds = 2ull * 512 * 64 * 2;        // two buffers of 256 + 256 rows x 64 bf16
     const long long blocks = plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_pipe_kernel<GLU, SWZ, false, WN>;
+    auto kern = gemm_bf16_pipe_kernel<GLU, SWZ, WN>;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(blocks)), dim3(128 * WN), lds, st, p, static_cast<long long*>(nullptr));
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(blocks)), dim3(128 * WN), lds, st, p);
     return hipGetLastError();
 }
 
-template <bool GLU, int WN = 2, int AUXA = 0, int AUXB = 0, bool DUAL = false, int NBUF = 4>
+template <bool GLU, int WN = 2, bool DUAL = false, int NBUF = 4>
 hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
     constexpr size_t lds = static_cast<size_t>(NBUF) * 512 * 32 * 2;        // NBUF buffers of 256 + 256 rows x 32 bf16
     const long long blocks = plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_ring_kernel<GLU, WN, AUXA, AUXB, DUAL, NBUF>;
+    auto kern = gemm_bf16_ring_kernel<GLU, WN, DUAL, NBUF>;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (err != hipSuccess) return err;
@@ -1190,18 +996,6 @@ inline bool persist_ok(const GemmParams& g, bool glu) {
     const long long MG = (t.MT + t.SM - 1) / t.SM, NG = (t.NT + t.SN - 1) / t.SN;
     // (with k_counts the contraction is at least min(128, K) long: four k-tiles)
     return g.K >= 128 && static_cast<long long>(g.E) * MG * NG <= kMaxSuper;
-}
-
-template <bool GLU, int GROUPING, int DEBUG_SKIP = 0>
-hipError_t launch_bf16_pp(GemmParams p, hipStream_t st) {
-    constexpr size_t lds = 4ull * 512 * 32 * 2;
-    const long long blocks = plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_pp_kernel<GLU, GROUPING, DEBUG_SKIP>;
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-    if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(blocks)), dim3(512), lds, st, p);
-    return hipGetLastError();
 }
 
 template <bool GLU, bool DUAL = false>
@@ -1235,7 +1029,7 @@ static bool pipelined_ok(const GemmParams& g, size_t a_rows) {
 // General entry for the other stages of the library: grouped "NT" product
 //   C[g][m][n] = sum_k A[g][m][k] * B[g][n][k],  g < G, m < m_counts[g] (or M), k < k_counts[g] (or K).
 hipError_t launch_grouped_gemm(const GroupedGemm& q, hipStream_t st) {
-    GemmParams g{q.A, q.B0, q.B1, q.C, q.m_counts, q.G, q.M, q.N, q.K, 0, 0, 0, 0, q.row_index, 0, q.a_rows};
+    GemmParams g{q.A, q.B0, q.B1, q.C, q.m_counts, q.G, q.M, q.N, q.K, 0, 0, 0, 0, q.row_index, q.a_rows};
     g.lda = q.lda; g.ldb = q.ldb; g.k_counts = q.k_counts; g.C2 = q.C2;
     if (q.N % 4 != 0 || q.K < 0 || q.G < 1 || q.M < 1) return hipErrorInvalidValue;
     if (q.dtype == ETR_BF16) {
@@ -1252,7 +1046,7 @@ hipError_t launch_grouped_gemm(const GroupedGemm& q, hipStream_t st) {
         switch (q.epilogue) {
             case GEMM_PLAIN: return ring ? launch_bf16_ring<false, 4>(g, st) : launch_bf16<128, 128, 64, 2, 2, false, 1>(g, st);
             case GEMM_SWIGLU: return ring ? launch_bf16_ring<true, 4>(g, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g, st);
-            case GEMM_DUAL: return ring ? launch_bf16_ring<true, 4, 0, 0, true>(g, st) : launch_bf16<128, 64, 64, 2, 2, true, 1, true>(g, st);
+            case GEMM_DUAL: return ring ? launch_bf16_ring<true, 4, true>(g, st) : launch_bf16<128, 64, 64, 2, 2, true, 1, true>(g, st);
         }
         return hipErrorInvalidValue;
     }
@@ -1267,7 +1061,7 @@ hipError_t launch_grouped_gemm(const GroupedGemm& q, hipStream_t st) {
 
 bool ffn_can_gather(const etr_config& c) {
     if (c.dtype != ETR_BF16) return false;
-    GemmParams g1{nullptr, nullptr, nullptr, nullptr, nullptr, c.E, c.capacity, c.H, c.d, 0, 0, 0, 0, nullptr, 0, c.T};
+    GemmParams g1{nullptr, nullptr, nullptr, nullptr, nullptr, c.E, c.capacity, c.H, c.d, 0, 0, 0, 0, nullptr, c.T};
     return pipelined_ok(g1, static_cast<size_t>(c.T));
 }
 
@@ -1276,8 +1070,8 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
                              hipEvent_t between, const int32_t* gather_rows) {
     // with gather_rows (= slot_token) xp is the token matrix x itself and GEMM-1 fetches row
     // gather_rows[e][s] of it: the rearrangement is folded into the operand load
-    GemmParams g1{xp, w_gate, w_up, hidden, counts, c.E, c.capacity, c.H, c.d, 0, 0, 0, 0, gather_rows, 0, c.T};
-    GemmParams g2{hidden, w_down, nullptr, yp, counts, c.E, c.capacity, c.d, c.H, 0, 0, 0, 0, nullptr, 0, c.capacity};
+    GemmParams g1{xp, w_gate, w_up, hidden, counts, c.E, c.capacity, c.H, c.d, 0, 0, 0, 0, gather_rows, c.T};
+    GemmParams g2{hidden, w_down, nullptr, yp, counts, c.E, c.capacity, c.d, c.H, 0, 0, 0, 0, nullptr, c.capacity};
     hipError_t err;
     if (c.dtype == ETR_BF16) {
         if (gather_rows && !ffn_can_gather(c)) return hipErrorInvalidValue;
