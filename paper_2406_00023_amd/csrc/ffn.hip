@@ -737,7 +737,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
         for (int j = 0; j < TB; ++j) fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
     };
 
-    int q = xcd * GS + slot_l;                           // round 0
+    int q = xcd * GS + slot_l;                           // first pass over the list
     if (q >= total) return;                              // uniform: nothing for this workgroup
     Tile cur, nxt;
     setup(q, cur);
