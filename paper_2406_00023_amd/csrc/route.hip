@@ -196,7 +196,22 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteParams p, con
         float acc = 0.f, gg = 0.f;
         if (e_lane < p.E) {
             const float* wr = Ws + e_lane * p.w_stride;
-            for (int q = sub; q < p.P; q += p.L) acc += g[q] * wr[q];
+            if ((p.P & 3) == 0) {
+                // four pooled features per LDS access and four independent accumulators: the loop is bound by
+                // LDS latency, not bandwidth (the row stride makes the 16-byte reads conflict-free, see launch_route)
+                const float4* g4 = reinterpret_cast<const float4*>(g);
+                const float4* w4 = reinterpret_cast<const float4*>(wr);
+                float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+#pragma unroll 4
+                for (int q = sub; q < (p.P >> 2); q += p.L) {
+                    const float4 gv = g4[q], wv = w4[q];
+                    a0 = fmaf(gv.x, wv.x, a0); a1 = fmaf(gv.y, wv.y, a1);
+                    a2 = fmaf(gv.z, wv.z, a2); a3 = fmaf(gv.w, wv.w, a3);
+                }
+                acc = (a0 + a1) + (a2 + a3);
+            } else {
+                for (int q = sub; q < p.P; q += p.L) acc += g[q] * wr[q];
+            }
         }
         for (int m = 1; m < p.L; m <<= 1) acc += __shfl_xor(acc, m, kWave);
         float den;
@@ -233,7 +248,11 @@ hipError_t launch_route(const etr_config& c, const void* x, const float* w_emb, 
     int e2 = 1;
     while (e2 < c.E) e2 <<= 1;
     p.L = kWave / e2;
-    p.w_stride = p.P + ((p.L - p.P % 64) % 64 + 64) % 64;
+    // LDS row stride of the embeddings.  Scalar walk (P % 4 != 0): stride = L (mod 64 banks), so the E x L lane grid
+    // reads distinct banks.  Vector walk: a 16-byte read is served 16 lanes at a time = 16/L experts x L lanes x 4
+    // banks, conflict-free when consecutive rows start 4L banks apart.
+    const int step = (p.P % 4 == 0) ? 4 * p.L : p.L;
+    p.w_stride = p.P + ((step - p.P % 64) % 64 + 64) % 64;
     const int V = c.dtype == ETR_BF16 ? 8 : 4;
     p.R = 0;
     if (c.D % V == 0) {
@@ -243,7 +262,7 @@ hipError_t launch_route(const etr_config& c, const void* x, const float* w_emb, 
     const size_t lds = sizeof(float) * (static_cast<size_t>(p.E) * p.w_stride + 64 + kRouteWaves * p.P);
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     int blocks = (c.T + kRouteWaves - 1) / kRouteWaves;
-    if (blocks > 256 * 8) blocks = 256 * 8;
+    if (blocks > 256 * 4) blocks = 256 * 4;          // what is resident at once (4 workgroups per CU): the embeddings are staged once per workgroup
     if (blocks < 1) blocks = 1;
     const bool fast = p.R > 0 && p.d / V <= kWave * kUnroll;
     auto kern = c.dtype == ETR_BF16 ? (fast ? route_kernel<true, true> : route_kernel<true, false>)
