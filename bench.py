@@ -80,10 +80,26 @@ def bench_backward(args, shape, cfg, t, dev):
     dwg, dwu = torch.empty(E, H, d, dtype=dt, device=dev), torch.empty(E, H, d, dtype=dt, device=dev)
     dwd = torch.empty(E, d, H, dtype=dt, device=dev)
     ws = B.alloc_workspace(B.etr_backward_workspace_bytes(cfg), dev)
+    a_saved = b_saved = None
+    train_ms = None
+    if args.saved:
+        a_saved, b_saved = (torch.empty(E, C, H, dtype=dt, device=dev) for _ in range(2))
+        out = torch.empty(T, d, dtype=dt, device=dev)
+        wsf = B.alloc_workspace(B.etr_workspace_bytes(cfg), dev)
+        fwd = lambda: B.etr_moe_forward_train(cfg, t["x"], t["w_emb"], t["w_gate"], t["w_up"], t["w_down"], out, a_saved,
+                                              b_saved, wsf)
+        for _ in range(args.warmup):
+            fwd()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fwd()
+        torch.cuda.synchronize()
+        train_ms = 1e3 * (time.perf_counter() - t0) / args.steps
 
     def step():
         B.etr_moe_backward(cfg, t["x"], t["w_emb"], t["w_gate"], t["w_up"], t["w_down"], score, gate, slot_of,
-                           slot_token, counts, dout, dx, dwg, dwu, dwd, ws)
+                           slot_token, counts, dout, dx, dwg, dwu, dwd, ws, a_saved=a_saved, b_saved=b_saved)
 
     for _ in range(args.warmup):
         step()
@@ -94,14 +110,17 @@ def bench_backward(args, shape, cfg, t, dev):
     torch.cuda.synchronize()
     elapsed = (time.perf_counter() - t0) / args.steps
     rows = int(counts.sum().item())
-    flop = 16.0 * rows * d * H       # recompute 4dH + W_d^T dout 2dH + input gradient 4dH + weight gradients 6dH per kept row
+    # recompute 4dH (not with --saved) + W_d^T dout 2dH + input gradient 4dH + weight gradients 6dH per kept row
+    flop = (12.0 if args.saved else 16.0) * rows * d * H
     peak = PEAK_BF16_TFLOPS if shape.dtype == I.DT_BF16 else PEAK_F32_TFLOPS
     print(json.dumps({
         "metric": "MoE-layer backward tokens/sec on 1 MI355X", "value": T / elapsed, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * elapsed, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if shape.dtype == I.DT_BF16 else "f32",
         "data": "synthetic",
-        "config": {"workload": f"{shape.name} backward: T={T} d={d} E={E} capacity={C} H={H}", "kept_rows": rows},
+        "config": {"workload": f"{shape.name} backward{' (pre-activations kept by the training forward)' if args.saved else ''}: "
+                               f"T={T} d={d} E={E} capacity={C} H={H}", "kept_rows": rows},
+        "forward_train_ms": train_ms,
         "roofline": {"kernel": "all products of the backward pass together (grouped GEMM kernel)",
                      "bound": "mfma" if shape.dtype == I.DT_BF16 else "alu", "achieved": flop / elapsed / 1e12,
                      "peak": peak, "unit": "TFLOP/s", "frac": flop / elapsed / 1e12 / peak, "traffic": None,
@@ -120,6 +139,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--backward", action="store_true",
                     help="time etr_moe_backward instead of the forward (not the headline metric; no cpu_baseline)")
+    ap.add_argument("--saved", action="store_true",
+                    help="with --backward: hand over the pre-activations kept by etr_moe_forward_train (no recomputation)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()

@@ -218,12 +218,14 @@ size_t etr_backward_workspace_bytes(const etr_config* cfg);
  *   dw_down[e] = sum_t gate dout[t] h^T;  dw_gate[e] = sum_t da x_t^T;  dw_up[e] = sum_t db x_t^T
  *   dx[t] = sum_e (Wg^T da + Wu^T db) + sum_e dscore[t][e] d score[t][e] / d x[t]  (Eq. 4 differentiated,
  *           in the form selected by cfg->cos)
- * The pre-activations are recomputed from x (nothing but the routing outputs is kept from forward).
+ * The pre-activations a, b are recomputed from x unless the caller hands over the copies that
+ * etr_moe_forward_train kept (a_saved, b_saved: both or neither; same results either way, bit for bit).
  *   in : x [T][d], w_emb [E][d/D] fp32, w_gate, w_up [E][H][d], w_down [E][d][H], dout [T][d] (dtype);
  *        score, gate [T][E] fp32, slot_of [T][E], slot_token [E][capacity], counts [E]: outputs of the
  *        forward call (etr_route + etr_select, or etr_moe_forward) for the same x and cfg
  *   out: dx [T][d], dw_gate, dw_up [E][H][d], dw_down [E][d][H] in the layer's dtype, overwritten
  *        (not accumulated); dgate, dscore [T][E] fp32, optional (may be NULL)
+ *   a_saved, b_saved [E][capacity][H] dtype in, optional (see above)
  * bf16: products accumulate in fp32; a, b, W_d^T dout and the per-row gradients are rounded to bf16
  * once each between the stages.  E * (d/D) * 4 bytes must fit in 120 KiB (ETR_ERR_UNSUPPORTED). */
 etr_status etr_moe_backward(const etr_config* cfg, const void* x, const float* w_emb,
@@ -231,7 +233,19 @@ etr_status etr_moe_backward(const etr_config* cfg, const void* x, const float* w
                             const float* score, const float* gate, const int32_t* slot_of,
                             const int32_t* slot_token, const int32_t* counts, const void* dout,
                             void* dx, void* dw_gate, void* dw_up, void* dw_down,
-                            float* dgate, float* dscore, void* ws, size_t ws_bytes, void* stream);
+                            float* dgate, float* dscore, const void* a_saved, const void* b_saved,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/* etr_moe_forward in training mode: the same computation and the same `out`, bit for bit, and the
+ * FFN pre-activations of the kept rows are kept for etr_moe_backward (which then skips their
+ * recomputation, a quarter of its matrix work):
+ *   a_save, b_save [E][capacity][H] dtype out: W_gate x and W_up x of buffer row (e, s), s < counts[e]
+ * Everything else as etr_moe_forward. */
+etr_status etr_moe_forward_train(const etr_config* cfg, const void* x, const float* w_emb,
+                                 const void* w_gate, const void* w_up, const void* w_down, void* out,
+                                 float* score, float* gate_out, int32_t* topk_expert, int32_t* slot_of,
+                                 int32_t* slot_token, int32_t* counts, void* a_save, void* b_save,
+                                 void* ws, size_t ws_bytes, void* stream);
 
 /* etr_moe_forward with stage boundaries marked on the stream, for measurement.
  *   events: HOST array of ETR_N_STAGE_EVENTS hipEvent_t handles (as void*), created by the

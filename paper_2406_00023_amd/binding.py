@@ -21,7 +21,8 @@ LIB_PATH = os.path.join(_HERE, "libetr_hip.so")
 EXPORTS = ("etr_workspace_bytes", "etr_select_workspace_bytes", "etr_ffn_workspace_bytes", "etr_status_string",
            "etr_route", "etr_select", "etr_dispatch", "etr_expert_ffn", "etr_combine", "etr_moe_forward",
            "etr_moe_forward_profiled", "etr_select_adaptive", "etr_stats_workspace_bytes", "etr_route_stats",
-           "etr_capacity_lower_bound", "etr_backward_workspace_bytes", "etr_moe_backward")
+           "etr_capacity_lower_bound", "etr_backward_workspace_bytes", "etr_moe_backward",
+           "etr_moe_forward_train")
 N_STAGE_EVENTS = 7
 STAGE_NAMES = ("route", "select", "dispatch", "ffn_gate_up", "ffn_down", "combine")
 
@@ -66,7 +67,8 @@ def load_library():
         "etr_select_adaptive": [cp, vp, vp, ctypes.c_float, vp, vp, vp, vp, vp, sz, vp],
         "etr_route_stats": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "etr_capacity_lower_bound": [cp, vp, vp, vp, vp, sz, vp],
-        "etr_moe_backward": [cp] + [vp] * 18 + [sz, vp],
+        "etr_moe_backward": [cp] + [vp] * 20 + [sz, vp],
+        "etr_moe_forward_train": [cp] + [vp] * 15 + [sz, vp],
         "etr_moe_forward_profiled": [cp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp,
                                      ctypes.POINTER(ctypes.c_void_p)],
     }
@@ -153,11 +155,19 @@ def etr_backward_workspace_bytes(cfg: EtrConfig) -> int:
 
 
 def etr_moe_backward(cfg, x, w_emb, w_gate, w_up, w_down, score, gate, slot_of, slot_token, counts, dout, dx, dw_gate,
-                     dw_up, dw_down, ws, dgate=None, dscore=None):
+                     dw_up, dw_down, ws, dgate=None, dscore=None, a_saved=None, b_saved=None):
     _check("etr_moe_backward", load_library().etr_moe_backward(
         ctypes.byref(cfg), _ptr(x), _ptr(w_emb), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(score), _ptr(gate),
         _ptr(slot_of), _ptr(slot_token), _ptr(counts), _ptr(dout), _ptr(dx), _ptr(dw_gate), _ptr(dw_up), _ptr(dw_down),
-        _ptr(dgate), _ptr(dscore), _ptr(ws), _nbytes(ws), _stream()))
+        _ptr(dgate), _ptr(dscore), _ptr(a_saved), _ptr(b_saved), _ptr(ws), _nbytes(ws), _stream()))
+
+
+def etr_moe_forward_train(cfg, x, w_emb, w_gate, w_up, w_down, out, a_save, b_save, ws, score=None, gate=None,
+                          topk_expert=None, slot_of=None, slot_token=None, counts=None):
+    _check("etr_moe_forward_train", load_library().etr_moe_forward_train(
+        ctypes.byref(cfg), _ptr(x), _ptr(w_emb), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(out), _ptr(score),
+        _ptr(gate), _ptr(topk_expert), _ptr(slot_of), _ptr(slot_token), _ptr(counts), _ptr(a_save), _ptr(b_save),
+        _ptr(ws), _nbytes(ws), _stream()))
 
 
 def etr_dispatch(cfg, x, slot_token, counts, xp):

@@ -185,18 +185,21 @@ etr_status etr_moe_backward(const etr_config* cfg, const void* x, const float* w
                             const void* w_up, const void* w_down, const float* score, const float* gate,
                             const int32_t* slot_of, const int32_t* slot_token, const int32_t* counts,
                             const void* dout, void* dx, void* dw_gate, void* dw_up, void* dw_down, float* dgate,
-                            float* dscore, void* ws, size_t ws_bytes, void* stream) {
+                            float* dscore, const void* a_saved, const void* b_saved, void* ws, size_t ws_bytes,
+                            void* stream) {
     etr_status s = check_config(cfg);
     if (s != ETR_OK) return s;
     ETR_REQUIRE_PTR(x); ETR_REQUIRE_PTR(w_emb); ETR_REQUIRE_PTR(w_gate); ETR_REQUIRE_PTR(w_up); ETR_REQUIRE_PTR(w_down);
     ETR_REQUIRE_PTR(score); ETR_REQUIRE_PTR(gate); ETR_REQUIRE_PTR(slot_of); ETR_REQUIRE_PTR(slot_token);
     ETR_REQUIRE_PTR(counts); ETR_REQUIRE_PTR(dout); ETR_REQUIRE_PTR(dx); ETR_REQUIRE_PTR(dw_gate);
     ETR_REQUIRE_PTR(dw_up); ETR_REQUIRE_PTR(dw_down); ETR_REQUIRE_PTR(ws);
-    ETR_OPTIONAL_PTR(dgate); ETR_OPTIONAL_PTR(dscore);
+    ETR_OPTIONAL_PTR(dgate); ETR_OPTIONAL_PTR(dscore); ETR_OPTIONAL_PTR(a_saved); ETR_OPTIONAL_PTR(b_saved);
+    if ((a_saved == nullptr) != (b_saved == nullptr)) return ETR_ERR_NULL;      // both or neither
     if (static_cast<size_t>(cfg->E) * (cfg->d / cfg->D) * 4 > 120 * 1024) return ETR_ERR_UNSUPPORTED;
     if (ws_bytes < backward_ws_bytes(*cfg)) return ETR_ERR_WORKSPACE;
     ETR_HIP(launch_moe_backward(*cfg, x, w_emb, w_gate, w_up, w_down, score, gate, slot_of, slot_token, counts, dout, dx,
-                                dw_gate, dw_up, dw_down, dgate, dscore, ws, static_cast<hipStream_t>(stream)));
+                                dw_gate, dw_up, dw_down, dgate, dscore, ws, static_cast<hipStream_t>(stream), a_saved,
+                                b_saved));
     return ETR_OK;
 }
 
@@ -232,7 +235,8 @@ etr_status etr_combine(const etr_config* cfg, const void* yp, const float* gate,
 static etr_status forward_impl(const etr_config* cfg, const void* x, const float* w_emb, const void* w_gate,
                                const void* w_up, const void* w_down, void* out, float* score, float* gate_out,
                                int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts, void* ws,
-                               size_t ws_bytes, void* stream, void* const* events) {
+                               size_t ws_bytes, void* stream, void* const* events, void* a_save = nullptr,
+                               void* b_save = nullptr) {
     etr_status s = check_config(cfg);
     if (s != ETR_OK) return s;
     ETR_REQUIRE_PTR(x); ETR_REQUIRE_PTR(w_emb); ETR_REQUIRE_PTR(w_gate); ETR_REQUIRE_PTR(w_up);
@@ -268,7 +272,7 @@ static etr_status forward_impl(const etr_config* cfg, const void* x, const float
     if (!gather) ETR_HIP(launch_dispatch(*cfg, x, stn, cn, xp, st));
     ETR_HIP(mark(3));
     ETR_HIP(launch_expert_ffn(*cfg, gather ? x : xp, cn, w_gate, w_up, w_down, yp, hidden, st,
-                              events ? static_cast<hipEvent_t>(events[4]) : nullptr, gather ? stn : nullptr));
+                              events ? static_cast<hipEvent_t>(events[4]) : nullptr, gather ? stn : nullptr, a_save, b_save));
     ETR_HIP(mark(5));
     ETR_HIP(launch_combine(*cfg, yp, gt, so, out, st));
     ETR_HIP(mark(6));
@@ -281,6 +285,15 @@ etr_status etr_moe_forward(const etr_config* cfg, const void* x, const float* w_
                            size_t ws_bytes, void* stream) {
     return forward_impl(cfg, x, w_emb, w_gate, w_up, w_down, out, score, gate_out, topk_expert, slot_of, slot_token,
                         counts, ws, ws_bytes, stream, nullptr);
+}
+
+etr_status etr_moe_forward_train(const etr_config* cfg, const void* x, const float* w_emb, const void* w_gate,
+                                 const void* w_up, const void* w_down, void* out, float* score, float* gate_out,
+                                 int32_t* topk_expert, int32_t* slot_of, int32_t* slot_token, int32_t* counts,
+                                 void* a_save, void* b_save, void* ws, size_t ws_bytes, void* stream) {
+    ETR_REQUIRE_PTR(a_save); ETR_REQUIRE_PTR(b_save);
+    return forward_impl(cfg, x, w_emb, w_gate, w_up, w_down, out, score, gate_out, topk_expert, slot_of, slot_token,
+                        counts, ws, ws_bytes, stream, nullptr, a_save, b_save);
 }
 
 etr_status etr_moe_forward_profiled(const etr_config* cfg, const void* x, const float* w_emb, const void* w_gate,

@@ -371,7 +371,8 @@ template <typename T>
 hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb, const void* w_gate, const void* w_up,
                          const void* w_down, const float* score, const float* gate, const int32_t* slot_of,
                          const int32_t* slot_token, const int32_t* counts, const void* dout, void* dx, void* dw_gate,
-                         void* dw_up, void* dw_down, float* dgate, float* dscore, void* ws, hipStream_t st) {
+                         void* dw_up, void* dw_down, float* dgate, float* dscore, void* ws, hipStream_t st,
+                         const void* a_saved, const void* b_saved) {
     const BackwardWs L = backward_layout(c);
     char* base = static_cast<char*>(ws);
     auto at = [&](size_t off) { return reinterpret_cast<T*>(base + off); };
@@ -396,11 +397,16 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
         gate_w = ge;
     }
     // a, b recomputed from the gathered token rows; u = gathered upstream gradient times Wd
-    GroupedGemm g1{x, w_gate, w_up, at(L.a), at(L.b), counts, nullptr, slot_token, E, C, H, d, 0, 0, Tn, GEMM_DUAL, c.dtype};
-    ETR_BW(launch_grouped_gemm(g1, st));
+    const T* pre_a = static_cast<const T*>(a_saved);
+    const T* pre_b = static_cast<const T*>(b_saved);
+    if (!pre_a || !pre_b) {                              // nothing kept from the forward call: recompute
+        GroupedGemm g1{x, w_gate, w_up, at(L.a), at(L.b), counts, nullptr, slot_token, E, C, H, d, 0, 0, Tn, GEMM_DUAL, c.dtype};
+        ETR_BW(launch_grouped_gemm(g1, st));
+        pre_a = at(L.a); pre_b = at(L.b);
+    }
     GroupedGemm g2{dout, at(L.wdT), nullptr, at(L.u), nullptr, counts, nullptr, slot_token, E, C, H, d, 0, 0, Tn, GEMM_PLAIN, c.dtype};
     ETR_BW(launch_grouped_gemm(g2, st));
-    hipLaunchKernelGGL(swiglu_backward_kernel<T>, dim3(cH, cC, E), dim3(kTileThreads), 0, st, at(L.u), at(L.a), at(L.b), gate_w,
+    hipLaunchKernelGGL(swiglu_backward_kernel<T>, dim3(cH, cC, E), dim3(kTileThreads), 0, st, at(L.u), pre_a, pre_b, gate_w,
                        slot_token, counts, at(L.dab), at(L.daT), at(L.dbT), at(L.hT),
                        reinterpret_cast<float*>(base + L.dgate_part), Tn, E, C, Cp, H);
     hipLaunchKernelGGL((gather_transpose_kernel<T, false>), dim3(cd, cC, E), dim3(kTileThreads), 0, st,
@@ -439,13 +445,13 @@ hipError_t launch_moe_backward(const etr_config& c, const void* x, const float* 
                                const void* w_up, const void* w_down, const float* score, const float* gate,
                                const int32_t* slot_of, const int32_t* slot_token, const int32_t* counts,
                                const void* dout, void* dx, void* dw_gate, void* dw_up, void* dw_down, float* dgate,
-                               float* dscore, void* ws, hipStream_t st) {
+                               float* dscore, void* ws, hipStream_t st, const void* a_saved, const void* b_saved) {
     if (static_cast<size_t>(c.E) * (c.d / c.D) * 4 > 120 * 1024) return hipErrorInvalidValue;   // embeddings must fit in LDS
     if (c.dtype == ETR_BF16)
         return backward_impl<uint16_t>(c, x, w_emb, w_gate, w_up, w_down, score, gate, slot_of, slot_token, counts, dout,
-                                       dx, dw_gate, dw_up, dw_down, dgate, dscore, ws, st);
+                                       dx, dw_gate, dw_up, dw_down, dgate, dscore, ws, st, a_saved, b_saved);
     return backward_impl<float>(c, x, w_emb, w_gate, w_up, w_down, score, gate, slot_of, slot_token, counts, dout, dx,
-                                dw_gate, dw_up, dw_down, dgate, dscore, ws, st);
+                                dw_gate, dw_up, dw_down, dgate, dscore, ws, st, a_saved, b_saved);
 }
 
 }  // namespace etr

@@ -50,7 +50,8 @@ size_t ffn_ws_bytes(const etr_config& c);
 hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t* counts, const void* w_gate,
                              const void* w_up, const void* w_down, void* yp, void* hidden, hipStream_t st,
                              hipEvent_t between = nullptr,    // optional event recorded between the two GEMMs
-                             const int32_t* gather_rows = nullptr);   // see ffn_can_gather
+                             const int32_t* gather_rows = nullptr,    // see ffn_can_gather
+                             void* a_save = nullptr, void* b_save = nullptr);   // optional [E][capacity][H]: W_gate x, W_up x
 // True when GEMM-1 can read its rows straight from the token matrix through slot_token
 // (then xp is never materialised by the fused forward).
 bool ffn_can_gather(const etr_config& c);
@@ -78,7 +79,8 @@ hipError_t launch_moe_backward(const etr_config& c, const void* x, const float* 
                                const void* w_up, const void* w_down, const float* score, const float* gate,
                                const int32_t* slot_of, const int32_t* slot_token, const int32_t* counts,
                                const void* dout, void* dx, void* dw_gate, void* dw_up, void* dw_down,
-                               float* dgate, float* dscore, void* ws, hipStream_t st);
+                               float* dgate, float* dscore, void* ws, hipStream_t st,
+                               const void* a_saved = nullptr, const void* b_saved = nullptr);   // from a training-mode forward
 
 // stats.hip
 size_t stats_ws_bytes(int T, int E);

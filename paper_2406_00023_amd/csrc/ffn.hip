@@ -37,6 +37,7 @@ struct GemmParams {
                                          // of 64, at least 128 (at most K), and the operands must hold zeros in
                                          // that padding
     void* C2 = nullptr;         // DUAL epilogue: the B1 product goes here, the B0 product to C, no activation
+    void* C3 = nullptr;         // SwiGLU epilogue that also keeps the two products: B0 product to C2, B1 product to C3
 };
 
 // rows of group e (counts may be absent: every group has `capacity` rows) and its contraction length
@@ -238,6 +239,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
                     const f32x16& u = acc[NB - 1][i][j];
                     pk = make_uint2(f2bf(u[q * 4]) | (f2bf(u[q * 4 + 1]) << 16), f2bf(u[q * 4 + 2]) | (f2bf(u[q * 4 + 3]) << 16));
                     *reinterpret_cast<uint2*>(C2g + static_cast<size_t>(m) * p.N + n) = pk;
+                }
+                if constexpr (GLU && !DUAL) {
+                    if (p.C3) {                                     // keep the pre-activations (training-mode forward)
+                        const size_t o = (static_cast<size_t>(e) * p.capacity + m) * p.N + n;
+                        const f32x16& g0 = acc[0][i][j];
+                        const f32x16& g1 = acc[NB - 1][i][j];
+                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C2) + o) =
+                            make_uint2(f2bf(g0[q * 4]) | (f2bf(g0[q * 4 + 1]) << 16), f2bf(g0[q * 4 + 2]) | (f2bf(g0[q * 4 + 3]) << 16));
+                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C3) + o) =
+                            make_uint2(f2bf(g1[q * 4]) | (f2bf(g1[q * 4 + 1]) << 16), f2bf(g1[q * 4 + 2]) | (f2bf(g1[q * 4 + 3]) << 16));
+                    }
                 }
             }
     }
@@ -852,6 +864,17 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
                         pk = make_uint2(f2bf(u2[qq * 4]) | (f2bf(u2[qq * 4 + 1]) << 16), f2bf(u2[qq * 4 + 2]) | (f2bf(u2[qq * 4 + 3]) << 16));
                         *reinterpret_cast<uint2*>(C2g + static_cast<size_t>(m) * p.N + n) = pk;
                     }
+                    if constexpr (GLU && !DUAL) {
+                        if (p.C3) {                                 // keep the pre-activations (training-mode forward)
+                            const size_t o = (static_cast<size_t>(cur.e) * p.capacity + m) * p.N + n;
+                            const f32x16& g0 = acc[i][j];
+                            const f32x16& g1 = acc[i][TO + j];
+                            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C2) + o) =
+                                make_uint2(f2bf(g0[qq * 4]) | (f2bf(g0[qq * 4 + 1]) << 16), f2bf(g0[qq * 4 + 2]) | (f2bf(g0[qq * 4 + 3]) << 16));
+                            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C3) + o) =
+                                make_uint2(f2bf(g1[qq * 4]) | (f2bf(g1[qq * 4 + 1]) << 16), f2bf(g1[qq * 4 + 2]) | (f2bf(g1[qq * 4 + 3]) << 16));
+                        }
+                    }
                 }
         }
         if (!has_next) break;
@@ -923,6 +946,13 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmParams p) {
             float* C2g = static_cast<float*>(p.C2) + static_cast<size_t>(e) * p.capacity * p.N;
             *reinterpret_cast<float4*>(C2g + static_cast<size_t>(m) * p.N + n) =
                 make_float4(acc[1][i][0], acc[1][i][1], acc[1][i][2], acc[1][i][3]);
+        }
+        if constexpr (GLU && !DUAL) {
+            if (p.C3) {                                           // keep the pre-activations (training-mode forward)
+                const size_t o = (static_cast<size_t>(e) * p.capacity + m) * p.N + n;
+                *reinterpret_cast<float4*>(static_cast<float*>(p.C2) + o) = make_float4(acc[0][i][0], acc[0][i][1], acc[0][i][2], acc[0][i][3]);
+                *reinterpret_cast<float4*>(static_cast<float*>(p.C3) + o) = make_float4(acc[1][i][0], acc[1][i][1], acc[1][i][2], acc[1][i][3]);
+            }
         }
         float o[4];
 #pragma unroll
@@ -1067,18 +1097,19 @@ bool ffn_can_gather(const etr_config& c) {
 
 hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t* counts, const void* w_gate,
                              const void* w_up, const void* w_down, void* yp, void* hidden, hipStream_t st,
-                             hipEvent_t between, const int32_t* gather_rows) {
+                             hipEvent_t between, const int32_t* gather_rows, void* a_save, void* b_save) {
     // with gather_rows (= slot_token) xp is the token matrix x itself and GEMM-1 fetches row
     // gather_rows[e][s] of it: the rearrangement is folded into the operand load
     GemmParams g1{xp, w_gate, w_up, hidden, counts, c.E, c.capacity, c.H, c.d, 0, 0, 0, 0, gather_rows, c.T};
     GemmParams g2{hidden, w_down, nullptr, yp, counts, c.E, c.capacity, c.d, c.H, 0, 0, 0, 0, nullptr, c.capacity};
+    if (a_save && b_save) { g1.C2 = a_save; g1.C3 = b_save; }      // training mode: GEMM-1 also keeps W_gate x and W_up x
     hipError_t err;
     if (c.dtype == ETR_BF16) {
         if (gather_rows && !ffn_can_gather(c)) return hipErrorInvalidValue;
         const bool pipe1 = pipelined_ok(g1, gather_rows ? static_cast<size_t>(c.T) : static_cast<size_t>(c.capacity));
         const int n_cu = cu_count();
         if (pipe1 && persist_ok(g1, true)) err = launch_bf16_persist<true>(g1, st, n_cu);
-        else err = pipe1 ? launch_bf16_ring<true, 4>(g1, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g1, st);
+        else err = (pipe1 && !g1.C3) ? launch_bf16_ring<true, 4>(g1, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g1, st);
         if (err != hipSuccess) return err;
         if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
         if (!pipelined_ok(g2, c.capacity)) return launch_bf16<128, 128, 64, 2, 2, false, 1>(g2, st);

@@ -131,3 +131,46 @@ def test_backward_full_size_sampled(H, oracle, name):
     e4, e5, e6 = H.scale_rel_err(g_gw, gw), H.scale_rel_err(g_uw, uw), H.scale_rel_err(g_dw, dw)
     _say(f"  dw_gate {e4} dw_up {e5} dw_down {e6}")
     assert e4 <= tol and e5 <= tol and e6 <= tol
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2s", "cfg3s", "odd"])
+def test_training_forward_keeps_pre_activations(H, oracle, name):
+    """etr_moe_forward_train gives the bytes of etr_moe_forward, and the backward fed with the kept
+    pre-activations gives the bytes of the backward that recomputes them."""
+    shape = (I.small_variant(I.CONFIGS["cfg2"], T=300, d=272, H=328) if name == "odd" else SMALL[name]())
+    _say(f"training forward {name} T={shape.T} d={shape.d} E={shape.E} C={shape.capacity} H={shape.H}")
+    bw = Backward(H, shape, shape.mode)                 # recomputing backward on the routing of route + select
+    L, cfg, t = bw.L, bw.L.cfg, bw.L.t
+    dev, dt = "cuda", shape.torch_dtype
+    T, E, C, d, Hh = shape.T, shape.E, cfg.capacity, shape.d, shape.H
+    out_plain = torch.empty(T, d, dtype=dt, device=dev)
+    out_train = torch.empty(T, d, dtype=dt, device=dev)
+    a = torch.full((E, C, Hh), 7.0, dtype=dt, device=dev)
+    b = torch.full((E, C, Hh), 7.0, dtype=dt, device=dev)
+    ws = B.alloc_workspace(B.etr_workspace_bytes(cfg))
+    B.etr_moe_forward(cfg, t["x"], t["w_emb"], t["w_gate"], t["w_up"], t["w_down"], out_plain, ws)
+    slot_of = torch.empty_like(L.slot_of)
+    B.etr_moe_forward_train(cfg, t["x"], t["w_emb"], t["w_gate"], t["w_up"], t["w_down"], out_train, a, b, ws,
+                            slot_of=slot_of)
+    torch.cuda.synchronize()
+    assert torch.equal(out_plain, out_train)
+    assert torch.equal(slot_of, L.slot_of)
+    # the kept values are W_gate x and W_up x of the kept rows (rows past counts[e] untouched)
+    hx = bw.host()
+    counts = H.to_np(L.counts)
+    st = H.to_np(L.slot_token)
+    e = int(np.argmax(counts))
+    rows = hx["x"][st[e, :counts[e]]]
+    xa = oracle.to_f64(rows, shape.dtype)
+    ref_a = xa @ oracle.to_f64(hx["w_gate"][e], shape.dtype).T
+    got_a = oracle.to_f64(H.to_np(a)[e, :counts[e]], shape.dtype)
+    assert H.scale_rel_err(got_a, ref_a) <= H.TOL_OUT[shape.dtype]
+    if counts[e] < C:
+        assert torch.all(a[e, counts[e]:] == 7.0) and torch.all(b[e, counts[e]:] == 7.0)
+    dx2, dwg2, dwu2, dwd2 = (torch.empty_like(v) for v in (bw.dx, bw.dwg, bw.dwu, bw.dwd))
+    wsb = B.alloc_workspace(B.etr_backward_workspace_bytes(cfg))
+    B.etr_moe_backward(cfg, t["x"], t["w_emb"], t["w_gate"], t["w_up"], t["w_down"], L.score, L.gate, L.slot_of,
+                       L.slot_token, L.counts, bw.dout, dx2, dwg2, dwu2, dwd2, wsb, a_saved=a, b_saved=b)
+    torch.cuda.synchronize()
+    for got, want, nm in ((dx2, bw.dx, "dx"), (dwg2, bw.dwg, "dw_gate"), (dwu2, bw.dwu, "dw_up"), (dwd2, bw.dwd, "dw_down")):
+        assert torch.equal(got, want), nm
