@@ -144,13 +144,16 @@ __global__ __launch_bounds__(kTileThreads) void gather_transpose_kernel(const T*
 //   in : u, a, b [E][C][H];  gate through slot_token
 //   out: dab [E][C][2H] = (da | db);  daT, dbT, hT [E][H][Cp];
 //        dgate_part [H/64][E][C]: this tile's share of <u, h> per row (summed by dx_kernel in tile order)
-template <typename T>
+// ROWS: no transposed copies; dab and h are [E][Cp][.] row-major with zero rows from counts[e] to padded_rows (the
+// products that contract over the rows read them through transposing LDS reads); hT then is that row-major h.
+template <typename T, bool ROWS>
 __global__ __launch_bounds__(kTileThreads) void swiglu_backward_kernel(
     const T* __restrict__ u, const T* __restrict__ a, const T* __restrict__ b, const float* __restrict__ gate,
     const int32_t* __restrict__ slot_token, const int32_t* __restrict__ counts, T* __restrict__ dab, T* __restrict__ daT,
     T* __restrict__ dbT, T* __restrict__ hT, float* __restrict__ dgate_part, int T_, int E, int C, int Cp, int H) {
     __shared__ __attribute__((aligned(16))) Tile<T> th, ta, tb;
     constexpr int V = Elt<T>::kVec, CH = kTile / V;
+    const size_t obase = static_cast<size_t>(blockIdx.z) * (ROWS ? Cp : C);     // first row of this expert in dab
     const int e = blockIdx.z, s0 = blockIdx.y * kTile, n0 = blockIdx.x * kTile;
     const int count = min(counts[e], C);
     if (s0 >= padded_rows(count, Cp)) return;
@@ -176,12 +179,22 @@ __global__ __launch_bounds__(kTileThreads) void swiglu_backward_kernel(
                 dbv[i] = dh * sl;
                 dot += uv[i] * hv[i];
             }
-            Elt<T>::store_vec(dab + (ebase + s) * 2 * H + n, dav);
-            Elt<T>::store_vec(dab + (ebase + s) * 2 * H + H + n, dbv);
+            if constexpr (!ROWS) {
+                Elt<T>::store_vec(dab + (obase + s) * 2 * H + n, dav);
+                Elt<T>::store_vec(dab + (obase + s) * 2 * H + H + n, dbv);
+            }
         }
+        if constexpr (ROWS) {
+            if (s < Cp && n < H) {                                   // (s < padded_rows: the block starts below it)
+                Elt<T>::store_vec(dab + (obase + s) * 2 * H + n, dav);
+                Elt<T>::store_vec(dab + (obase + s) * 2 * H + H + n, dbv);
+                Elt<T>::store_vec(hT + (obase + s) * H + n, hv);
+            }
+        } else {
 #pragma unroll
-        for (int i = 0; i < V; ++i) {
-            th.v[r][cc + i] = Elt<T>::narrow(hv[i]); ta.v[r][cc + i] = Elt<T>::narrow(dav[i]); tb.v[r][cc + i] = Elt<T>::narrow(dbv[i]);
+            for (int i = 0; i < V; ++i) {
+                th.v[r][cc + i] = Elt<T>::narrow(hv[i]); ta.v[r][cc + i] = Elt<T>::narrow(dav[i]); tb.v[r][cc + i] = Elt<T>::narrow(dbv[i]);
+            }
         }
         // the CH consecutive lanes of one row add up their shares (fixed order)
 #pragma unroll
@@ -189,11 +202,49 @@ __global__ __launch_bounds__(kTileThreads) void swiglu_backward_kernel(
         if ((q % CH) == 0 && s < count)
             dgate_part[(static_cast<size_t>(blockIdx.x) * E + e) * C + s] = dot;
     }
-    __syncthreads();
-    const size_t tb_off = static_cast<size_t>(e) * H * Cp;
-    store_transposed<T>(th, hT + tb_off, Cp, n0, H, s0, Cp);
-    store_transposed<T>(ta, daT + tb_off, Cp, n0, H, s0, Cp);
-    store_transposed<T>(tb, dbT + tb_off, Cp, n0, H, s0, Cp);
+    if constexpr (!ROWS) {
+        __syncthreads();
+        const size_t tb_off = static_cast<size_t>(e) * H * Cp;
+        store_transposed<T>(th, hT + tb_off, Cp, n0, H, s0, Cp);
+        store_transposed<T>(ta, daT + tb_off, Cp, n0, H, s0, Cp);
+        store_transposed<T>(tb, dbT + tb_off, Cp, n0, H, s0, Cp);
+    }
+}
+
+// dst[e][s][:] = src[slot_token[e][s]][:] (* gate[slot_token[e][s]][e]) for s < counts[e], zero rows from counts[e] to
+// padded_rows; dst is [E][Cp][d].  One wavefront per row, 16 bytes per lane and access.
+template <typename T, bool SCALE>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const T* __restrict__ src, const int32_t* __restrict__ slot_token,
+                                                          const int32_t* __restrict__ counts, const float* __restrict__ gate,
+                                                          T* __restrict__ dst, int T_, int d, int E, int C, int Cp) {
+    constexpr int V = Elt<T>::kVec;
+    const int lane = threadIdx.x & 63;
+    const long long row = static_cast<long long>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (row >= static_cast<long long>(E) * Cp) return;
+    const int e = static_cast<int>(row / Cp), s = static_cast<int>(row - static_cast<long long>(e) * Cp);
+    const int count = min(counts[e], C);
+    if (s >= padded_rows(count, Cp)) return;
+    int t = -1;
+    float gt = 1.0f;
+    if (s < count) {
+        t = slot_token[static_cast<size_t>(e) * C + s];
+        if (t < 0 || t >= T_) t = -1;
+        else if (SCALE) gt = gate[static_cast<size_t>(t) * E + e];
+    }
+    T* out = dst + static_cast<size_t>(row) * d;
+    for (int j = lane * V; j < d; j += 64 * V) {
+        float f[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) f[i] = 0.f;
+        if (t >= 0) {
+            Elt<T>::load_vec(src + static_cast<size_t>(t) * d + j, f);
+            if (SCALE) {
+#pragma unroll
+                for (int i = 0; i < V; ++i) f[i] *= gt;
+            }
+        }
+        Elt<T>::store_vec(out + j, f);
+    }
 }
 
 // Variant with renormalised weights: gate_eff[t][e] = gate[t][e] / (sum of gate[t][.] over the experts that kept t)
@@ -221,7 +272,7 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
                                                  const int32_t* __restrict__ slot_of, const float* __restrict__ dgate_part, int n_part,
                                                  const T* __restrict__ dxp, T* __restrict__ dx, float* __restrict__ dgate_out,
                                                  float* __restrict__ dscore_out, int T_, int d, int E, int D, int C,
-                                                 int cos_mode, int gate_norm) {
+                                                 int cos_mode, int gate_norm, int Cx) {     // Cx: rows per expert of dxp
     extern __shared__ float sm[];
     const int P = d / D;
     float* w = sm;                       // [E][P]
@@ -330,7 +381,7 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
         for (int e = 0; e < E; ++e) {              // ascending expert order, as in the forward sum
             const int s = sl[e];
             if (s >= 0) {
-                Elt<T>::load_vec(dxp + (static_cast<size_t>(e) * C + s) * d + j, f);
+                Elt<T>::load_vec(dxp + (static_cast<size_t>(e) * Cx + s) * d + j, f);
 #pragma unroll
                 for (int i = 0; i < V; ++i) acc[i] += f[i];
             }
@@ -354,13 +405,13 @@ BackwardWs backward_layout(const etr_config& c) {
     w.a = take(E * C * H * es);
     w.b = take(E * C * H * es);
     w.u = take(E * C * H * es);
-    w.dab = take(E * C * 2 * H * es);
+    w.dab = take(E * Cp * 2 * H * es);
     w.daT = take(E * H * Cp * es);
     w.dbT = take(E * H * Cp * es);
     w.hT = take(E * H * Cp * es);
     w.xpT = take(E * d * Cp * es);
     w.dypT = take(E * d * Cp * es);
-    w.dxp = take(E * C * d * es);
+    w.dxp = take(E * Cp * d * es);
     w.dgate_part = take((H + kTile - 1) / kTile * E * C * 4);
     w.gate_eff = take(static_cast<size_t>(c.T) * E * 4);
     w.total = off;
@@ -381,14 +432,6 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
     const unsigned cd = (d + kTile - 1) / kTile, cH = (H + kTile - 1) / kTile, cC = Cp / kTile;
     hipError_t err;
 #define ETR_BW(call) do { if ((err = (call)) != hipSuccess) return err; } while (0)
-    // weights with the contraction index made contiguous: WdT[e][H][d], WguT[e][d][2H] = (Wg^T | Wu^T)
-    hipLaunchKernelGGL(transpose_kernel<T>, dim3(cH, cd, E), dim3(kTileThreads), 0, st, static_cast<const T*>(w_down),
-                       at(L.wdT), d, H, d, 0);
-    hipLaunchKernelGGL(transpose_kernel<T>, dim3(cd, cH, E), dim3(kTileThreads), 0, st, static_cast<const T*>(w_gate),
-                       at(L.wguT), H, d, 2 * H, 0);
-    hipLaunchKernelGGL(transpose_kernel<T>, dim3(cd, cH, E), dim3(kTileThreads), 0, st, static_cast<const T*>(w_up),
-                       at(L.wguT), H, d, 2 * H, H);
-    ETR_BW(hipGetLastError());
     // weights of Eq. 1 as the forward applied them
     const float* gate_w = gate;
     if (c.gate_norm) {
@@ -396,7 +439,7 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
         hipLaunchKernelGGL(gate_eff_kernel, dim3((Tn + 255) / 256), dim3(256), 0, st, gate, slot_of, ge, Tn, E);
         gate_w = ge;
     }
-    // a, b recomputed from the gathered token rows; u = gathered upstream gradient times Wd
+    float* dgate_part = reinterpret_cast<float*>(base + L.dgate_part);
     const T* pre_a = static_cast<const T*>(a_saved);
     const T* pre_b = static_cast<const T*>(b_saved);
     if (!pre_a || !pre_b) {                              // nothing kept from the forward call: recompute
@@ -404,26 +447,71 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
         ETR_BW(launch_grouped_gemm(g1, st));
         pre_a = at(L.a); pre_b = at(L.b);
     }
-    GroupedGemm g2{dout, at(L.wdT), nullptr, at(L.u), nullptr, counts, nullptr, slot_token, E, C, H, d, 0, 0, Tn, GEMM_PLAIN, c.dtype};
-    ETR_BW(launch_grouped_gemm(g2, st));
-    hipLaunchKernelGGL(swiglu_backward_kernel<T>, dim3(cH, cC, E), dim3(kTileThreads), 0, st, at(L.u), pre_a, pre_b, gate_w,
-                       slot_token, counts, at(L.dab), at(L.daT), at(L.dbT), at(L.hT),
-                       reinterpret_cast<float*>(base + L.dgate_part), Tn, E, C, Cp, H);
-    hipLaunchKernelGGL((gather_transpose_kernel<T, false>), dim3(cd, cC, E), dim3(kTileThreads), 0, st,
-                       static_cast<const T*>(x), slot_token, counts, gate, at(L.xpT), Tn, d, E, C, Cp);
-    hipLaunchKernelGGL((gather_transpose_kernel<T, true>), dim3(cd, cC, E), dim3(kTileThreads), 0, st,
-                       static_cast<const T*>(dout), slot_token, counts, gate_w, at(L.dypT), Tn, d, E, C, Cp);
-    ETR_BW(hipGetLastError());
-    // dXp = (da | db) (Wg^T | Wu^T)^T
-    GroupedGemm g3{at(L.dab), at(L.wguT), nullptr, at(L.dxp), nullptr, counts, nullptr, nullptr, E, C, d, 2 * H, 0, 0, C, GEMM_PLAIN, c.dtype};
-    ETR_BW(launch_grouped_gemm(g3, st));
-    // weight gradients: contraction over the kept rows of each expert
-    GroupedGemm g4{at(L.dypT), at(L.hT), nullptr, dw_down, nullptr, nullptr, counts, nullptr, E, d, H, Cp, Cp, Cp, d, GEMM_PLAIN, c.dtype};
-    ETR_BW(launch_grouped_gemm(g4, st));
-    GroupedGemm g5{at(L.daT), at(L.xpT), nullptr, dw_gate, nullptr, nullptr, counts, nullptr, E, H, d, Cp, Cp, Cp, H, GEMM_PLAIN, c.dtype};
-    ETR_BW(launch_grouped_gemm(g5, st));
-    GroupedGemm g6{at(L.dbT), at(L.xpT), nullptr, dw_up, nullptr, nullptr, counts, nullptr, E, H, d, Cp, Cp, Cp, H, GEMM_PLAIN, c.dtype};
-    ETR_BW(launch_grouped_gemm(g6, st));
+
+    // Direct path: the grouped product reads operands whose contraction index is the slow one through transposing
+    // LDS reads, so neither the weights nor the per-row quantities are transposed in memory.
+    //   u = dOut_p Wd (Wd as [d][H]);  dXp = (da|db) (Wg ; Wu) (two [H][d] halves of the contraction);
+    //   dWd = dYp^T h;  dWg = da^T Xp;  dWu = db^T Xp  (contraction over the rows, all operands row-major)
+    GroupedGemm t2{dout, w_down, nullptr, at(L.u), nullptr, counts, nullptr, slot_token, E, C, H, d, 0, H, Tn, GEMM_PLAIN, c.dtype};
+    t2.tb = true;
+    GroupedGemm t3{at(L.dab), w_gate, w_up, at(L.dxp), nullptr, counts, nullptr, nullptr, E, Cp, d, 2 * H, 0, d, Cp, GEMM_PLAIN, c.dtype};
+    t3.tb = true;
+    GroupedGemm t4{at(L.dypT), at(L.hT), nullptr, dw_down, nullptr, nullptr, counts, nullptr, E, d, H, Cp, d, H, d, GEMM_PLAIN, c.dtype};
+    t4.ta = t4.tb = true;
+    GroupedGemm t5{at(L.dab), at(L.xpT), nullptr, dw_gate, nullptr, nullptr, counts, nullptr, E, H, d, Cp, 2 * H, d, H, GEMM_PLAIN, c.dtype};
+    t5.ta = t5.tb = true;
+    GroupedGemm t6 = t5;
+    t6.A = at(L.dab) + H; t6.C = dw_up;
+    const bool direct = grouped_gemm_transposed_ok(t2) && grouped_gemm_transposed_ok(t3) && grouped_gemm_transposed_ok(t4) &&
+                        grouped_gemm_transposed_ok(t5) && grouped_gemm_transposed_ok(t6);
+    int dxp_rows = C;
+    if (direct) {
+        ETR_BW(launch_grouped_gemm(t2, st));
+        hipLaunchKernelGGL((swiglu_backward_kernel<T, true>), dim3(cH, cC, E), dim3(kTileThreads), 0, st, at(L.u), pre_a, pre_b,
+                           gate_w, slot_token, counts, at(L.dab), static_cast<T*>(nullptr), static_cast<T*>(nullptr), at(L.hT),
+                           dgate_part, Tn, E, C, Cp, H);
+        const unsigned row_blocks = static_cast<unsigned>((static_cast<long long>(E) * Cp + 3) / 4);
+        hipLaunchKernelGGL((gather_rows_kernel<T, false>), dim3(row_blocks), dim3(256), 0, st, static_cast<const T*>(x),
+                           slot_token, counts, gate, at(L.xpT), Tn, d, E, C, Cp);
+        hipLaunchKernelGGL((gather_rows_kernel<T, true>), dim3(row_blocks), dim3(256), 0, st, static_cast<const T*>(dout),
+                           slot_token, counts, gate_w, at(L.dypT), Tn, d, E, C, Cp);
+        ETR_BW(hipGetLastError());
+        ETR_BW(launch_grouped_gemm(t3, st));
+        ETR_BW(launch_grouped_gemm(t4, st));
+        ETR_BW(launch_grouped_gemm(t5, st));
+        ETR_BW(launch_grouped_gemm(t6, st));
+        dxp_rows = Cp;
+    } else {
+        // Fallback (fp32, or shapes the transposing kernel does not take): every product on the "NT" kernel, with
+        // the weights transposed once per call and transposed copies of the per-row quantities.
+        // WdT[e][H][d], WguT[e][d][2H] = (Wg^T | Wu^T)
+        hipLaunchKernelGGL(transpose_kernel<T>, dim3(cH, cd, E), dim3(kTileThreads), 0, st, static_cast<const T*>(w_down),
+                           at(L.wdT), d, H, d, 0);
+        hipLaunchKernelGGL(transpose_kernel<T>, dim3(cd, cH, E), dim3(kTileThreads), 0, st, static_cast<const T*>(w_gate),
+                           at(L.wguT), H, d, 2 * H, 0);
+        hipLaunchKernelGGL(transpose_kernel<T>, dim3(cd, cH, E), dim3(kTileThreads), 0, st, static_cast<const T*>(w_up),
+                           at(L.wguT), H, d, 2 * H, H);
+        ETR_BW(hipGetLastError());
+        GroupedGemm g2{dout, at(L.wdT), nullptr, at(L.u), nullptr, counts, nullptr, slot_token, E, C, H, d, 0, 0, Tn, GEMM_PLAIN, c.dtype};
+        ETR_BW(launch_grouped_gemm(g2, st));
+        hipLaunchKernelGGL((swiglu_backward_kernel<T, false>), dim3(cH, cC, E), dim3(kTileThreads), 0, st, at(L.u), pre_a, pre_b,
+                           gate_w, slot_token, counts, at(L.dab), at(L.daT), at(L.dbT), at(L.hT), dgate_part, Tn, E, C, Cp, H);
+        hipLaunchKernelGGL((gather_transpose_kernel<T, false>), dim3(cd, cC, E), dim3(kTileThreads), 0, st,
+                           static_cast<const T*>(x), slot_token, counts, gate, at(L.xpT), Tn, d, E, C, Cp);
+        hipLaunchKernelGGL((gather_transpose_kernel<T, true>), dim3(cd, cC, E), dim3(kTileThreads), 0, st,
+                           static_cast<const T*>(dout), slot_token, counts, gate_w, at(L.dypT), Tn, d, E, C, Cp);
+        ETR_BW(hipGetLastError());
+        // dXp = (da | db) (Wg^T | Wu^T)^T
+        GroupedGemm g3{at(L.dab), at(L.wguT), nullptr, at(L.dxp), nullptr, counts, nullptr, nullptr, E, C, d, 2 * H, 0, 0, C, GEMM_PLAIN, c.dtype};
+        ETR_BW(launch_grouped_gemm(g3, st));
+        // weight gradients: contraction over the kept rows of each expert
+        GroupedGemm g4{at(L.dypT), at(L.hT), nullptr, dw_down, nullptr, nullptr, counts, nullptr, E, d, H, Cp, Cp, Cp, d, GEMM_PLAIN, c.dtype};
+        ETR_BW(launch_grouped_gemm(g4, st));
+        GroupedGemm g5{at(L.daT), at(L.xpT), nullptr, dw_gate, nullptr, nullptr, counts, nullptr, E, H, d, Cp, Cp, Cp, H, GEMM_PLAIN, c.dtype};
+        ETR_BW(launch_grouped_gemm(g5, st));
+        GroupedGemm g6{at(L.dbT), at(L.xpT), nullptr, dw_up, nullptr, nullptr, counts, nullptr, E, H, d, Cp, Cp, Cp, H, GEMM_PLAIN, c.dtype};
+        ETR_BW(launch_grouped_gemm(g6, st));
+    }
     const int P = d / c.D;
     const size_t lds = (static_cast<size_t>(E) * P + E + 4 * (2 * P + 2 * E)) * 4;
     auto kern = dx_kernel<T>;
@@ -431,8 +519,8 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
         ETR_BW(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                    static_cast<int>(lds)));
     hipLaunchKernelGGL(kern, dim3((Tn + 3) / 4), dim3(256), lds, st, static_cast<const T*>(x), w_emb, score, gate, slot_of,
-                       reinterpret_cast<const float*>(base + L.dgate_part), static_cast<int>(cH), at(L.dxp), static_cast<T*>(dx), dgate, dscore,
-                       Tn, d, E, c.D, C, static_cast<int>(c.cos), static_cast<int>(c.gate_norm));
+                       dgate_part, static_cast<int>(cH), at(L.dxp), static_cast<T*>(dx), dgate, dscore,
+                       Tn, d, E, c.D, C, static_cast<int>(c.cos), static_cast<int>(c.gate_norm), dxp_rows);
 #undef ETR_BW
     return hipGetLastError();
 }

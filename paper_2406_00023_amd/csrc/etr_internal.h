@@ -70,8 +70,13 @@ struct GroupedGemm {
     int G, M, N, K, lda, ldb, a_rows;
     int epilogue;
     int dtype;
+    // Operands with the contraction index slow (bf16, plain epilogue only; see grouped_gemm_transposed_ok):
+    // ta: A is [G][K][lda] holding A[g][m][k] at (k, m); tb: B0 is [G][K][ldb] holding B[g][n][k] at (k, n).
+    // With tb and B1 the contraction is split in the middle: B0 and B1 are [G][K/2][ldb] each.
+    bool ta = false, tb = false;
 };
 hipError_t launch_grouped_gemm(const GroupedGemm& g, hipStream_t st);
+bool grouped_gemm_transposed_ok(const GroupedGemm& g);
 
 // backward.hip
 size_t backward_ws_bytes(const etr_config& c);

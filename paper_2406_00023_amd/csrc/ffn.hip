@@ -621,8 +621,18 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
 // ---------------------------------------------------------------------------------------
 constexpr int kMaxSuper = 4096;          // super-tiles the LDS prefix can hold (16 KiB)
 
-template <bool GLU, bool DUAL = false>
+//
+// Operands whose contraction index is the slow one (TRA: A is [K][M], TRB: B is [K][N], row strides lda / ldb,
+// group stride K * ld; with TRB and B1 the contraction is split in the middle: first half from B0, second half
+// from B1, each [K/2][N]).  Such a tile is staged in LDS as [block of 32 rows][32 k][32 rows] (64 bytes per k) and
+// the MFMA fragments come out through the transposing read ds_read_b64_tr_b16: inside a group of 16 lanes, lane i
+// supplies the address of 4 consecutive elements and receives element i % 4 of lanes i/4, i/4 + 4, i/4 + 8,
+// i/4 + 12.  With lane (q = i % 4, j = i / 4) pointing at (k0 + j, r0 + 4 q) lane i receives rows r0 + i at
+// k0 .. k0 + 3: two reads give the 8 consecutive k of one row that the MFMA operand layout wants.  The four k of a
+// group are 64 bytes apart, so 32 lanes cover all 64 banks once: conflict-free without a swizzle.
+template <bool GLU, bool DUAL = false, bool TRA = false, bool TRB = false>
 __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
+    static_assert(!(GLU && TRB), "the transposed B operand is for plain products");
     constexpr int BM = 256, BR = 256, CPR = 4, NBUF = 4, AHEAD = NBUF - 1;
     constexpr int BN = GLU ? 128 : 256;
     constexpr int STAGE = (BM + BR) * CPR;
@@ -637,6 +647,10 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
     const int wm = wave / WN, wn = wave % WN;
     const int r32 = lane & 31, half = lane >> 5;
     const int KCA = (p.lda ? p.lda : p.K) / 8, KCB = (p.ldb ? p.ldb : p.K) / 8;
+    // bytes from one k-tile of an operand to the next
+    const size_t stepA = TRA ? static_cast<size_t>(32) * KCA * 16 : CPR * 16;
+    const size_t stepB = TRB ? static_cast<size_t>(32) * KCB * 16 : CPR * 16;
+    const bool splitB = TRB && p.B1 != nullptr;
 
     // ---- exclusive prefix of the number of live tiles per super-tile
     const int MG = (p.MT + p.SM - 1) / p.SM, NG = (p.NT + p.SN - 1) / p.SN;
@@ -685,7 +699,16 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
         int e, m0, n0, count, KT;
         const char* Abase;
         const char* Bbase;
+        const char* Bbase1;                              // second half of a split transposed B
         uint32_t off[2 * NCP];
+    };
+    // per-lane byte offset inside a k-tile of a [K][rows] operand.  Copy unit u = (block of 32 rows, half of the 32 k):
+    // 16 k x 64 bytes, four lanes per k, the access shape of the row-major copies (64-byte pieces of 16 memory rows)
+    auto kmajor_off = [&](int u, int r0, int limit, int kc) -> uint32_t {
+        const int krow = (u & 1) * 16 + (lane >> 2);
+        int r = r0 + (u >> 1) * 32 + (lane & 3) * 8;
+        r = r + 8 <= limit ? r : limit - 8;              // stay inside the row; such columns are never stored
+        return (static_cast<uint32_t>(krow) * kc * 8 + r) * 2u;
     };
     // the tile with list index q (q < total)
     auto setup = [&](int q, Tile& t) {
@@ -703,25 +726,48 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
         t.e = e; t.m0 = mt * BM; t.n0 = nt * BN;
         t.count = group_rows(p, e);
         t.KT = group_k(p, e) / 32;
-        t.Abase = reinterpret_cast<const char*>(p.A) + (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KCA * 16);
-        t.Bbase = reinterpret_cast<const char*>((GLU && wave >= NW / 2) ? p.B1 : p.B0) + static_cast<size_t>(e) * p.N * KCB * 16;
+        if constexpr (TRA) t.Abase = reinterpret_cast<const char*>(p.A) + static_cast<size_t>(e) * p.K * KCA * 16;
+        else t.Abase = reinterpret_cast<const char*>(p.A) + (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KCA * 16);
+        if constexpr (TRB) {
+            const size_t per_group = static_cast<size_t>(splitB ? p.K / 2 : p.K) * KCB * 16;
+            t.Bbase = reinterpret_cast<const char*>(p.B0) + e * per_group;
+            t.Bbase1 = splitB ? reinterpret_cast<const char*>(p.B1) + e * per_group : t.Bbase;
+        } else {
+            t.Bbase = reinterpret_cast<const char*>((GLU && wave >= NW / 2) ? p.B1 : p.B0) + static_cast<size_t>(e) * p.N * KCB * 16;
+            t.Bbase1 = t.Bbase;
+        }
 #pragma unroll
         for (int i = 0; i < NCP; ++i) {
             const int rr = (wave * NCP + i) * 16 + (lane >> 2);
             const int c = (lane & 3) ^ ((rr >> 2) & 3);
-            int m = t.m0 + rr;
-            m = m < t.count ? m : t.count - 1;
-            const int row = p.row_index ? min(max(p.row_index[static_cast<size_t>(e) * p.capacity + m], 0), p.a_rows - 1) : m;
-            t.off[i] = (static_cast<uint32_t>(row) * KCA + c) * 16u;
-            int n = t.n0 + (GLU ? (rr & 127) : rr);
-            n = n < p.N ? n : p.N - 1;
-            t.off[NCP + i] = (static_cast<uint32_t>(n) * KCB + c) * 16u;
+            if constexpr (TRA) {
+                t.off[i] = kmajor_off(wave * NCP + i, t.m0, p.capacity, KCA);
+            } else {
+                int m = t.m0 + rr;
+                m = m < t.count ? m : t.count - 1;
+                const int row = p.row_index ? min(max(p.row_index[static_cast<size_t>(e) * p.capacity + m], 0), p.a_rows - 1) : m;
+                t.off[i] = (static_cast<uint32_t>(row) * KCA + c) * 16u;
+            }
+            if constexpr (TRB) {
+                t.off[NCP + i] = kmajor_off(wave * NCP + i, t.n0, p.N, KCB);
+            } else {
+                int n = t.n0 + (GLU ? (rr & 127) : rr);
+                n = n < p.N ? n : p.N - 1;
+                t.off[NCP + i] = (static_cast<uint32_t>(n) * KCB + c) * 16u;
+            }
         }
+    };
+    // address of k-tile k of the B operand (wave-uniform); all arguments by value, so that the tile records stay in
+    // registers
+    auto b_ktile = [&](const char* b0, const char* b1, int kt_count, int k) -> uint64_t {
+        const bool second = splitB && k >= (kt_count >> 1);
+        const int kk = second ? k - (kt_count >> 1) : k;
+        return reinterpret_cast<uint64_t>(second ? b1 : b0) + kk * stepB;
     };
     // copy j (0..NCP-1: A row groups, NCP..2NCP-1: B row groups) of k-tile k of tile t into the ring slot of step g
     auto issue_copy = [&](const Tile& t, int k, int g, int j) {
         uint4* dst = lds + (g & (NBUF - 1)) * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
-        const uint64_t b64 = reinterpret_cast<uint64_t>(j < NCP ? t.Abase : t.Bbase) + static_cast<uint64_t>(k) * (CPR * 16);
+        const uint64_t b64 = j < NCP ? reinterpret_cast<uint64_t>(t.Abase) + k * stepA : b_ktile(t.Bbase, t.Bbase1, t.KT, k);
         const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
         const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
         const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
@@ -738,15 +784,52 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
         b_row[j] = BM * CPR + (br + r32) * CPR;
     }
     const int ck0 = half ^ sw, ck1 = (2 + half) ^ sw;
+    // transposing reads: byte offset, inside the operand's part of a ring slot, of this lane's 4 elements for the
+    // 32-row fragment that starts at row rf (first k-substep, first half of its 8 k)
+    auto tr_off = [&](int rf) -> uint32_t {
+        const int r = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);           // inside the block of 32 rows
+        const int kb = 8 * (lane >> 5) + ((lane & 15) >> 2);
+        return static_cast<uint32_t>((rf >> 5) * 2048 + kb * 64 + r * 2);
+    };
+    uint32_t a_tr[4], b_tr[TB];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a_tr[i] = tr_off(wm * 128 + i * 32);
+#pragma unroll
+    for (int j = 0; j < TB; ++j) b_tr[j] = BM * CPR * 16 + tr_off(wn * (32 * TB) + j * 32);
+    // The reads are written as assembly: through the compiler's builtin every such read waits for ALL outstanding
+    // copies (vmcnt(0)), because it is taken to alias the asynchronous LDS writes.  The hardware counter is not
+    // tracked for assembly, so the loops below wait (lgkmcnt(0)) themselves before the fragments are used.
+    typedef int v2i __attribute__((ext_vector_type(2)));
+    typedef int v4i __attribute__((ext_vector_type(4)));
+    const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)lds_raw));
+    auto tr_frag = [&](uint32_t byte) -> bf16x8 {          // k .. k+3 and k+4 .. k+7 of one row
+        const uint32_t addr = lds_base + byte;
+        v2i x0, x1;
+        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(x0) : "v"(addr));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:256" : "=v"(x1) : "v"(addr));
+        const v4i r = {x0.x, x0.y, x1.x, x1.y};
+        return __builtin_bit_cast(bf16x8, r);
+    };
+    auto tr_wait = [&]() {                                 // fragments read through tr_frag have arrived
+        if constexpr (TRA || TRB) __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0)
+    };
 
     f32x16 acc[4][TB];
     bf16x8 fa[2][4], fb[2][TB];
+    // set = k-substep (0: k 0..15 of the tile, 1: k 16..31); ck is the swizzled chunk of the row-major layout
     auto load_frags = [&](int set, int g, int ck) {
         const uint4* base = lds + (g & (NBUF - 1)) * STAGE + ck;
+        const uint32_t slot = static_cast<uint32_t>(g & (NBUF - 1)) * (STAGE * 16) + set * 1024;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
+        for (int i = 0; i < 4; ++i) {
+            if constexpr (TRA) fa[set][i] = tr_frag(slot + a_tr[i]);
+            else fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
+        }
 #pragma unroll
-        for (int j = 0; j < TB; ++j) fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
+        for (int j = 0; j < TB; ++j) {
+            if constexpr (TRB) fb[set][j] = tr_frag(slot + b_tr[j]);
+            else fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
+        }
     };
 
     int q = xcd * GS + slot_l;                           // first pass over the list
@@ -779,19 +862,23 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
         for (; kt < kt_fetch; ++kt, ++g) {
             const bool in_cur = kt + AHEAD < KT;
             const int kf = in_cur ? kt + AHEAD : kt + AHEAD - KT;
-            const char* baseA = in_cur ? cur.Abase : nxt.Abase;
-            const char* baseB = in_cur ? cur.Bbase : nxt.Bbase;
+            const char* srcA = in_cur ? cur.Abase : nxt.Abase;
+            const char* srcB0 = in_cur ? cur.Bbase : nxt.Bbase;
+            const char* srcB1 = in_cur ? cur.Bbase1 : nxt.Bbase1;
+            const uint64_t baseA = reinterpret_cast<uint64_t>(srcA) + kf * stepA;
+            const uint64_t baseB = b_ktile(srcB0, srcB1, in_cur ? KT : nxt.KT, kf);
             uint32_t offs[2 * NCP];
 #pragma unroll
             for (int j = 0; j < 2 * NCP; ++j) offs[j] = in_cur ? cur.off[j] : nxt.off[j];
             auto copy = [&](int j) {
                 uint4* dst = lds + ((g + AHEAD) & (NBUF - 1)) * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
-                const uint64_t b64 = reinterpret_cast<uint64_t>(j < NCP ? baseA : baseB) + static_cast<uint64_t>(kf) * (CPR * 16);
+                const uint64_t b64 = j < NCP ? baseA : baseB;
                 const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
                 const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
                 const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
                 __builtin_amdgcn_global_load_lds((global_cptr)(base + offs[j]), (lds_ptr)dst, 16, 0, 0);
             };
+            tr_wait();                                               // the first substep's fragments (read one step ago)
             __builtin_amdgcn_sched_barrier(0);
             load_frags(1, g, ck1);
 #pragma unroll
@@ -816,6 +903,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
             }
         }
         for (; kt < KT; ++kt, ++g) {                                 // tail of this workgroup's last tile: nothing to fetch
+            tr_wait();
             __builtin_amdgcn_sched_barrier(0);
             load_frags(1, g, ck1);
 #pragma unroll
@@ -1009,11 +1097,11 @@ hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
 
 // Persistent ring kernel: needs every group's contraction length >= 96 (three k-tiles to prefetch)
 // and the super-tile prefix to fit in LDS.
-template <bool GLU, bool DUAL = false>
+template <bool GLU, bool DUAL = false, bool TRA = false, bool TRB = false>
 hipError_t launch_bf16_persist(GemmParams p, hipStream_t st, int n_cu) {
     constexpr size_t lds = 4ull * 512 * 32 * 2;
     plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_persist_kernel<GLU, DUAL>;
+    auto kern = gemm_bf16_persist_kernel<GLU, DUAL, TRA, TRB>;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (err != hipSuccess) return err;
@@ -1058,10 +1146,39 @@ static bool pipelined_ok(const GemmParams& g, size_t a_rows) {
 
 // General entry for the other stages of the library: grouped "NT" product
 //   C[g][m][n] = sum_k A[g][m][k] * B[g][n][k],  g < G, m < m_counts[g] (or M), k < k_counts[g] (or K).
-hipError_t launch_grouped_gemm(const GroupedGemm& q, hipStream_t st) {
+static GemmParams params_of(const GroupedGemm& q) {
     GemmParams g{q.A, q.B0, q.B1, q.C, q.m_counts, q.G, q.M, q.N, q.K, 0, 0, 0, 0, q.row_index, q.a_rows};
     g.lda = q.lda; g.ldb = q.ldb; g.k_counts = q.k_counts; g.C2 = q.C2;
+    return g;
+}
+
+// Operands stored with the contraction index slow run only on the persistent bf16 kernel.
+bool grouped_gemm_transposed_ok(const GroupedGemm& q) {
+    if (q.dtype != ETR_BF16 || q.epilogue != GEMM_PLAIN || !(q.ta || q.tb)) return false;
+    if (q.K < 128 || q.K % 64 != 0 || q.N % 4 != 0) return false;
+    if (q.tb && (q.N % 8 != 0 || q.N < 8)) return false;           // 16-byte chunks along the rows of a [K][rows] operand
+    if (q.ta && (q.M % 8 != 0 || q.M < 8)) return false;
+    const int lda = q.lda ? q.lda : q.K, ldb = q.ldb ? q.ldb : q.K;
+    if (lda % 8 != 0 || ldb % 8 != 0) return false;
+    if (q.ta && (q.row_index || q.m_counts)) return false;
+    if (q.B1 && !(q.tb && q.K % 128 == 0 && !q.k_counts)) return false;          // split B: two halves of whole k-tiles
+    // 32-bit per-lane offsets inside one k-tile / one operand
+    const size_t a_span = q.ta ? 32ull * lda * 2 : (q.row_index ? static_cast<size_t>(q.a_rows) : static_cast<size_t>(q.M)) * lda * 2;
+    const size_t b_span = q.tb ? 32ull * ldb * 2 : static_cast<size_t>(q.N) * ldb * 2;
+    if (a_span >= (1ull << 32) || b_span >= (1ull << 32)) return false;
+    return persist_ok(params_of(q), false);
+}
+
+hipError_t launch_grouped_gemm(const GroupedGemm& q, hipStream_t st) {
+    GemmParams g = params_of(q);
     if (q.N % 4 != 0 || q.K < 0 || q.G < 1 || q.M < 1) return hipErrorInvalidValue;
+    if (q.ta || q.tb) {
+        if (!grouped_gemm_transposed_ok(q)) return hipErrorInvalidValue;
+        const int n_cu = cu_count();
+        if (q.ta && q.tb) return launch_bf16_persist<false, false, true, true>(g, st, n_cu);
+        if (q.tb) return launch_bf16_persist<false, false, false, true>(g, st, n_cu);
+        return launch_bf16_persist<false, false, true, false>(g, st, n_cu);
+    }
     if (q.dtype == ETR_BF16) {
         if (q.K % 8 != 0 || (q.lda ? q.lda : q.K) % 8 != 0 || (q.ldb ? q.ldb : q.K) % 8 != 0) return hipErrorInvalidValue;
         const bool ring = pipelined_ok(g, q.row_index ? static_cast<size_t>(q.a_rows) : static_cast<size_t>(q.M));
