@@ -174,3 +174,38 @@ def test_training_forward_keeps_pre_activations(H, oracle, name):
     torch.cuda.synchronize()
     for got, want, nm in ((dx2, bw.dx, "dx"), (dwg2, bw.dwg, "dw_gate"), (dwu2, bw.dwu, "dw_up"), (dwd2, bw.dwd, "dw_down")):
         assert torch.equal(got, want), nm
+
+
+def test_backward_with_an_empty_and_a_one_row_expert(H, oracle):
+    """Hand-edited routing tables on the shape that takes the transposition-free path: one expert keeps nothing
+    (its weight gradients must be exact zeros), one keeps a single row."""
+    shape = SMALL["cfg2s"]()
+    _say("backward with edited tables (empty expert, one-row expert)")
+    bw = Backward(H, shape, shape.mode)
+    L, cfg, t = bw.L, bw.L.cfg, bw.L.t
+    slot_of, slot_token, counts = (H.to_np(v).copy() for v in (L.slot_of, L.slot_token, L.counts))
+    empty, single = 3, 5
+    slot_of[:, empty] = -1; slot_token[empty, :] = -1; counts[empty] = 0
+    keep = slot_token[single, 0]
+    slot_of[:, single] = -1; slot_of[keep, single] = 0
+    slot_token[single, :] = -1; slot_token[single, 0] = keep; counts[single] = 1
+    d_slot_of, d_slot_token, d_counts = (torch.from_numpy(v).cuda() for v in (slot_of, slot_token, counts))
+    ws = B.alloc_workspace(B.etr_backward_workspace_bytes(cfg))
+    ws.fill_(0xFF)
+    dgate = torch.empty_like(bw.dgate)
+    B.etr_moe_backward(cfg, t["x"], t["w_emb"], t["w_gate"], t["w_up"], t["w_down"], L.score, L.gate, d_slot_of, d_slot_token,
+                       d_counts, bw.dout, bw.dx, bw.dwg, bw.dwu, bw.dwd, ws, dgate=dgate)
+    torch.cuda.synchronize()
+    hx = bw.host()
+    ref = oracle.moe_backward(hx["x"], hx["w_emb"], hx["w_gate"], hx["w_up"], hx["w_down"], slot_of, hx["dout"],
+                              D=shape.D, dtype=shape.dtype)
+    tol = H.TOL_OUT[shape.dtype]
+    for got, key in ((bw.dx, "dx"), (bw.dwg, "dw_gate"), (bw.dwu, "dw_up"), (bw.dwd, "dw_down")):
+        assert _err(H, oracle, got, ref[key], shape.dtype) <= tol, key
+    assert H.scale_rel_err(H.to_np(dgate).astype(np.float64), ref["dgate"]) <= tol
+    for g in (bw.dwg, bw.dwu, bw.dwd):
+        assert not H.to_np(g)[empty].any()
+    # the one-row expert: its gradient is that row's outer product, compare on its own scale
+    for got, key in ((bw.dwg, "dw_gate"), (bw.dwd, "dw_down")):
+        a = oracle.to_f64(H.to_np(got)[single], shape.dtype)
+        assert H.scale_rel_err(a, ref[key][single]) <= tol, key
