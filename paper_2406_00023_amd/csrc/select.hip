@@ -401,7 +401,9 @@ hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_
     hipLaunchKernelGGL(expert_choice_kernel<II>, dim3(c.E), dim3(kSelThreads), 0, st, w.keyT, w.Tpad, c.T, w.ipt, \
                        c.capacity, c.mode, capacity_dev, sum_need, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts)
     if (w.ipt <= 4) ETR_EC(4);
+    else if (w.ipt <= 8) ETR_EC(8);
     else if (w.ipt <= 16) ETR_EC(16);
+    else if (w.ipt <= 32) ETR_EC(32);
     else if (w.ipt <= 64) ETR_EC(64);
     else ETR_EC(0);
 #undef ETR_EC
