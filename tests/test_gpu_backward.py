@@ -104,7 +104,7 @@ def test_backward_small_all_gradients(H, oracle, name, mode, cos):
         assert not H.to_np(bw.dwg)[e].any() and not H.to_np(bw.dwd)[e].any()
 
 
-@pytest.mark.parametrize("name", ["cfg2"])
+@pytest.mark.parametrize("name", ["cfg2", "cfg5"])
 def test_backward_full_size_sampled(H, oracle, name):
     shape = I.CONFIGS[name]
     _say(f"backward full size {name}")
