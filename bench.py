@@ -257,7 +257,7 @@ def main():
                                f"capacity={cfg.capacity} H={shape.H} mode={('TCR', 'ECR', 'BIDIR')[cfg.mode]} "
                                f"tokens={shape.recipe}",
                    "kept_rows": rows},
-        "roofline": {"kernel": "gemm_bf16_persist_kernel<GLU> (FFN gate/up projections + SwiGLU)"
+        "roofline": {"kernel": "gemm_bf16_persist64_kernel<GLU> (FFN gate/up projections + SwiGLU)"
                      if shape.dtype == I.DT_BF16 else "gemm_f32_kernel<GLU>",
                      "bound": "mfma" if shape.dtype == I.DT_BF16 else "alu",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,

@@ -972,6 +972,286 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Persistent kernel with 64-wide k-tiles for row-major operands: the same tile list and the same
+// run-on across tile boundaries as above, but every copy instruction fetches whole 128-byte lines
+// (8 rows x 128 bytes instead of 16 rows x 64 bytes).  Measured on a copy-only loop over L2-resident
+// data the line-sized pieces move 1.6 times the bytes per cycle of the half-line ones, and in the
+// ring kernel above the copies, not the matrix pipe, set the cycle count.
+//
+// Two LDS buffers of 64 KiB.  Step g multiplies buffer g & 1 in four k-substeps; after the third
+// substep's fragments are in registers nobody reads that buffer any more, so behind one wait
+// (all copies landed, all own LDS reads done) and one barrier the eight copies of step g + 2 are
+// issued into it, interleaved with the MFMAs of the fourth substep.  They have three quarters of a
+// step to land.  Past the end of a tile step g + 2 is the first or second k-tile of the next one.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int live_row_tiles(const GemmParams& p, int e, int mg, int BM) {
+    const int mtv = (group_rows(p, e) + BM - 1) / BM;
+    return min(max(mtv - mg * p.SM, 0), p.SM);
+}
+__device__ __forceinline__ int live_col_tiles(const GemmParams& p, int ng) { return min(p.NT - ng * p.SN, p.SN); }
+
+// pre[s] = number of live tiles in the super-tiles before s (s <= S = E * MG * NG), by 512 threads
+__device__ __forceinline__ void live_tile_prefix(const GemmParams& p, int BM, int MG, int NG, int* pre, int* wave_tot) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int S = p.E * MG * NG;
+    const int CH = (S + 511) / 512;
+    auto tiles_of = [&](int s) {
+        const int e = s / (MG * NG), r = s - e * (MG * NG);
+        return live_row_tiles(p, e, r % MG, BM) * live_col_tiles(p, r / MG);
+    };
+    int sum = 0;
+    for (int i = 0; i < CH; ++i) {
+        const int s = tid * CH + i;
+        if (s < S) sum += tiles_of(s);
+    }
+    int inc = sum;
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+        const int o = __shfl_up(inc, m, 64);
+        if (lane >= m) inc += o;
+    }
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    int run = inc - sum;
+    for (int w = 0; w < wave; ++w) run += wave_tot[w];
+    for (int i = 0; i < CH; ++i) {
+        const int s = tid * CH + i;
+        if (s < S) {
+            pre[s] = run;
+            run += tiles_of(s);
+        }
+    }
+    if (tid == 511) pre[S] = run;                        // thread 511 owns the last chunk (or nothing): run = total
+    __syncthreads();
+}
+
+template <bool GLU, bool DUAL = false>
+__global__ __launch_bounds__(512) void gemm_bf16_persist64_kernel(GemmParams p) {
+    constexpr int BM = 256, BR = 256, CPR = 8, SWZ = 1;
+    constexpr int BN = GLU ? 128 : 256;
+    constexpr int STAGE = (BM + BR) * CPR;               // uint4 per LDS buffer (64 KiB)
+    constexpr int WN = 4, NW = 8, TB = 2, NCP = 4;       // NCP: groups of 8 rows each wave copies per operand
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    uint4* lds = reinterpret_cast<uint4*>(lds_raw);
+    __shared__ int pre[kMaxSuper + 1];
+    __shared__ int wave_tot[NW];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int r32 = lane & 31, half = lane >> 5;
+    const int KCA = (p.lda ? p.lda : p.K) / 8, KCB = (p.ldb ? p.ldb : p.K) / 8;
+
+    const int MG = (p.MT + p.SM - 1) / p.SM, NG = (p.NT + p.SN - 1) / p.SN;
+    const int S = p.E * MG * NG;
+    live_tile_prefix(p, BM, MG, NG, pre, wave_tot);
+    const int total = pre[S];
+    const int GS = gridDim.x >> 3;                       // tiles per group = workgroups per XCD
+    const int xcd = blockIdx.x & 7, slot_l = blockIdx.x >> 3;
+
+    struct Tile {
+        int e, m0, n0, count, KT;
+        const char* Abase;
+        const char* Bbase;
+        uint32_t off[2 * NCP];
+    };
+    auto setup = [&](int q, Tile& t) {
+        int lo = 0, hi = S;                              // largest s with pre[s] <= q
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (pre[mid] <= q) lo = mid; else hi = mid;
+        }
+        const int s = __builtin_amdgcn_readfirstlane(lo);
+        const int u = __builtin_amdgcn_readfirstlane(q - pre[s]);
+        const int e = s / (MG * NG), r = s - e * (MG * NG);
+        const int mg = r % MG, ng = r / MG;
+        const int vm = live_row_tiles(p, e, mg, BM);
+        const int mt = mg * p.SM + u % vm, nt = ng * p.SN + u / vm;
+        t.e = e; t.m0 = mt * BM; t.n0 = nt * BN;
+        t.count = group_rows(p, e);
+        t.KT = group_k(p, e) / 64;
+        t.Abase = reinterpret_cast<const char*>(p.A) + (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KCA * 16);
+        t.Bbase = reinterpret_cast<const char*>((GLU && wave >= NW / 2) ? p.B1 : p.B0) + static_cast<size_t>(e) * p.N * KCB * 16;
+#pragma unroll
+        for (int i = 0; i < NCP; ++i) {
+            const int rr = (wave * NCP + i) * 8 + (lane >> 3);
+            const int c = (lane & 7) ^ ((rr >> SWZ) & 7);
+            int m = t.m0 + rr;
+            m = m < t.count ? m : t.count - 1;           // rows past the count replay a valid row; never stored
+            const int row = p.row_index ? min(max(p.row_index[static_cast<size_t>(e) * p.capacity + m], 0), p.a_rows - 1) : m;
+            t.off[i] = (static_cast<uint32_t>(row) * KCA + c) * 16u;
+            int n = t.n0 + (GLU ? (rr & 127) : rr);
+            n = n < p.N ? n : p.N - 1;
+            t.off[NCP + i] = (static_cast<uint32_t>(n) * KCB + c) * 16u;
+        }
+    };
+    // copy j (0..NCP-1: A row groups, NCP..2NCP-1: B row groups) of the k-tile at abase / bbase into buffer buf
+    auto issue_copy = [&](uint64_t abase, uint64_t bbase, uint32_t off, int buf, int j) {
+        uint4* dst = lds + buf * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
+        const uint64_t b64 = j < NCP ? abase : bbase;
+        const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
+        const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
+        const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+        __builtin_amdgcn_global_load_lds((global_cptr)(base + off), (lds_ptr)dst, 16, 0, 0);
+    };
+
+    const int sw = (r32 >> SWZ) & 7;
+    int a_row[4], b_row[TB];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a_row[i] = (wm * 128 + i * 32 + r32) * CPR;
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+        const int br = GLU ? ((j / (TB / 2)) * 128 + wn * (16 * TB) + (j % (TB / 2)) * 32) : (wn * (32 * TB) + j * 32);
+        b_row[j] = BM * CPR + (br + r32) * CPR;
+    }
+    int ck[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) ck[ks] = (ks * 2 + half) ^ sw;
+
+    f32x16 acc[4][TB];
+    bf16x8 fa[2][4], fb[2][TB];
+    auto load_frags = [&](int set, int buf, int ks) {
+        const uint4* base = lds + buf * STAGE + ck[ks];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
+#pragma unroll
+        for (int j = 0; j < TB; ++j) fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
+    };
+    auto mfma_block = [&](int set) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < TB; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
+    };
+
+    int q = xcd * GS + slot_l;                           // first pass over the list
+    if (q >= total) return;                              // uniform: nothing for this workgroup
+    Tile cur, nxt;
+    setup(q, cur);
+    int g = 0;                                           // global step: buffer g & 1
+    for (int t = 0; t < 2; ++t)                          // KT >= 2 is a launch condition
+#pragma unroll
+        for (int j = 0; j < 2 * NCP; ++j)
+            issue_copy(reinterpret_cast<uint64_t>(cur.Abase) + t * 128, reinterpret_cast<uint64_t>(cur.Bbase) + t * 128, cur.off[j], t, j);
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * NCP, false));             // the first k-tile (copies retire in order)
+    __builtin_amdgcn_s_barrier();
+    load_frags(0, 0, 0);
+
+    for (;;) {
+        const int qn = q + 8 * GS;                       // same XCD, next round
+        const bool has_next = qn < total;
+        if (has_next) setup(qn, nxt);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < TB; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        const int KT = cur.KT;
+        // Fetching part: k-tile kt + 2, which past KT is a k-tile of the next tile; the source is chosen with
+        // selects outside the unrolled MFMA sequences, which carry no branches.
+        const int kt_fetch = has_next ? KT : KT - 2;
+        int kt = 0;
+        for (; kt < kt_fetch; ++kt, ++g) {
+            const bool in_cur = kt + 2 < KT;
+            const int kf = in_cur ? kt + 2 : kt + 2 - KT;
+            const uint64_t baseA = reinterpret_cast<uint64_t>(in_cur ? cur.Abase : nxt.Abase) + kf * 128;
+            const uint64_t baseB = reinterpret_cast<uint64_t>(in_cur ? cur.Bbase : nxt.Bbase) + kf * 128;
+            uint32_t offs[2 * NCP];
+#pragma unroll
+            for (int j = 0; j < 2 * NCP; ++j) offs[j] = in_cur ? cur.off[j] : nxt.off[j];
+            const int buf = g & 1;
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(1, buf, 1);
+            mfma_block(0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(0, buf, 2);
+            mfma_block(1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(1, buf, 3);
+            mfma_block(0);
+            __builtin_amdgcn_sched_barrier(0);
+            // k-tile g + 1 has landed and this wave's reads of buffer buf are done; past the barrier that holds for all
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(0, buf ^ 1, 0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int j = 0; j < TB; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][j], fa[1][i], acc[i][j], 0, 0, 0);
+                    issue_copy(baseA, baseB, offs[i * TB + j], buf, i * TB + j);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        for (; kt < KT; ++kt, ++g) {                     // the last two steps of this workgroup's last tile: nothing to fetch
+            const int buf = g & 1;
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(1, buf, 1);
+            mfma_block(0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(0, buf, 2);
+            mfma_block(1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(1, buf, 3);
+            mfma_block(0);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            if (kt + 1 < KT) load_frags(0, buf ^ 1, 0);
+            mfma_block(1);
+        }
+        // ---- epilogue of cur (the copies of the next tile are in flight)
+        uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(cur.e) * p.capacity * p.N;
+        uint16_t* C2g = DUAL ? reinterpret_cast<uint16_t*>(p.C2) + static_cast<size_t>(cur.e) * p.capacity * p.N : nullptr;
+        constexpr int TO = GLU ? TB / 2 : TB;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int m = cur.m0 + wm * 128 + i * 32 + r32;
+            if (m >= cur.count) continue;
+#pragma unroll
+            for (int j = 0; j < TO; ++j)
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                    const int n = cur.n0 + wn * (32 * TO) + j * 32 + qq * 8 + half * 4;
+                    if (n >= p.N) continue;
+                    float o[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        if constexpr (GLU && !DUAL) o[v] = silu(acc[i][j][qq * 4 + v]) * acc[i][TO + j][qq * 4 + v];
+                        else o[v] = acc[i][j][qq * 4 + v];
+                    }
+                    uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
+                    *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
+                    if constexpr (GLU && DUAL) {
+                        const f32x16& u2 = acc[i][TB - TO + j];
+                        pk = make_uint2(f2bf(u2[qq * 4]) | (f2bf(u2[qq * 4 + 1]) << 16), f2bf(u2[qq * 4 + 2]) | (f2bf(u2[qq * 4 + 3]) << 16));
+                        *reinterpret_cast<uint2*>(C2g + static_cast<size_t>(m) * p.N + n) = pk;
+                    }
+                    if constexpr (GLU && !DUAL) {
+                        if (p.C3) {                                 // keep the pre-activations (training-mode forward)
+                            const size_t o3 = (static_cast<size_t>(cur.e) * p.capacity + m) * p.N + n;
+                            const f32x16& g0 = acc[i][j];
+                            const f32x16& g1 = acc[i][TO + j];
+                            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C2) + o3) =
+                                make_uint2(f2bf(g0[qq * 4]) | (f2bf(g0[qq * 4 + 1]) << 16), f2bf(g0[qq * 4 + 2]) | (f2bf(g0[qq * 4 + 3]) << 16));
+                            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C3) + o3) =
+                                make_uint2(f2bf(g1[qq * 4]) | (f2bf(g1[qq * 4 + 1]) << 16), f2bf(g1[qq * 4 + 2]) | (f2bf(g1[qq * 4 + 3]) << 16));
+                        }
+                    }
+                }
+        }
+        if (!has_next) break;
+        cur = nxt;
+        q = qn;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // fp32 grouped GEMM, 64x64 tile, 4x4 outputs per thread, plain FMA
 // ---------------------------------------------------------------------------------------
 template <bool GLU, bool DUAL = false>
@@ -1108,6 +1388,17 @@ hipError_t launch_bf16_persist(GemmParams p, hipStream_t st, int n_cu) {
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(512), lds, st, p);
     return hipGetLastError();
 }
+template <bool GLU, bool DUAL = false>
+hipError_t launch_bf16_persist64(GemmParams p, hipStream_t st, int n_cu) {
+    constexpr size_t lds = 2ull * 512 * 64 * 2;                             // two buffers of 256 + 256 rows x 64 bf16
+    plan_tiles(p, 256, GLU ? 128 : 256);
+    auto kern = gemm_bf16_persist64_kernel<GLU, DUAL>;
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(512), lds, st, p);
+    return hipGetLastError();
+}
 inline bool persist_ok(const GemmParams& g, bool glu) {
     GemmParams t = g;
     plan_tiles(t, 256, glu ? 128 : 256);
@@ -1185,9 +1476,9 @@ hipError_t launch_grouped_gemm(const GroupedGemm& q, hipStream_t st) {
         if (ring && persist_ok(g, q.epilogue != GEMM_PLAIN)) {
             const int n_cu = cu_count();
             switch (q.epilogue) {
-                case GEMM_PLAIN: return launch_bf16_persist<false>(g, st, n_cu);
-                case GEMM_SWIGLU: return launch_bf16_persist<true>(g, st, n_cu);
-                case GEMM_DUAL: return launch_bf16_persist<true, true>(g, st, n_cu);
+                case GEMM_PLAIN: return launch_bf16_persist64<false>(g, st, n_cu);
+                case GEMM_SWIGLU: return launch_bf16_persist64<true>(g, st, n_cu);
+                case GEMM_DUAL: return launch_bf16_persist64<true, true>(g, st, n_cu);
             }
         }
         switch (q.epilogue) {
@@ -1225,7 +1516,7 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
         if (gather_rows && !ffn_can_gather(c)) return hipErrorInvalidValue;
         const bool pipe1 = pipelined_ok(g1, gather_rows ? static_cast<size_t>(c.T) : static_cast<size_t>(c.capacity));
         const int n_cu = cu_count();
-        if (pipe1 && persist_ok(g1, true)) err = launch_bf16_persist<true>(g1, st, n_cu);
+        if (pipe1 && persist_ok(g1, true)) err = launch_bf16_persist64<true>(g1, st, n_cu);
         else err = (pipe1 && !g1.C3) ? launch_bf16_ring<true, 4>(g1, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g1, st);
         if (err != hipSuccess) return err;
         if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
@@ -1234,7 +1525,7 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
         // two-stage kernel with 64-wide k-tiles is the faster one per tile; otherwise the persistent kernel
         // wins through its overlap of tile boundaries and its even split of the live tiles.
         const long long tiles = static_cast<long long>(c.E) * ((c.capacity + 255) / 256) * ((c.d + 255) / 256);
-        if (persist_ok(g2, false) && tiles > 2ll * n_cu) return launch_bf16_persist<false>(g2, st, n_cu);
+        if (persist_ok(g2, false) && tiles > 2ll * n_cu) return launch_bf16_persist64<false>(g2, st, n_cu);
         return launch_bf16_pipe<false, 1, 4>(g2, st);
     }
     if (gather_rows) return hipErrorInvalidValue;
