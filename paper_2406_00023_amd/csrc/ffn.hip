@@ -1521,11 +1521,7 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
         if (err != hipSuccess) return err;
         if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
         if (!pipelined_ok(g2, c.capacity)) return launch_bf16<128, 128, 64, 2, 2, false, 1>(g2, st);
-        // With at most two tiles per CU the makespan is two tile times whatever the schedule, and the
-        // two-stage kernel with 64-wide k-tiles is the faster one per tile; otherwise the persistent kernel
-        // wins through its overlap of tile boundaries and its even split of the live tiles.
-        const long long tiles = static_cast<long long>(c.E) * ((c.capacity + 255) / 256) * ((c.d + 255) / 256);
-        if (persist_ok(g2, false) && tiles > 2ll * n_cu) return launch_bf16_persist64<false>(g2, st, n_cu);
+        if (persist_ok(g2, false)) return launch_bf16_persist64<false>(g2, st, n_cu);
         return launch_bf16_pipe<false, 1, 4>(g2, st);
     }
     if (gather_rows) return hipErrorInvalidValue;
