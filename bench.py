@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel (FFN gate/up GEMM), measured with rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE on this very command and scaled by what a plain 1 GiB copy reads on the same counters (fetch x2.0,
 # write x1.0); the summaries are profiles/moe_forward_<cfg>_kernels_and_traffic.txt. None = not measured.
-MEASURED_TRAFFIC_BYTES = {"cfg2": 1035.2e6 + 136.6e6, "cfg5": 12754.1e6 + 723.0e6}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 1034.2e6 + 136.6e6, "cfg5": 13652.0e6 + 719.5e6}
 
 
 def _to_np(t):
