@@ -171,6 +171,10 @@ def test_select_external_scores(H, oracle, T, E, k, C, levels):
     (I.DT_BF16, 2, 40, 64, 64, [40, 7]),               # pipelined kernels with only two k-tiles
     (I.DT_BF16, 1, 300, 128, 192, [300]),              # four and six k-tiles: prologue meets drain
     (I.DT_BF16, 3, 600, 2048, 512, [600, 256, 257]),   # counts on and just past a row-tile boundary
+    # more live tiles than CUs with only two k-tiles: every persistent workgroup runs on from one tile into the next
+    # while it is still inside the first tile's prologue (GEMM-1 in the first case, GEMM-2 in the second)
+    (I.DT_BF16, 8, 2048, 128, 1024, [2048, 1500, 2048, 300, 2047, 1025, 2048, 1800]),
+    (I.DT_BF16, 8, 2048, 2048, 128, [2048, 1500, 0, 300, 2047, 1025, 2048, 1800]),
 ])
 def test_expert_ffn(H, oracle, dtype, E, C, d, H_, counts):
     _say(f"case ffn dtype={dtype} E={E} C={C} d={d} H={H_} counts={counts}")
