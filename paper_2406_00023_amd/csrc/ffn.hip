@@ -255,187 +255,23 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
     }
 }
 
-// ---------------------------------------------------------------------------------------
-// Pipelined bf16 MFMA grouped GEMM for K % 64 == 0: 256 x 256 staged rows, BK = 64, four
-// waves (one per SIMD), each owning a 128 x 128 slice of accumulators (256 registers).
-//   * global -> LDS copies bypass the registers (global_load_lds_dwordx4): a wave-load
-//     fills 1 KiB = 8 tile rows; the XOR swizzle is applied on the source side (lane l
-//     fetches the chunk that belongs in LDS slot l), two LDS buffers of 64 KiB;
-//   * the copy of tile kt+2 is issued right after the barrier that retires tile kt, so
-//     it has a whole iteration (64 MFMAs per wave) to land;
-//   * MFMA operands are double-buffered in registers: the ds_reads of k-substep s+1 are
-//     issued before the 16 MFMAs of substep s;
-//   * one barrier per iteration.
-// With GLU the 256 staged weight rows are 128 gate rows + 128 up rows of the same output
-// columns and the epilogue is SiLU(gate)*up.  With row_index the A rows are gathered
-// straight from the token matrix (dispatch folded into the load).
-// ---------------------------------------------------------------------------------------
-// Workgroup barrier that the compiler may not move memory accesses across (no instructions of its own
-// besides s_barrier; the waits that make data visible are written out next to each use).
-__device__ __forceinline__ void wg_barrier() {
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
 typedef const __attribute__((address_space(1))) void* global_cptr;
 typedef __attribute__((address_space(3))) void* lds_ptr;
 
-template <bool GLU, int SWZ, int WN = 2>
-__global__ __launch_bounds__(128 * WN) void gemm_bf16_pipe_kernel(GemmParams p) {
-    constexpr int BM = 256, BR = 256, CPR = 8;
-    constexpr int NW = 2 * WN;                          // waves: 2 row groups x WN column groups
-    constexpr int TB = 4 / (WN / 2);                    // weight fragments per wave and k-substep (4 or 2)
-    constexpr int NCP = 32 / NW;                        // row groups (of 8 rows) each wave copies per operand
-    constexpr int BN = GLU ? 128 : 256;                 // output columns per tile
-    constexpr int STAGE = (BM + BR) * CPR;              // uint4 per LDS buffer (64 KiB)
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    uint4* lds = reinterpret_cast<uint4*>(lds_raw);
-
-    int e, mt, nt;
-    if (!decode_tile(p, e, mt, nt)) return;
-    const int count = min(p.counts[e], p.capacity);
-    const int m0 = mt * BM, n0 = nt * BN;
-    if (m0 >= count) return;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
-    const int r32 = lane & 31, half = lane >> 5;
-    const int KC = p.K / 8, KT = p.K / 64;
-
-    // ---- sources of the asynchronous copies: wave w fills row groups w*NCP .. w*NCP+NCP-1 (8 rows each)
-    const uint4* Abase = reinterpret_cast<const uint4*>(p.A) +
-                         (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KC);
-    const uint4* Bbase = reinterpret_cast<const uint4*>((GLU && wave >= NW / 2) ? p.B1 : p.B0) +
-                         static_cast<size_t>(e) * p.N * KC;
-    uint32_t a_off[NCP], b_off[NCP];
-#pragma unroll
-    for (int i = 0; i < NCP; ++i) {
-        const int r = (wave * NCP + i) * 8 + (lane >> 3);
-        const int c = (lane & 7) ^ ((r >> SWZ) & 7);
-        int m = m0 + r;
-        m = m < count ? m : count - 1;                   // rows past the count replay a valid row; never stored
-        const int row = p.row_index ? min(max(p.row_index[static_cast<size_t>(e) * p.capacity + m], 0), p.a_rows - 1) : m;
-        a_off[i] = static_cast<uint32_t>(row) * KC + c;
-        int n = n0 + (GLU ? (r & 127) : r);
-        n = n < p.N ? n : p.N - 1;
-        b_off[i] = static_cast<uint32_t>(n) * KC + c;
-    }
-    auto issue_copies = [&](int kt, int buf) {
-        uint4* dstA = lds + buf * STAGE + wave * (NCP * 64);
-        uint4* dstB = dstA + BM * CPR;
-#pragma unroll
-        for (int i = 0; i < NCP; ++i) {
-            __builtin_amdgcn_global_load_lds((global_cptr)(Abase + a_off[i] + kt * CPR), (lds_ptr)(dstA + i * 64), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((global_cptr)(Bbase + b_off[i] + kt * CPR), (lds_ptr)(dstB + i * 64), 16, 0, 0);
-        }
-    };
-
-    // ---- MFMA operand addressing: row offsets are multiples of 32, so the swizzle term
-    // depends on the lane only
-    const int sw = (r32 >> SWZ) & 7;
-    int a_row[4], b_row[TB];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a_row[i] = (wm * 128 + i * 32 + r32) * CPR;
-#pragma unroll
-    for (int j = 0; j < TB; ++j) {
-        // GLU: first half of the fragments are gate rows, second half the up rows of the same columns
-        const int br = GLU ? ((j / (TB / 2)) * 128 + wn * (16 * TB) + (j % (TB / 2)) * 32) : (wn * (32 * TB) + j * 32);
-        b_row[j] = BM * CPR + (br + r32) * CPR;
-    }
-    int ck[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) ck[ks] = (ks * 2 + half) ^ sw;
-
-    f32x16 acc[4][TB];                                  // [m block][weight block]
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < TB; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    bf16x8 fa[2][4], fb[2][TB];
-    auto load_frags = [&](int set, int buf, int ks) {
-        const uint4* base = lds + buf * STAGE + ck[ks];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
-#pragma unroll
-        for (int j = 0; j < TB; ++j) fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
-    };
-    auto mfma_step = [&](int set) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < TB; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
-    };
-
-    // ---- prologue: tiles 0 and 1 in flight, wait for tile 0 only (copies retire in order)
-    issue_copies(0, 0);
-    if (KT > 1) {
-        issue_copies(1, 1);
-        if constexpr (NCP == 8) __builtin_amdgcn_s_waitcnt(0x4F70);   // vmcnt(16)
-        else __builtin_amdgcn_s_waitcnt(0x0F78);                      // vmcnt(8)
-    } else {
-        __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0)
-    }
-    __builtin_amdgcn_s_barrier();
-    load_frags(0, 0, 0);
-
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags(1, cur, 1);
-        mfma_step(0);
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags(0, cur, 2);
-        mfma_step(1);
-        __builtin_amdgcn_sched_barrier(0);
-        load_frags(1, cur, 3);
-        mfma_step(0);
-        __builtin_amdgcn_sched_barrier(0);
-        // tile kt+1 has landed for every wave and nobody reads buffer `cur` any more
-        __builtin_amdgcn_s_waitcnt(0x0070);             // vmcnt(0) lgkmcnt(0)
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        if (kt + 2 < KT) issue_copies(kt + 2, cur);
-        if (kt + 1 < KT) load_frags(0, cur ^ 1, 0);
-        mfma_step(1);
-    }
-
-    // ---- epilogue: lane holds, per 32x32 block, row m = lane%32 and columns (v/4)*8 + (lane/32)*4 + v%4
-    uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(e) * p.capacity * p.N;
-    constexpr int TO = GLU ? TB / 2 : TB;              // output blocks per wave row
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + wm * 128 + i * 32 + r32;
-        if (m >= count) continue;
-#pragma unroll
-        for (int j = 0; j < TO; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * (32 * TO) + j * 32 + q * 8 + half * 4;
-                if (n >= p.N) continue;
-                float o[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    if constexpr (GLU) o[v] = silu(acc[i][j][q * 4 + v]) * acc[i][TO + j][q * 4 + v];
-                    else o[v] = acc[i][j][q * 4 + v];
-                }
-                uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
-                *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
-            }
-    }
-}
-
 // ---------------------------------------------------------------------------------------
-// Variant with BK = 32 and a ring of four 32 KiB LDS buffers: the asynchronous copies of
-// tile kt+3 are spread one by one between the MFMAs of iteration kt (a copy issued in a
-// burst blocks the wave's MFMA issue for about 25 cycles each), and they have two full
-// iterations to land: before barrier(kt) a wave waits only until at most 12 copies are
-// outstanding (s_waitcnt vmcnt(12)), i.e. until its share of tile kt+1 is in LDS.
+// Pipelined bf16 MFMA grouped GEMM (launched for K % 64 == 0; one workgroup per tile; the fall-back of the
+// persistent kernels below): 256 x 256 staged rows, BK = 32, a ring of four 32 KiB LDS buffers.
+//   * global -> LDS copies bypass the registers (global_load_lds_dwordx4); the XOR swizzle is
+//     applied on the source side (lane l fetches the chunk that belongs in LDS slot l);
+//   * the copies of tile kt+3 are spread one by one between the MFMAs of iteration kt (a copy
+//     issued in a burst blocks the wave's MFMA issue for about 25 cycles each), and they have two
+//     full iterations to land: before barrier(kt) a wave waits only until at most 12 copies are
+//     outstanding (s_waitcnt vmcnt(12)), i.e. until its share of tile kt+1 is in LDS;
+//   * MFMA operands are double-buffered in registers: the ds_reads of k-substep s+1 are issued
+//     before the MFMAs of substep s; one barrier per iteration.
+// With GLU the 256 staged weight rows are 128 gate rows + 128 up rows of the same output columns
+// and the epilogue is SiLU(gate)*up.  With row_index the A rows are gathered straight from the
+// token matrix (dispatch folded into the load).
 // ---------------------------------------------------------------------------------------
 // s_waitcnt immediate: vmcnt(n) (6 bits, split 3:0 and 15:14), expcnt untouched, lgkmcnt(0) or untouched
 constexpr int waitcnt_imm(int vm, bool lgkm0) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm0 ? 0 : 0x0F00); }
@@ -1351,18 +1187,6 @@ hipError_t launch_bf16(GemmParams p, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <bool GLU, int SWZ, int WN = 2>
-hipError_t launch_bf16_pipe(GemmParams p, hipStream_t st) {
-    constexpr size_t lds = 2ull * 512 * 64 * 2;        // two buffers of 256 + 256 rows x 64 bf16
-    const long long blocks = plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_pipe_kernel<GLU, SWZ, WN>;
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-    if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(blocks)), dim3(128 * WN), lds, st, p);
-    return hipGetLastError();
-}
-
 template <bool GLU, int WN = 2, bool DUAL = false, int NBUF = 4>
 hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
     constexpr size_t lds = static_cast<size_t>(NBUF) * 512 * 32 * 2;        // NBUF buffers of 256 + 256 rows x 32 bf16
@@ -1522,7 +1346,7 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
         if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
         if (!pipelined_ok(g2, c.capacity)) return launch_bf16<128, 128, 64, 2, 2, false, 1>(g2, st);
         if (persist_ok(g2, false)) return launch_bf16_persist64<false>(g2, st, n_cu);
-        return launch_bf16_pipe<false, 1, 4>(g2, st);
+        return launch_bf16_ring<false, 4>(g2, st);
     }
     if (gather_rows) return hipErrorInvalidValue;
     err = launch_f32<true>(g1, st);
