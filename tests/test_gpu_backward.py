@@ -104,32 +104,47 @@ def test_backward_small_all_gradients(H, oracle, name, mode, cos):
         assert not H.to_np(bw.dwg)[e].any() and not H.to_np(bw.dwd)[e].any()
 
 
-@pytest.mark.parametrize("name", ["cfg2", "cfg5"])
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5"])
 def test_backward_full_size_sampled(H, oracle, name):
+    """Full-size gradients on samples the oracle computes one by one, laid out over the tiles the grouped products
+    schedule: one token in every 256-row tile of every expert's buffer (the last kept row included) plus a random
+    sample for dx / dgate / dscore; one hidden unit in every 128-wide tile of H of every expert for the weight
+    gradients (a row of dW_gate and dW_up and a column of dW_down each, all d entries)."""
     shape = I.CONFIGS[name]
     _say(f"backward full size {name}")
     bw = Backward(H, shape, shape.mode)
     hx = bw.host()
     rng = np.random.default_rng(7)
-    tokens = np.sort(rng.choice(shape.T, 24, replace=False)).astype(np.int32)
+    counts, slot_token = H.to_np(bw.L.counts), H.to_np(bw.L.slot_token)
+    toks = set(rng.choice(shape.T, 24, replace=False).tolist())
+    for e in range(shape.E):
+        n = int(counts[e])
+        for lo in range(0, n, 256):
+            toks.add(int(slot_token[e, int(rng.integers(lo, min(lo + 256, n)))]))
+        if n:
+            toks.add(int(slot_token[e, n - 1]))
+    tokens = np.array(sorted(toks), np.int32)
     dx, dg, ds = oracle.backward_tokens(hx["x"], hx["w_emb"], hx["w_gate"], hx["w_up"], hx["w_down"], hx["slot_of"],
                                         hx["dout"], tokens, D=shape.D, dtype=shape.dtype)
     tol = H.TOL_OUT[shape.dtype]
     got_dx = oracle.to_f64(H.to_np(bw.dx), shape.dtype)[tokens]
     e1 = H.scale_rel_err(got_dx, dx)
+    e1r = H.row_rel_err(got_dx, dx)
     e2 = H.scale_rel_err(H.to_np(bw.dgate).astype(np.float64)[tokens], dg)
     e3 = H.scale_rel_err(H.to_np(bw.dscore).astype(np.float64)[tokens], ds)
-    _say(f"  dx {e1} dgate {e2} dscore {e3}")
-    assert e1 <= tol and e2 <= tol and e3 <= tol
-    ue = rng.integers(0, shape.E, 12).astype(np.int32)
-    ui = rng.integers(0, shape.H, 12).astype(np.int32)
+    _say(f"  {len(tokens)} tokens: dx {e1} (per row {e1r}) dgate {e2} dscore {e3}")
+    assert e1 <= tol and e1r <= tol and e2 <= tol and e3 <= tol
+    n_ht = (shape.H + 127) // 128
+    ue = np.repeat(np.arange(shape.E), n_ht).astype(np.int32)
+    lo = np.tile(np.arange(n_ht) * 128, shape.E)
+    ui = (lo + rng.integers(0, 128, lo.shape[0])).clip(max=shape.H - 1).astype(np.int32)
     gw, uw, dw = oracle.backward_hidden_units(hx["x"], hx["w_emb"], hx["w_gate"], hx["w_up"], hx["w_down"], hx["slot_of"],
                                               hx["dout"], ue, ui, D=shape.D, dtype=shape.dtype)
-    g_gw = oracle.to_f64(H.to_np(bw.dwg), shape.dtype)[ue, ui]
-    g_uw = oracle.to_f64(H.to_np(bw.dwu), shape.dtype)[ue, ui]
-    g_dw = oracle.to_f64(H.to_np(bw.dwd), shape.dtype)[ue, :, ui]
+    g_gw = oracle.to_f64(H.to_np(bw.dwg)[ue, ui], shape.dtype)
+    g_uw = oracle.to_f64(H.to_np(bw.dwu)[ue, ui], shape.dtype)
+    g_dw = oracle.to_f64(H.to_np(bw.dwd)[ue, :, ui], shape.dtype)
     e4, e5, e6 = H.scale_rel_err(g_gw, gw), H.scale_rel_err(g_uw, uw), H.scale_rel_err(g_dw, dw)
-    _say(f"  dw_gate {e4} dw_up {e5} dw_down {e6}")
+    _say(f"  {len(ue)} hidden units: dw_gate {e4} dw_up {e5} dw_down {e6}")
     assert e4 <= tol and e5 <= tol and e6 <= tol
 
 
