@@ -48,13 +48,68 @@ __device__ __forceinline__ int group_k(const GemmParams& p, int e) {
     return p.k_counts ? min(max((max(p.k_counts[e], 0) + 63) & ~63, 128), p.K) : p.K;
 }
 
-__device__ __forceinline__ uint32_t f2bf(float f) {            // fp32 -> bf16 bits, round to nearest even
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+// Two fp32 values -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ uint2 pack_bf16x4(float a, float b, float c, float d) {
+    return make_uint2(pack_bf16(a, b), pack_bf16(c, d));
 }
 
-__device__ __forceinline__ float silu(float a) { return a / (1.0f + __expf(-a)); }
+// SiLU(a) = a / (1 + exp(-a)) with the hardware exponential and reciprocal (about 1 ulp each; the result
+// is rounded to bf16 right after)
+__device__ __forceinline__ float silu(float a) {
+    return a * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896341f * a));
+}
+
+// Epilogue shared by the MFMA kernels.  acc[i][j] is the 32 x 32 block at rows m_base + 32 i, staged weight rows
+// 32 j of this wave (GLU: the first TB/2 blocks are gate rows, the others the up rows of the same output columns).
+// A lane holds, per block, row m = lane % 32 and the columns (v / 4) * 8 + (lane / 32) * 4 + v % 4, so every store is
+// four consecutive bf16 of one row.
+// KEEP (SwiGLU epilogue only): the two products are stored as well (C2, C3), for the training-mode forward.
+template <bool GLU, bool DUAL, int TI, int TB, bool KEEP = false>
+__device__ __forceinline__ void store_blocks(const GemmParams& p, const f32x16 (&acc)[TI][TB], int e, int m_base,
+                                             int n_base, int count, int r32, int half) {
+    constexpr int TO = GLU ? TB / 2 : TB;
+    uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(e) * p.capacity * p.N;
+    uint16_t* C2g = (GLU && (DUAL || KEEP)) ? reinterpret_cast<uint16_t*>(p.C2) + static_cast<size_t>(e) * p.capacity * p.N : nullptr;
+    uint16_t* C3g = (GLU && !DUAL && KEEP) ? reinterpret_cast<uint16_t*>(p.C3) + static_cast<size_t>(e) * p.capacity * p.N : nullptr;
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+        const int m = m_base + i * 32 + r32;
+        if (m >= count) continue;
+#pragma unroll
+        for (int j = 0; j < TO; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n_base + j * 32 + q * 8 + half * 4;
+                if (n >= p.N) continue;
+                const size_t o = static_cast<size_t>(m) * p.N + n;
+                const f32x16& g0 = acc[i][j];
+                if constexpr (GLU) {
+                    const f32x16& g1 = acc[i][TO + j];
+                    if constexpr (DUAL) {                           // both products, no activation
+                        *reinterpret_cast<uint2*>(Cg + o) = pack_bf16x4(g0[q * 4], g0[q * 4 + 1], g0[q * 4 + 2], g0[q * 4 + 3]);
+                        *reinterpret_cast<uint2*>(C2g + o) = pack_bf16x4(g1[q * 4], g1[q * 4 + 1], g1[q * 4 + 2], g1[q * 4 + 3]);
+                    } else {
+                        *reinterpret_cast<uint2*>(Cg + o) =
+                            pack_bf16x4(silu(g0[q * 4]) * g1[q * 4], silu(g0[q * 4 + 1]) * g1[q * 4 + 1],
+                                        silu(g0[q * 4 + 2]) * g1[q * 4 + 2], silu(g0[q * 4 + 3]) * g1[q * 4 + 3]);
+                        if constexpr (KEEP) {                       // keep the pre-activations (training-mode forward)
+                            *reinterpret_cast<uint2*>(C2g + o) = pack_bf16x4(g0[q * 4], g0[q * 4 + 1], g0[q * 4 + 2], g0[q * 4 + 3]);
+                            *reinterpret_cast<uint2*>(C3g + o) = pack_bf16x4(g1[q * 4], g1[q * 4 + 1], g1[q * 4 + 2], g1[q * 4 + 3]);
+                        }
+                    }
+                } else {
+                    *reinterpret_cast<uint2*>(Cg + o) = pack_bf16x4(g0[q * 4], g0[q * 4 + 1], g0[q * 4 + 2], g0[q * 4 + 3]);
+                }
+            }
+        __builtin_amdgcn_sched_barrier(0);               // one row of blocks at a time: keeps the live set small
+    }
+}
 
 // Workgroup -> (expert, row tile, column tile).  Hardware deals consecutive workgroups round-robin
 // to the 8 XCDs, each with its own 4 MiB L2 and 32 CUs.  Tiles are grouped into "super-tiles" of
@@ -227,28 +282,25 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
             for (int q = 0; q < 4; ++q) {
                 const int n = n0 + wn0 + j * 32 + q * 8 + half * 4;
                 if (n >= p.N) continue;
+                const f32x16& g0 = acc[0][i][j];
+                const f32x16& g1 = acc[NB - 1][i][j];
                 float o[4];
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    if constexpr (GLU && !DUAL) o[v] = silu(acc[0][i][j][q * 4 + v]) * acc[1][i][j][q * 4 + v];
-                    else o[v] = acc[0][i][j][q * 4 + v];
+                    if constexpr (GLU && !DUAL) o[v] = silu(g0[q * 4 + v]) * g1[q * 4 + v];
+                    else o[v] = g0[q * 4 + v];
                 }
-                uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
-                *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
-                if constexpr (GLU && DUAL) {
-                    const f32x16& u = acc[NB - 1][i][j];
-                    pk = make_uint2(f2bf(u[q * 4]) | (f2bf(u[q * 4 + 1]) << 16), f2bf(u[q * 4 + 2]) | (f2bf(u[q * 4 + 3]) << 16));
-                    *reinterpret_cast<uint2*>(C2g + static_cast<size_t>(m) * p.N + n) = pk;
-                }
+                *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pack_bf16x4(o[0], o[1], o[2], o[3]);
+                if constexpr (GLU && DUAL)
+                    *reinterpret_cast<uint2*>(C2g + static_cast<size_t>(m) * p.N + n) =
+                        pack_bf16x4(g1[q * 4], g1[q * 4 + 1], g1[q * 4 + 2], g1[q * 4 + 3]);
                 if constexpr (GLU && !DUAL) {
                     if (p.C3) {                                     // keep the pre-activations (training-mode forward)
-                        const size_t o = (static_cast<size_t>(e) * p.capacity + m) * p.N + n;
-                        const f32x16& g0 = acc[0][i][j];
-                        const f32x16& g1 = acc[NB - 1][i][j];
-                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C2) + o) =
-                            make_uint2(f2bf(g0[q * 4]) | (f2bf(g0[q * 4 + 1]) << 16), f2bf(g0[q * 4 + 2]) | (f2bf(g0[q * 4 + 3]) << 16));
-                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C3) + o) =
-                            make_uint2(f2bf(g1[q * 4]) | (f2bf(g1[q * 4 + 1]) << 16), f2bf(g1[q * 4 + 2]) | (f2bf(g1[q * 4 + 3]) << 16));
+                        const size_t o3 = (static_cast<size_t>(e) * p.capacity + m) * p.N + n;
+                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C2) + o3) =
+                            pack_bf16x4(g0[q * 4], g0[q * 4 + 1], g0[q * 4 + 2], g0[q * 4 + 3]);
+                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C3) + o3) =
+                            pack_bf16x4(g1[q * 4], g1[q * 4 + 1], g1[q * 4 + 2], g1[q * 4 + 3]);
                     }
                 }
             }
@@ -406,35 +458,9 @@ __global__ __launch_bounds__(128 * WN) void gemm_bf16_ring_kernel(GemmParams p) 
         mfma_step(1, false, 0, 0);
     }
 
-    // ---- epilogue: lane holds, per 32x32 block, row m = lane%32 and columns (v/4)*8 + (lane/32)*4 + v%4
-    uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(e) * p.capacity * p.N;
-    uint16_t* C2g = DUAL ? reinterpret_cast<uint16_t*>(p.C2) + static_cast<size_t>(e) * p.capacity * p.N : nullptr;
     constexpr int TO = GLU ? TB / 2 : TB;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + wm * 128 + i * 32 + r32;
-        if (m >= count) continue;
-#pragma unroll
-        for (int j = 0; j < TO; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * (32 * TO) + j * 32 + q * 8 + half * 4;
-                if (n >= p.N) continue;
-                float o[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    if constexpr (GLU && !DUAL) o[v] = silu(acc[i][j][q * 4 + v]) * acc[i][TO + j][q * 4 + v];
-                    else o[v] = acc[i][j][q * 4 + v];
-                }
-                uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
-                *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
-                if constexpr (GLU && DUAL) {
-                    const f32x16& u = acc[i][TB - TO + j];
-                    pk = make_uint2(f2bf(u[q * 4]) | (f2bf(u[q * 4 + 1]) << 16), f2bf(u[q * 4 + 2]) | (f2bf(u[q * 4 + 3]) << 16));
-                    *reinterpret_cast<uint2*>(C2g + static_cast<size_t>(m) * p.N + n) = pk;
-                }
-            }
-    }
+    if (GLU && !DUAL && p.C3) store_blocks<GLU, DUAL, 4, TB, GLU && !DUAL>(p, acc, e, m0 + wm * 128, n0 + wn * (32 * TO), count, r32, half);
+    else store_blocks<GLU, DUAL, 4, TB>(p, acc, e, m0 + wm * 128, n0 + wn * (32 * TO), count, r32, half);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -633,22 +659,75 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
 #pragma unroll
     for (int j = 0; j < TB; ++j) b_tr[j] = BM * CPR * 16 + tr_off(wn * (32 * TB) + j * 32);
     // The reads are written as assembly: through the compiler's builtin every such read waits for ALL outstanding
-    // copies (vmcnt(0)), because it is taken to alias the asynchronous LDS writes.  The hardware counter is not
-    // tracked for assembly, so the loops below wait (lgkmcnt(0)) themselves before the fragments are used.
+    // copies (vmcnt(0)), because it is taken to alias the asynchronous LDS writes.  The compiler does not track the
+    // LDS counter for assembly, so every statement below carries its own wait (lgkmcnt(0)) behind its reads: when
+    // the statement ends its outputs are ordinary, fully written registers, and nothing depends on how the register
+    // allocator treats them afterwards.  All reads of one statement are in flight together; the statement is placed
+    // one k-substep before the fragments are used, so the wait overlaps with the MFMAs of the other wave of the SIMD.
     typedef int v2i __attribute__((ext_vector_type(2)));
     typedef int v4i __attribute__((ext_vector_type(4)));
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)lds_raw));
-    auto tr_frag = [&](uint32_t byte) -> bf16x8 {          // k .. k+3 and k+4 .. k+7 of one row
-        const uint32_t addr = lds_base + byte;
-        v2i x0, x1;
-        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(x0) : "v"(addr));
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:256" : "=v"(x1) : "v"(addr));
-        const v4i r = {x0.x, x0.y, x1.x, x1.y};
+    auto tr_pack = [](v2i lo, v2i hi) -> bf16x8 {          // k .. k+3 and k+4 .. k+7 of one row
+        const v4i r = {lo.x, lo.y, hi.x, hi.y};
         return __builtin_bit_cast(bf16x8, r);
     };
-    auto tr_wait = [&]() {                                 // fragments read through tr_frag have arrived
-        if constexpr (TRA || TRB) __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0)
+    auto tr_frags4 = [&](bf16x8* f, uint32_t slot, const uint32_t* off) {
+        const uint32_t a0 = lds_base + slot + off[0], a1 = lds_base + slot + off[1];
+        const uint32_t a2 = lds_base + slot + off[2], a3 = lds_base + slot + off[3];
+        v2i x0, x1, x2, x3, x4, x5, x6, x7;
+        asm volatile(
+            "ds_read_b64_tr_b16 %0, %8\n\t"
+            "ds_read_b64_tr_b16 %1, %8 offset:256\n\t"
+            "ds_read_b64_tr_b16 %2, %9\n\t"
+            "ds_read_b64_tr_b16 %3, %9 offset:256\n\t"
+            "ds_read_b64_tr_b16 %4, %10\n\t"
+            "ds_read_b64_tr_b16 %5, %10 offset:256\n\t"
+            "ds_read_b64_tr_b16 %6, %11\n\t"
+            "ds_read_b64_tr_b16 %7, %11 offset:256\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(x0), "=&v"(x1), "=&v"(x2), "=&v"(x3), "=&v"(x4), "=&v"(x5), "=&v"(x6), "=&v"(x7)
+            : "v"(a0), "v"(a1), "v"(a2), "v"(a3));
+        f[0] = tr_pack(x0, x1); f[1] = tr_pack(x2, x3); f[2] = tr_pack(x4, x5); f[3] = tr_pack(x6, x7);
     };
+    auto tr_frags2 = [&](bf16x8* f, uint32_t slot, const uint32_t* off) {
+        const uint32_t a0 = lds_base + slot + off[0], a1 = lds_base + slot + off[1];
+        v2i x0, x1, x2, x3;
+        asm volatile(
+            "ds_read_b64_tr_b16 %0, %4\n\t"
+            "ds_read_b64_tr_b16 %1, %4 offset:256\n\t"
+            "ds_read_b64_tr_b16 %2, %5\n\t"
+            "ds_read_b64_tr_b16 %3, %5 offset:256\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(x0), "=&v"(x1), "=&v"(x2), "=&v"(x3)
+            : "v"(a0), "v"(a1));
+        f[0] = tr_pack(x0, x1); f[1] = tr_pack(x2, x3);
+    };
+    auto tr_frags6 = [&](bf16x8* f, bf16x8* h, uint32_t slot, const uint32_t* off, const uint32_t* off2) {
+        const uint32_t a0 = lds_base + slot + off[0], a1 = lds_base + slot + off[1];
+        const uint32_t a2 = lds_base + slot + off[2], a3 = lds_base + slot + off[3];
+        const uint32_t a4 = lds_base + slot + off2[0], a5 = lds_base + slot + off2[1];
+        v2i x0, x1, x2, x3, x4, x5, x6, x7, x8, x9, x10, x11;
+        asm volatile(
+            "ds_read_b64_tr_b16 %0, %12\n\t"
+            "ds_read_b64_tr_b16 %1, %12 offset:256\n\t"
+            "ds_read_b64_tr_b16 %2, %13\n\t"
+            "ds_read_b64_tr_b16 %3, %13 offset:256\n\t"
+            "ds_read_b64_tr_b16 %4, %14\n\t"
+            "ds_read_b64_tr_b16 %5, %14 offset:256\n\t"
+            "ds_read_b64_tr_b16 %6, %15\n\t"
+            "ds_read_b64_tr_b16 %7, %15 offset:256\n\t"
+            "ds_read_b64_tr_b16 %8, %16\n\t"
+            "ds_read_b64_tr_b16 %9, %16 offset:256\n\t"
+            "ds_read_b64_tr_b16 %10, %17\n\t"
+            "ds_read_b64_tr_b16 %11, %17 offset:256\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(x0), "=&v"(x1), "=&v"(x2), "=&v"(x3), "=&v"(x4), "=&v"(x5), "=&v"(x6), "=&v"(x7), "=&v"(x8),
+              "=&v"(x9), "=&v"(x10), "=&v"(x11)
+            : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(a4), "v"(a5));
+        f[0] = tr_pack(x0, x1); f[1] = tr_pack(x2, x3); f[2] = tr_pack(x4, x5); f[3] = tr_pack(x6, x7);
+        h[0] = tr_pack(x8, x9); h[1] = tr_pack(x10, x11);
+    };
+    static_assert(TB == 2, "tr_frags2 / tr_frags6 read the two weight fragments of a wave");
 
     f32x16 acc[4][TB];
     bf16x8 fa[2][4], fb[2][TB];
@@ -656,16 +735,18 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
     auto load_frags = [&](int set, int g, int ck) {
         const uint4* base = lds + (g & (NBUF - 1)) * STAGE + ck;
         const uint32_t slot = static_cast<uint32_t>(g & (NBUF - 1)) * (STAGE * 16) + set * 1024;
+        // row-major operands first: their reads are in flight while the transposing statement waits
+        if constexpr (!TRA) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            if constexpr (TRA) fa[set][i] = tr_frag(slot + a_tr[i]);
-            else fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
+            for (int i = 0; i < 4; ++i) fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
         }
+        if constexpr (!TRB) {
 #pragma unroll
-        for (int j = 0; j < TB; ++j) {
-            if constexpr (TRB) fb[set][j] = tr_frag(slot + b_tr[j]);
-            else fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
+            for (int j = 0; j < TB; ++j) fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
         }
+        if constexpr (TRA && TRB) tr_frags6(fa[set], fb[set], slot, a_tr, b_tr);
+        else if constexpr (TRA) tr_frags4(fa[set], slot, a_tr);
+        else if constexpr (TRB) tr_frags2(fb[set], slot, b_tr);
     };
 
     int q = xcd * GS + slot_l;                           // first pass over the list
@@ -714,7 +795,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
                 const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
                 __builtin_amdgcn_global_load_lds((global_cptr)(base + offs[j]), (lds_ptr)dst, 16, 0, 0);
             };
-            tr_wait();                                               // the first substep's fragments (read one step ago)
             __builtin_amdgcn_sched_barrier(0);
             load_frags(1, g, ck1);
 #pragma unroll
@@ -739,7 +819,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
             }
         }
         for (; kt < KT; ++kt, ++g) {                                 // tail of this workgroup's last tile: nothing to fetch
-            tr_wait();
             __builtin_amdgcn_sched_barrier(0);
             load_frags(1, g, ck1);
 #pragma unroll
@@ -762,45 +841,11 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
             }
         }
         // ---- epilogue of cur (the copies of the next tile are in flight)
-        uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(cur.e) * p.capacity * p.N;
-        uint16_t* C2g = DUAL ? reinterpret_cast<uint16_t*>(p.C2) + static_cast<size_t>(cur.e) * p.capacity * p.N : nullptr;
         constexpr int TO = GLU ? TB / 2 : TB;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = cur.m0 + wm * 128 + i * 32 + r32;
-            if (m >= cur.count) continue;
-#pragma unroll
-            for (int j = 0; j < TO; ++j)
-#pragma unroll
-                for (int qq = 0; qq < 4; ++qq) {
-                    const int n = cur.n0 + wn * (32 * TO) + j * 32 + qq * 8 + half * 4;
-                    if (n >= p.N) continue;
-                    float o[4];
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        if constexpr (GLU && !DUAL) o[v] = silu(acc[i][j][qq * 4 + v]) * acc[i][TO + j][qq * 4 + v];
-                        else o[v] = acc[i][j][qq * 4 + v];
-                    }
-                    uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
-                    *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
-                    if constexpr (GLU && DUAL) {
-                        const f32x16& u2 = acc[i][TB - TO + j];
-                        pk = make_uint2(f2bf(u2[qq * 4]) | (f2bf(u2[qq * 4 + 1]) << 16), f2bf(u2[qq * 4 + 2]) | (f2bf(u2[qq * 4 + 3]) << 16));
-                        *reinterpret_cast<uint2*>(C2g + static_cast<size_t>(m) * p.N + n) = pk;
-                    }
-                    if constexpr (GLU && !DUAL) {
-                        if (p.C3) {                                 // keep the pre-activations (training-mode forward)
-                            const size_t o = (static_cast<size_t>(cur.e) * p.capacity + m) * p.N + n;
-                            const f32x16& g0 = acc[i][j];
-                            const f32x16& g1 = acc[i][TO + j];
-                            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C2) + o) =
-                                make_uint2(f2bf(g0[qq * 4]) | (f2bf(g0[qq * 4 + 1]) << 16), f2bf(g0[qq * 4 + 2]) | (f2bf(g0[qq * 4 + 3]) << 16));
-                            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C3) + o) =
-                                make_uint2(f2bf(g1[qq * 4]) | (f2bf(g1[qq * 4 + 1]) << 16), f2bf(g1[qq * 4 + 2]) | (f2bf(g1[qq * 4 + 3]) << 16));
-                        }
-                    }
-                }
-        }
+        if (GLU && !DUAL && p.C3)
+            store_blocks<GLU, DUAL, 4, TB, GLU && !DUAL>(p, acc, cur.e, cur.m0 + wm * 128, cur.n0 + wn * (32 * TO), cur.count, r32, half);
+        else
+            store_blocks<GLU, DUAL, 4, TB>(p, acc, cur.e, cur.m0 + wm * 128, cur.n0 + wn * (32 * TO), cur.count, r32, half);
         if (!has_next) break;
         cur = nxt;
         q = qn;
@@ -826,11 +871,12 @@ __device__ __forceinline__ int live_row_tiles(const GemmParams& p, int e, int mg
 }
 __device__ __forceinline__ int live_col_tiles(const GemmParams& p, int ng) { return min(p.NT - ng * p.SN, p.SN); }
 
-// pre[s] = number of live tiles in the super-tiles before s (s <= S = E * MG * NG), by 512 threads
+// pre[s] = number of live tiles in the super-tiles before s (s <= S = E * MG * NG), by NTH threads
+template <int NTH = 512>
 __device__ __forceinline__ void live_tile_prefix(const GemmParams& p, int BM, int MG, int NG, int* pre, int* wave_tot) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = p.E * MG * NG;
-    const int CH = (S + 511) / 512;
+    const int CH = (S + NTH - 1) / NTH;
     auto tiles_of = [&](int s) {
         const int e = s / (MG * NG), r = s - e * (MG * NG);
         return live_row_tiles(p, e, r % MG, BM) * live_col_tiles(p, r / MG);
@@ -857,7 +903,7 @@ __device__ __forceinline__ void live_tile_prefix(const GemmParams& p, int BM, in
             run += tiles_of(s);
         }
     }
-    if (tid == 511) pre[S] = run;                        // thread 511 owns the last chunk (or nothing): run = total
+    if (tid == NTH - 1) pre[S] = run;                    // the last thread owns the last chunk (or nothing): run = total
     __syncthreads();
 }
 
@@ -1042,49 +1088,271 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist64_kernel(GemmParams p) 
             mfma_block(1);
         }
         // ---- epilogue of cur (the copies of the next tile are in flight)
-        uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + static_cast<size_t>(cur.e) * p.capacity * p.N;
-        uint16_t* C2g = DUAL ? reinterpret_cast<uint16_t*>(p.C2) + static_cast<size_t>(cur.e) * p.capacity * p.N : nullptr;
         constexpr int TO = GLU ? TB / 2 : TB;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = cur.m0 + wm * 128 + i * 32 + r32;
-            if (m >= cur.count) continue;
-#pragma unroll
-            for (int j = 0; j < TO; ++j)
-#pragma unroll
-                for (int qq = 0; qq < 4; ++qq) {
-                    const int n = cur.n0 + wn * (32 * TO) + j * 32 + qq * 8 + half * 4;
-                    if (n >= p.N) continue;
-                    float o[4];
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        if constexpr (GLU && !DUAL) o[v] = silu(acc[i][j][qq * 4 + v]) * acc[i][TO + j][qq * 4 + v];
-                        else o[v] = acc[i][j][qq * 4 + v];
-                    }
-                    uint2 pk = make_uint2(f2bf(o[0]) | (f2bf(o[1]) << 16), f2bf(o[2]) | (f2bf(o[3]) << 16));
-                    *reinterpret_cast<uint2*>(Cg + static_cast<size_t>(m) * p.N + n) = pk;
-                    if constexpr (GLU && DUAL) {
-                        const f32x16& u2 = acc[i][TB - TO + j];
-                        pk = make_uint2(f2bf(u2[qq * 4]) | (f2bf(u2[qq * 4 + 1]) << 16), f2bf(u2[qq * 4 + 2]) | (f2bf(u2[qq * 4 + 3]) << 16));
-                        *reinterpret_cast<uint2*>(C2g + static_cast<size_t>(m) * p.N + n) = pk;
-                    }
-                    if constexpr (GLU && !DUAL) {
-                        if (p.C3) {                                 // keep the pre-activations (training-mode forward)
-                            const size_t o3 = (static_cast<size_t>(cur.e) * p.capacity + m) * p.N + n;
-                            const f32x16& g0 = acc[i][j];
-                            const f32x16& g1 = acc[i][TO + j];
-                            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C2) + o3) =
-                                make_uint2(f2bf(g0[qq * 4]) | (f2bf(g0[qq * 4 + 1]) << 16), f2bf(g0[qq * 4 + 2]) | (f2bf(g0[qq * 4 + 3]) << 16));
-                            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(p.C3) + o3) =
-                                make_uint2(f2bf(g1[qq * 4]) | (f2bf(g1[qq * 4 + 1]) << 16), f2bf(g1[qq * 4 + 2]) | (f2bf(g1[qq * 4 + 3]) << 16));
-                        }
-                    }
-                }
-        }
+        if (GLU && !DUAL && p.C3)
+            store_blocks<GLU, DUAL, 4, TB, GLU && !DUAL>(p, acc, cur.e, cur.m0 + wm * 128, cur.n0 + wn * (32 * TO), cur.count, r32, half);
+        else
+            store_blocks<GLU, DUAL, 4, TB>(p, acc, cur.e, cur.m0 + wm * 128, cur.n0 + wn * (32 * TO), cur.count, r32, half);
         if (!has_next) break;
         cur = nxt;
         q = qn;
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Four-wave form of the 64-wide persistent kernel: the same 256 x 256 tile, tile list, run-on across tile
+// boundaries and epilogue, but one wave per SIMD with a 128 x 128 accumulator slice (256 accumulator registers).
+// Per k-substep a wave reads 4 + 4 fragments for 16 MFMAs instead of 4 + 2 for 8: a third fewer bytes leave
+// LDS per flop, and there is one barrier per 64 MFMAs of a wave instead of one per 32.
+//
+// Copies.  Buffer g & 1 is released by the barrier before the fourth substep of step g.  A wave's copies of
+// k-tile g + 2 are spread over two substeps: its 8 groups of token rows go out between the MFMAs of that fourth
+// substep, its 8 groups of weight rows between the MFMAs of the first substep of step g + 1 (64 KiB inside one
+// substep is twice what a CU's address unit takes in that time, and a wave that waits for a slot there issues no
+// MFMA either).  All of them land before the barrier of step g + 1, two substeps later.  The weight rows of a
+// tile are N-aligned (a launch condition), so their addresses are a wave-uniform base plus one of two per-lane
+// offsets that never change; only the token rows carry per-tile lane offsets.  There is always something to
+// copy: past the end of a workgroup's list the last k-tile is fetched again into a buffer nobody reads any more,
+// which keeps the unrolled MFMA sequences free of branches.
+//
+// Gathered token rows (row_index).  The 256 row indices of a tile travel through LDS as well: one 4-byte
+// asynchronous copy per wave, requested two tiles ahead, so no wave ever waits for a global load while it sets up
+// a tile.  Three slots rotate; a slot is read one tile after it was requested (at least two barriers with
+// vmcnt(0) lie in between) and rewritten two tiles after it was read.
+//
+// Fragment reads of the next substep are issued after the first four MFMAs of the current one, so the wait in
+// front of a substep's first MFMA only ever covers reads that are 12 MFMAs old.
+// ---------------------------------------------------------------------------------------
+template <bool GLU, bool DUAL = false, bool KEEP = false>
+__global__ __launch_bounds__(256) void gemm_bf16_persist128_kernel(GemmParams p) {
+    static_assert(!KEEP || (GLU && !DUAL), "the pre-activations are kept by the SwiGLU epilogue only");
+    constexpr int BM = 256, BR = 256, CPR = 8, SWZ = 1;
+    constexpr int BN = GLU ? 128 : 256;
+    constexpr int STAGE = (BM + BR) * CPR;               // uint4 per LDS buffer (64 KiB)
+    constexpr int WN = 2, NW = 4, TB = 4, NCP = 8;       // NCP: groups of 8 rows each wave copies per operand
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    uint4* lds = reinterpret_cast<uint4*>(lds_raw);
+    __shared__ int pre[kMaxSuper + 1];
+    __shared__ int wave_tot[NW];
+    __shared__ int row_ids[3][BM];                       // gathered rows of a tile: this, the next, the one after
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int r32 = lane & 31, half = lane >> 5;
+    const int KCA = (p.lda ? p.lda : p.K) / 8, KCB = (p.ldb ? p.ldb : p.K) / 8;
+    const bool gather = p.row_index != nullptr;
+
+    const int MG = (p.MT + p.SM - 1) / p.SM, NG = (p.NT + p.SN - 1) / p.SN;
+    const int S = p.E * MG * NG;
+    live_tile_prefix<256>(p, BM, MG, NG, pre, wave_tot);
+    const int total = pre[S];
+    const int GS = gridDim.x >> 3;                       // tiles per group = workgroups per XCD
+    const int xcd = blockIdx.x & 7, slot_l = blockIdx.x >> 3;
+
+    struct Tile {
+        int e, m0, n0, count, KT;
+        uint64_t Abase, Bbase;                           // wave-uniform; Bbase includes the wave's first weight row
+        uint32_t offA[NCP];                              // per-lane byte offsets of the 8 token-row groups
+    };
+    // row group i of this wave: rows rr0 + 8 i, chunk c0 ^ 4 (i & 1) of the swizzle (8 rows further on flips bit 2)
+    const int rr0 = wave * (NCP * 8) + (lane >> 3);
+    const int c0 = (lane & 7) ^ ((rr0 >> SWZ) & 7);
+    const uint32_t laneB[2] = {(static_cast<uint32_t>(lane >> 3) * KCB + c0) * 16u,
+                               (static_cast<uint32_t>(lane >> 3) * KCB + (c0 ^ 4)) * 16u};
+    const uint64_t strideB8 = static_cast<uint64_t>(8) * KCB * 16;      // 8 weight rows further on
+
+    auto decode = [&](int q, Tile& t) {                  // scalar part of the tile with list index q
+        int lo = 0, hi = S;                              // largest s with pre[s] <= q
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (pre[mid] <= q) lo = mid; else hi = mid;
+        }
+        const int s = __builtin_amdgcn_readfirstlane(lo);
+        const int u = __builtin_amdgcn_readfirstlane(q - pre[s]);
+        const int e = s / (MG * NG), r = s - e * (MG * NG);
+        const int mg = r % MG, ng = r / MG;
+        const int vm = live_row_tiles(p, e, mg, BM);
+        const int mt = mg * p.SM + u % vm, nt = ng * p.SN + u / vm;
+        t.e = e; t.m0 = mt * BM; t.n0 = nt * BN;
+        t.count = group_rows(p, e);
+        t.KT = group_k(p, e) / 64;
+        t.Abase = reinterpret_cast<uint64_t>(p.A) + (gather ? 0 : static_cast<uint64_t>(e) * p.capacity * KCA * 16);
+        // this wave's 64 staged weight rows: GLU stages 128 gate rows, then the 128 up rows of the same columns
+        const int nrow = t.n0 + (GLU ? (wave & 1) * 64 : wave * 64);
+        t.Bbase = reinterpret_cast<uint64_t>((GLU && wave >= NW / 2) ? p.B1 : p.B0) +
+                  (static_cast<uint64_t>(e) * p.N + nrow) * KCB * 16;
+    };
+    // asynchronous copy of the tile's row indices (this wave's 64 rows) into slot `slot`
+    auto request_rows = [&](const Tile& t, int slot) {
+        int m = t.m0 + wave * 64 + lane;
+        m = m < t.count ? m : t.count - 1;               // rows past the count replay a valid row; never stored
+        const int32_t* src = p.row_index + static_cast<size_t>(t.e) * p.capacity + m;
+        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(&row_ids[slot][wave * 64]), 4, 0, 0);
+    };
+    // per-lane offsets of the token rows; with `gather` the indices have landed in slot `slot`
+    auto finish = [&](Tile& t, int slot) {
+        int row[NCP];
+        if (gather) {                                    // one uniform branch around straight-line code
+#pragma unroll
+            for (int i = 0; i < NCP; ++i) row[i] = min(max(row_ids[slot][rr0 + 8 * i], 0), p.a_rows - 1);
+        } else {
+#pragma unroll
+            for (int i = 0; i < NCP; ++i) row[i] = min(t.m0 + rr0 + 8 * i, t.count - 1);
+        }
+#pragma unroll
+        for (int i = 0; i < NCP; ++i) t.offA[i] = (static_cast<uint32_t>(row[i]) * KCA + (c0 ^ (4 * (i & 1)))) * 16u;
+    };
+    auto copy_to = [&](uint64_t b64, uint32_t off, uint4* dst) {
+        const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
+        const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
+        const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
+        __builtin_amdgcn_global_load_lds((global_cptr)(base + off), (lds_ptr)dst, 16, 0, 0);
+    };
+    // token-row group i / weight-row group i of the k-tile at abase / bbase into buffer buf
+    auto copy_a = [&](uint64_t abase, uint32_t off, int buf, int i) {
+        copy_to(abase, off, lds + buf * STAGE + (wave * NCP + i) * 64);
+    };
+    auto copy_b = [&](uint64_t bbase, int buf, int i) {
+        copy_to(bbase + i * strideB8, laneB[i & 1], lds + buf * STAGE + BM * CPR + (wave * NCP + i) * 64);
+    };
+
+    const int sw = (r32 >> SWZ) & 7;
+    int a_row[4], b_row[TB];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a_row[i] = (wm * 128 + i * 32 + r32) * CPR;
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+        const int br = GLU ? ((j / (TB / 2)) * 128 + wn * (16 * TB) + (j % (TB / 2)) * 32) : (wn * (32 * TB) + j * 32);
+        b_row[j] = BM * CPR + (br + r32) * CPR;
+    }
+    int ck[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) ck[ks] = (ks * 2 + half) ^ sw;
+
+    f32x16 acc[4][TB];
+    bf16x8 fa[2][4], fb[2][TB];
+    auto load_frags = [&](int set, int buf, int ks) {
+        const uint4* base = lds + buf * STAGE + ck[ks];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
+#pragma unroll
+        for (int j = 0; j < TB; ++j) fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
+    };
+    auto mfma_row = [&](int set, int i) {
+#pragma unroll
+        for (int j = 0; j < TB; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
+    };
+
+    int q = xcd * GS + slot_l;                           // first pass over the list
+    if (q >= total) return;                              // uniform: nothing for this workgroup
+    Tile cur, nxt;
+    decode(q, cur);
+    int seq = 0;                                         // tiles this workgroup has started; tile n uses slot n % 3
+    if (gather) {
+        request_rows(cur, 0);
+        if (q + 8 * GS < total) {
+            decode(q + 8 * GS, nxt);
+            request_rows(nxt, 1);
+        }
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, false));
+    }
+    finish(cur, 0);
+    int g = 0;                                           // global step: buffer g & 1
+    for (int t = 0; t < 2; ++t) {                        // KT >= 2 is a launch condition
+#pragma unroll
+        for (int i = 0; i < NCP; ++i) copy_a(cur.Abase + t * 128, cur.offA[i], t, i);
+#pragma unroll
+        for (int i = 0; i < NCP; ++i) copy_b(cur.Bbase + t * 128, t, i);
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * NCP, false));             // the first k-tile (copies retire in order)
+    __builtin_amdgcn_s_barrier();
+    load_frags(0, 0, 0);
+    uint64_t lateB = cur.Bbase + 128;                    // weight rows still owed to the other buffer (none yet:
+                                                         // the second k-tile's own once more)
+    for (;;) {
+        const int qn = q + 8 * GS;                       // same XCD, next round
+        const bool has_next = qn < total;
+        if (has_next) {
+            decode(qn, nxt);
+            finish(nxt, (seq + 1) % 3);
+            const int qnn = qn + 8 * GS;
+            if (gather && qnn < total) {
+                Tile t2;
+                decode(qnn, t2);
+                request_rows(t2, (seq + 2) % 3);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < TB; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        const int KT = cur.KT;
+        for (int kt = 0; kt < KT; ++kt, ++g) {
+            // k-tile g + 2: of this tile, else of the next one, else (nothing left) this tile's last one again
+            const bool in_cur = kt + 2 < KT;
+            const bool from_next = !in_cur && has_next;
+            const int kf = in_cur ? kt + 2 : (from_next ? kt + 2 - KT : KT - 1);
+            const uint64_t baseA = (from_next ? nxt.Abase : cur.Abase) + kf * 128;
+            const uint64_t baseB = (from_next ? nxt.Bbase : cur.Bbase) + kf * 128;
+            uint32_t offs[NCP];
+#pragma unroll
+            for (int i = 0; i < NCP; ++i) offs[i] = from_next ? nxt.offA[i] : cur.offA[i];
+            const int buf = g & 1;
+            // substep 0, with the weight rows of k-tile g + 1 into the other buffer
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_row(0, 0);
+            copy_b(lateB, buf ^ 1, 0); copy_b(lateB, buf ^ 1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(1, buf, 1);
+#pragma unroll
+            for (int i = 1; i < 4; ++i) {
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_row(0, i);
+                copy_b(lateB, buf ^ 1, 2 * i); copy_b(lateB, buf ^ 1, 2 * i + 1);
+            }
+            // substeps 1 and 2
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_row(1, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(0, buf, 2);
+            mfma_row(1, 1); mfma_row(1, 2); mfma_row(1, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_row(0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(1, buf, 3);
+            mfma_row(0, 1); mfma_row(0, 2); mfma_row(0, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            // k-tile g + 1 has landed and this wave's reads of buffer buf are done; past the barrier that holds for all
+            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
+            __builtin_amdgcn_s_barrier();
+            // substep 3, with the token rows of k-tile g + 2 into the buffer just released
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_row(1, 0);
+            copy_a(baseA, offs[0], buf, 0); copy_a(baseA, offs[1], buf, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(0, buf ^ 1, 0);
+#pragma unroll
+            for (int i = 1; i < 4; ++i) {
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_row(1, i);
+                copy_a(baseA, offs[2 * i], buf, 2 * i); copy_a(baseA, offs[2 * i + 1], buf, 2 * i + 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            lateB = baseB;
+        }
+        // ---- epilogue of cur (the copies of the next tile are in flight)
+        constexpr int TO = GLU ? TB / 2 : TB;
+        store_blocks<GLU, DUAL, 4, TB, KEEP>(p, acc, cur.e, cur.m0 + wm * 128, cur.n0 + wn * (32 * TO), cur.count, r32, half);
+        if (!has_next) break;
+        cur = nxt;
+        q = qn;
+        ++seq;
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, false));   // the re-fetched k-tiles of the last two steps
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1223,6 +1491,19 @@ hipError_t launch_bf16_persist64(GemmParams p, hipStream_t st, int n_cu) {
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(512), lds, st, p);
     return hipGetLastError();
 }
+template <bool GLU, bool DUAL = false, bool KEEP = false>
+hipError_t launch_bf16_persist128(GemmParams p, hipStream_t st, int n_cu) {
+    constexpr size_t lds = 2ull * 512 * 64 * 2;                             // two buffers of 256 + 256 rows x 64 bf16
+    plan_tiles(p, 256, GLU ? 128 : 256);
+    auto kern = gemm_bf16_persist128_kernel<GLU, DUAL, KEEP>;
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(256), lds, st, p);
+    return hipGetLastError();
+}
+// the four-wave kernel also wants whole column tiles (its weight-row addresses are not clamped)
+inline bool persist128_ok(const GemmParams& g, bool glu) { return g.N % (glu ? 128 : 256) == 0; }
 inline bool persist_ok(const GemmParams& g, bool glu) {
     GemmParams t = g;
     plan_tiles(t, 256, glu ? 128 : 256);
@@ -1299,10 +1580,11 @@ hipError_t launch_grouped_gemm(const GroupedGemm& q, hipStream_t st) {
         const bool ring = pipelined_ok(g, q.row_index ? static_cast<size_t>(q.a_rows) : static_cast<size_t>(q.M));
         if (ring && persist_ok(g, q.epilogue != GEMM_PLAIN)) {
             const int n_cu = cu_count();
+            const bool wide = persist128_ok(g, q.epilogue != GEMM_PLAIN);
             switch (q.epilogue) {
-                case GEMM_PLAIN: return launch_bf16_persist64<false>(g, st, n_cu);
-                case GEMM_SWIGLU: return launch_bf16_persist64<true>(g, st, n_cu);
-                case GEMM_DUAL: return launch_bf16_persist64<true, true>(g, st, n_cu);
+                case GEMM_PLAIN: return wide ? launch_bf16_persist128<false>(g, st, n_cu) : launch_bf16_persist64<false>(g, st, n_cu);
+                case GEMM_SWIGLU: return wide ? launch_bf16_persist128<true>(g, st, n_cu) : launch_bf16_persist64<true>(g, st, n_cu);
+                case GEMM_DUAL: return wide ? launch_bf16_persist128<true, true>(g, st, n_cu) : launch_bf16_persist64<true, true>(g, st, n_cu);
             }
         }
         switch (q.epilogue) {
@@ -1340,12 +1622,16 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
         if (gather_rows && !ffn_can_gather(c)) return hipErrorInvalidValue;
         const bool pipe1 = pipelined_ok(g1, gather_rows ? static_cast<size_t>(c.T) : static_cast<size_t>(c.capacity));
         const int n_cu = cu_count();
-        if (pipe1 && persist_ok(g1, true)) err = launch_bf16_persist64<true>(g1, st, n_cu);
+        if (pipe1 && persist_ok(g1, true)) {
+            if (!persist128_ok(g1, true)) err = launch_bf16_persist64<true>(g1, st, n_cu);
+            else err = g1.C3 ? launch_bf16_persist128<true, false, true>(g1, st, n_cu) : launch_bf16_persist128<true>(g1, st, n_cu);
+        }
         else err = (pipe1 && !g1.C3) ? launch_bf16_ring<true, 4>(g1, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g1, st);
         if (err != hipSuccess) return err;
         if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
         if (!pipelined_ok(g2, c.capacity)) return launch_bf16<128, 128, 64, 2, 2, false, 1>(g2, st);
-        if (persist_ok(g2, false)) return launch_bf16_persist64<false>(g2, st, n_cu);
+        if (persist_ok(g2, false))
+            return persist128_ok(g2, false) ? launch_bf16_persist128<false>(g2, st, n_cu) : launch_bf16_persist64<false>(g2, st, n_cu);
         return launch_bf16_ring<false, 4>(g2, st);
     }
     if (gather_rows) return hipErrorInvalidValue;

@@ -37,11 +37,15 @@ SMALL = {
     "cfg3s": lambda: I.small_variant(I.CONFIGS["cfg3"], T=900, d=1024, H=1032),
     "cfg4s": lambda: I.small_variant(I.CONFIGS["cfg4"], T=1500, d=1024, H=328),
     "cfg5s": lambda: I.small_variant(I.CONFIGS["cfg5"], T=700, H=200),     # full d: 64 pooled features for 64 global experts
+    # widths on whole column tiles of both GEMMs (H % 128 == 0, d % 256 == 0): the four-wave persistent kernel,
+    # with the token rows gathered inside GEMM-1 in the fused call
+    "cfg2w": lambda: I.small_variant(I.CONFIGS["cfg2"], T=1300, d=512, H=640),
+    "cfg5w": lambda: I.small_variant(I.CONFIGS["cfg5"], T=900, H=256),
 }
 
 
 @pytest.mark.parametrize("name,mode", [("cfg1", TCR), ("cfg1", ECR), ("cfg1", BIDIR), ("cfg2s", TCR), ("cfg3s", ECR),
-                                       ("cfg4s", BIDIR), ("cfg5s", BIDIR)])
+                                       ("cfg4s", BIDIR), ("cfg5s", BIDIR), ("cfg2w", TCR), ("cfg5w", BIDIR)])
 def test_layer_stage_by_stage_and_fused(H, oracle, name, mode):
     shape = SMALL[name]()
     _say(f"case {name} mode={mode} T={shape.T} d={shape.d} E={shape.E} C={shape.capacity} H={shape.H}")
@@ -175,6 +179,10 @@ def test_select_external_scores(H, oracle, T, E, k, C, levels):
     # while it is still inside the first tile's prologue (GEMM-1 in the first case, GEMM-2 in the second)
     (I.DT_BF16, 8, 2048, 128, 1024, [2048, 1500, 2048, 300, 2047, 1025, 2048, 1800]),
     (I.DT_BF16, 8, 2048, 2048, 128, [2048, 1500, 0, 300, 2047, 1025, 2048, 1800]),
+    # whole column tiles in both GEMMs (the four-wave kernel): an odd number of k-tiles, an empty expert between
+    # live ones, one-row and one-past-a-tile experts; then more live tiles than CUs with a long second contraction
+    (I.DT_BF16, 6, 900, 768, 1152, [900, 0, 513, 1, 899, 256]),
+    (I.DT_BF16, 8, 1100, 256, 2816, [1100, 700, 1, 1024, 0, 1025, 300, 1100]),
 ])
 def test_expert_ffn(H, oracle, dtype, E, C, d, H_, counts):
     _say(f"case ffn dtype={dtype} E={E} C={C} d={d} H={H_} counts={counts}")
