@@ -1,19 +1,24 @@
 #!/usr/bin/env python3
 """Benchmark of the ETR MoE-layer forward on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2] [--capacity C] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg5] [--capacity C]
+                    [--no-others] [--no-cpu-baseline]
 
 A "step" is one pass of the whole hot path (route -> select -> dispatch -> expert FFN ->
 combine, one etr_moe_forward call) over one batch of seeded synthetic tokens that is
-already resident in HBM.  Prints ONE JSON line: tokens/s of the whole layer, the roofline
-position of the dominant kernel (the gate/up MFMA grouped GEMM) measured with HIP events
-on the launch stream, per-stage times, and the CPU oracle timed on a bounded sample.
+already resident in HBM.  Prints ONE JSON line.  The headline (value, roofline, cpu_baseline)
+is the largest single-GPU workload, cfg5; the other bf16 workloads (cfg2, cfg3 and cfg4 at
+each value of its capacity schedule) are timed after it, with fewer steps, and reported under
+"other_workloads" of the same line.  Per workload: tokens/s of the whole layer, the two FFN
+GEMMs against the bf16 MFMA peak (durations from HIP events recorded by the library on the
+launch stream), and the HBM-bound stages called on their own against the HBM peak.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -24,11 +29,20 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3       # fp32 vector
 PEAK_HBM_GBS = 8000.0
+INFINITY_CACHE_BYTES = 256e6  # a stage whose working set fits here is not an HBM measurement
 
-# HBM bytes per launch of the dominant kernel (FFN gate/up GEMM), measured with rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE on this very command and scaled by what a plain 1 GiB copy reads on the same counters (fetch x2.0,
-# write x1.0); the summaries are profiles/moe_forward_<cfg>_kernels_and_traffic.txt. None = not measured.
-MEASURED_TRAFFIC_BYTES = {"cfg2": 1034.2e6 + 136.6e6, "cfg5": 13652.0e6 + 719.5e6}
+
+def profiled_traffic(config: str):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
+    what a plain copy reads on the same counters) and kept in profiles/: (bytes, file) or (None, None).  The figure
+    is quoted from that file, not measured by this run."""
+    path = os.path.join(ROOT, "profiles", f"moe_forward_{config}_kernels_and_traffic.txt")
+    try:
+        with open(path) as f:
+            m = re.search(r"^# dominant_kernel_traffic_bytes_per_launch:\s*([0-9.eE+]+)", f.read(), re.M)
+        return (float(m.group(1)), os.path.relpath(path, ROOT)) if m else (None, None)
+    except OSError:
+        return None, None
 
 
 def _to_np(t):
@@ -38,26 +52,38 @@ def _to_np(t):
     return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
 
 
-def cpu_baseline(shape, cfg, tensors, budget_tokens: int):
-    """Times the oracle (as it stands) on the host cores: routing on all T tokens, the expert
-    FFN and the weighted sum on the first `budget_tokens` tokens, extrapolated linearly in tokens."""
+def cpu_baseline(shape, cfg, tensors, budget_tokens: int, single_thread_tokens: int):
+    """Times the oracle (as it stands) on the host cores: routing on all T tokens, the expert FFN and the
+    weighted sum on the first `budget_tokens` tokens, extrapolated linearly in tokens; then the same on ONE
+    thread with a smaller token sample."""
     import numpy as np
     from oracle import etr_ref
     host = {k: _to_np(v) for k, v in tensors.items()}
-    n = min(budget_tokens, shape.T)
-    t0 = time.perf_counter()
-    score, _ = etr_ref.route(host["x"], host["w_emb"], shape.D, shape.dtype, cfg.cos)
-    etr_ref.select(score, shape.k, cfg.capacity, cfg.mode)
-    t_routing = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    etr_ref.moe_forward(host["x"], host["w_emb"], host["w_gate"], host["w_up"], host["w_down"], D=shape.D, k=shape.k,
-                        capacity=cfg.capacity, dtype=shape.dtype, mode=cfg.mode, cos_mode=cfg.cos,
-                        tokens=np.arange(n, dtype=np.int32))
-    t_sample = time.perf_counter() - t0
-    t_full = t_routing + max(t_sample - t_routing, 0.0) * (shape.T / n)
-    return {"value": shape.T / t_full, "unit": "tokens/s", "cores": etr_ref.num_threads(), "kind": "oracle",
-            "sample": f"routing on all {shape.T} tokens ({t_routing:.2f} s); FFN+combine on the first {n} tokens "
-                      f"({t_sample - t_routing:.2f} s), extrapolated linearly to {shape.T}"}
+
+    def leg(n):
+        n = min(n, shape.T)
+        t0 = time.perf_counter()
+        score, _ = etr_ref.route(host["x"], host["w_emb"], shape.D, shape.dtype, cfg.cos)
+        etr_ref.select(score, shape.k, cfg.capacity, cfg.mode)
+        t_routing = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        etr_ref.moe_forward(host["x"], host["w_emb"], host["w_gate"], host["w_up"], host["w_down"], D=shape.D, k=shape.k,
+                            capacity=cfg.capacity, dtype=shape.dtype, mode=cfg.mode, cos_mode=cfg.cos,
+                            tokens=np.arange(n, dtype=np.int32))
+        t_sample = time.perf_counter() - t0
+        t_full = t_routing + max(t_sample - t_routing, 0.0) * (shape.T / n)
+        return shape.T / t_full, (f"routing on all {shape.T} tokens ({t_routing:.2f} s); FFN+combine on the first {n} "
+                                  f"tokens ({max(t_sample - t_routing, 0.0):.2f} s), extrapolated linearly to {shape.T}")
+
+    cores = etr_ref.num_threads()
+    value, sample = leg(budget_tokens)
+    etr_ref.set_num_threads(1)
+    try:
+        v1, s1 = leg(single_thread_tokens)
+    finally:
+        etr_ref.set_num_threads(cores)
+    return {"value": value, "unit": "tokens/s", "cores": cores, "kind": "oracle", "sample": sample,
+            "single_thread": {"value": v1, "unit": "tokens/s", "cores": 1, "sample": s1}}
 
 
 def bench_backward(args, shape, cfg, t, dev):
@@ -128,41 +154,15 @@ def bench_backward(args, shape, cfg, t, dev):
     }), flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="cfg2")
-    ap.add_argument("--capacity", type=int, default=None, help="override the capacity (cfg4's schedule)")
-    ap.add_argument("--cpu-tokens", type=int, default=8192, help="tokens of the oracle's FFN sample")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--backward", action="store_true",
-                    help="time etr_moe_backward instead of the forward (not the headline metric; no cpu_baseline)")
-    ap.add_argument("--saved", action="store_true",
-                    help="with --backward: hand over the pre-activations kept by etr_moe_forward_train (no recomputation)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1")
-
+def measure_forward(shape, cfg, t, steps, warmup, dev):
+    """Times `steps` fused forward calls (only the dominant kernel bracketed by events), then a second pass with
+    every stage boundary marked, then the HBM-bound stages on their own.  Returns a dict of raw figures."""
     import torch
     from paper_2406_00023_amd import binding as B
     from paper_2406_00023_amd import inputs as I
 
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
-    B.load_library()
-    shape = I.CONFIGS[args.config]
-    cfg = B.make_config(shape, capacity=args.capacity)
-    dev = "cuda:0"
-    torch.cuda.set_device(0)
-    t = I.make_inputs(shape, dev)
     out = torch.empty(shape.T, shape.d, dtype=shape.torch_dtype, device=dev)
     counts = torch.zeros(shape.E, dtype=torch.int32, device=dev)
-    if args.backward:
-        return bench_backward(args, shape, cfg, t, dev)
     ws = B.alloc_workspace(B.etr_workspace_bytes(cfg), dev)
 
     def step(events=None):
@@ -172,24 +172,28 @@ def main():
             B.etr_moe_forward_profiled(cfg, t["x"], t["w_emb"], t["w_gate"], t["w_up"], t["w_down"], out, ws, events,
                                        counts=counts)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     # timed region: K steps; only the dominant kernel (FFN gate/up GEMM) is bracketed by events
     # (boundaries 3 and 4), because every recorded event costs a few microseconds of stream time
-    gemm_events = [B.StageEvents(only=(3, 4)) for _ in range(args.steps)]
+    gemm_events = [B.StageEvents(only=(3, 4)) for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(steps):
         step(gemm_events[i])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    t_gemm1_ms = sum(B.elapsed_ms(ev, 3, 4) for ev in gemm_events) / args.steps
+    t_gemm1_ms = sum(B.elapsed_ms(ev, 3, 4) for ev in gemm_events) / steps
     # second pass, all stage boundaries marked: the per-stage breakdown (not part of `value`)
-    events = [B.StageEvents() for _ in range(args.steps)]
-    for i in range(args.steps):
+    events = [B.StageEvents() for _ in range(steps)]
+    for i in range(steps):
         step(events[i])
     torch.cuda.synchronize()
+    stage = [0.0] * (B.N_STAGE_EVENTS - 1)
+    for ev in events:
+        for i, ms in enumerate(ev.stage_ms()):
+            stage[i] += ms / steps
 
     # the HBM-bound stages once more on their own (the fused call folds the rearrangement into GEMM-1
     # and the stage events include launch gaps): plain hipEvent timing of back-to-back stage calls
@@ -219,63 +223,137 @@ def main():
         "dispatch": time_stage(lambda: B.etr_dispatch(cfg, t["x"], slot_token, counts, xp)),
         "combine": time_stage(lambda: B.etr_combine(cfg, xp, gate, slot_of, out)),
     }
-
-    ms_per_step = 1e3 * elapsed / args.steps
-    stage = [0.0] * (B.N_STAGE_EVENTS - 1)
-    for ev in events:
-        for i, ms in enumerate(ev.stage_ms()):
-            stage[i] += ms / args.steps
     rows = int(counts.sum().item())
     elt = 4 if shape.dtype == I.DT_F32 else 2
-    # dominant kernel: FFN GEMM-1 (gate and up projections + SwiGLU), 4*d*H flop per kept row
-    flops_gemm1 = 4.0 * rows * shape.d * shape.H
-    t_gemm1 = t_gemm1_ms * 1e-3
-    peak = PEAK_BF16_TFLOPS if shape.dtype == I.DT_BF16 else PEAK_F32_TFLOPS
-    achieved = flops_gemm1 / t_gemm1 / 1e12
-    stages = {name: round(ms, 5) for name, ms in zip(B.STAGE_NAMES, stage)}
-    # algorithmic bytes of the HBM-bound stages -> GB/s (for the report; the roofline object is the GEMM's)
-    TE = shape.T * shape.E
+    TE = T * E
     bytes_alg = {
-        "route": shape.T * shape.d * elt + 2 * TE * 4,
-        "dispatch": rows * (2 * shape.d * elt + 4),
-        "combine": rows * shape.d * elt + shape.T * shape.d * elt + TE * 8,
+        "route": T * d * elt + 2 * TE * 4,
+        "dispatch": rows * (2 * d * elt + 4),
+        "combine": rows * d * elt + T * d * elt + TE * 8,
     }
-    hbm = {k: {"us": round(alone[k] * 1e3, 2), "GBs": round(v / (alone[k] * 1e-3) / 1e9, 1),
-               "frac_of_8TBs": round(v / (alone[k] * 1e-3) / 1e9 / PEAK_HBM_GBS, 3)} for k, v in bytes_alg.items()}
+    hbm = {}
+    for k, v in bytes_alg.items():
+        gbs = v / (alone[k] * 1e-3) / 1e9
+        hbm[k] = {"us": round(alone[k] * 1e3, 2), "algorithmic_MB": round(v / 1e6, 1), "GBs": round(gbs, 1)}
+        if v > INFINITY_CACHE_BYTES:
+            hbm[k]["frac_of_8TBs"] = round(gbs / PEAK_HBM_GBS, 3)
+        else:   # back-to-back calls on a working set that stays in the 256 MB Infinity Cache: not an HBM figure
+            hbm[k]["frac_of_8TBs"] = None
+            hbm[k]["note"] = "working set fits the Infinity Cache; latency-bound, no HBM fraction quoted"
     hbm["select"] = {"us": round(alone["select"] * 1e3, 2)}
-    flops_gemm2 = 2.0 * rows * shape.d * shape.H
+    peak = PEAK_BF16_TFLOPS if shape.dtype == I.DT_BF16 else PEAK_F32_TFLOPS
+    flops_gemm1 = 4.0 * rows * d * shape.H
+    flops_gemm2 = 2.0 * rows * d * shape.H
+    gemm1 = flops_gemm1 / (t_gemm1_ms * 1e-3) / 1e12
+    gemm2 = flops_gemm2 / (stage[4] * 1e-3) / 1e12 if stage[4] > 0 else None
+    del ws, xp
+    return dict(ms_per_step=1e3 * elapsed / steps, tokens_per_s=T / (elapsed / steps), rows=rows, peak=peak,
+                flops_gemm1=flops_gemm1, gemm1_TFLOPs=gemm1, gemm2_TFLOPs=gemm2,
+                stage_ms={name: round(ms, 5) for name, ms in zip(B.STAGE_NAMES, stage)}, stage_alone=hbm,
+                algorithmic_bytes_gemm1=elt * (2.0 * E * shape.H * d + rows * d + rows * shape.H))
+
+
+def workload_name(shape, cfg):
+    return (f"{shape.name}: T={shape.T} d={shape.d} E={shape.E} D={shape.D} k={shape.k} capacity={cfg.capacity} "
+            f"H={shape.H} mode={('TCR', 'ECR', 'BIDIR', 'TCR_RANK', 'BIDIR_STRICT')[cfg.mode]} tokens={shape.recipe}")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="cfg5", help="headline workload (default: the largest single-GPU one)")
+    ap.add_argument("--capacity", type=int, default=None, help="override the capacity (cfg4's schedule)")
+    ap.add_argument("--no-others", action="store_true", help="time the headline workload only")
+    ap.add_argument("--other-steps", type=int, default=20, help="timed steps of each of the other workloads")
+    ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the oracle's FFN sample (all host cores)")
+    ap.add_argument("--cpu-tokens-1", type=int, default=256, help="tokens of the oracle's FFN sample on one thread")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--backward", action="store_true",
+                    help="time etr_moe_backward instead of the forward (not the headline metric; no cpu_baseline)")
+    ap.add_argument("--saved", action="store_true",
+                    help="with --backward: hand over the pre-activations kept by etr_moe_forward_train (no recomputation)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1")
+
+    import torch
+    from paper_2406_00023_amd import binding as B
+    from paper_2406_00023_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    B.load_library()
+    shape = I.CONFIGS[args.config]
+    cfg = B.make_config(shape, capacity=args.capacity)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    t = I.make_inputs(shape, dev)
+    if args.backward:
+        return bench_backward(args, shape, cfg, t, dev)
+
+    m = measure_forward(shape, cfg, t, args.steps, args.warmup, dev)
+    bf16 = shape.dtype == I.DT_BF16
+    traffic, traffic_file = profiled_traffic(args.config) if args.capacity is None else (None, None)
     res = {
         "metric": "MoE-layer tokens/sec on 1 MI355X",
-        "value": shape.T / (elapsed / args.steps),
+        "value": m["tokens_per_s"],
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": m["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if shape.dtype == I.DT_BF16 else "f32",
+        "dtype": "bf16" if bf16 else "f32",
         "data": "synthetic",
-        "config": {"workload": f"{shape.name}: T={shape.T} d={shape.d} E={shape.E} D={shape.D} k={shape.k} "
-                               f"capacity={cfg.capacity} H={shape.H} mode={('TCR', 'ECR', 'BIDIR')[cfg.mode]} "
-                               f"tokens={shape.recipe}",
-                   "kept_rows": rows},
-        "roofline": {"kernel": "gemm_bf16_persist64_kernel<GLU> (FFN gate/up projections + SwiGLU)"
-                     if shape.dtype == I.DT_BF16 else "gemm_f32_kernel<GLU>",
-                     "bound": "mfma" if shape.dtype == I.DT_BF16 else "alu",
-                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if args.capacity is None else None,
-                     "algorithmic_flop": flops_gemm1,
-                     "algorithmic_bytes": elt * (2.0 * shape.E * shape.H * shape.d + rows * shape.d
-                                                 + rows * shape.H)},
-        "stage_ms": stages,
-        "stage_alone": hbm,
-        "ffn_down_TFLOPs": flops_gemm2 / (stage[4] * 1e-3) / 1e12 if stage[4] > 0 else None,
+        "config": {"workload": workload_name(shape, cfg), "kept_rows": m["rows"]},
+        "roofline": {"kernel": "gemm_bf16_persistent_kernel<GLU> (FFN gate/up projections + SwiGLU)" if bf16
+                     else "gemm_f32_kernel<GLU>",
+                     "bound": "mfma" if bf16 else "alu",
+                     "achieved": m["gemm1_TFLOPs"], "peak": m["peak"], "unit": "TFLOP/s",
+                     "frac": m["gemm1_TFLOPs"] / m["peak"],
+                     "traffic": traffic,
+                     "traffic_source": (f"quoted from {traffic_file} (rocprofv3 FETCH_SIZE x2.0 + WRITE_SIZE x1.0 per launch), "
+                                        "not measured by this run") if traffic_file else None,
+                     "algorithmic_flop": m["flops_gemm1"],
+                     "algorithmic_bytes": m["algorithmic_bytes_gemm1"]},
+        "stage_ms": m["stage_ms"],
+        "stage_alone": m["stage_alone"],
+        "ffn_down_TFLOPs": m["gemm2_TFLOPs"],
+        "ffn_down_frac": m["gemm2_TFLOPs"] / m["peak"] if m["gemm2_TFLOPs"] else None,
     }
     if args.calibrate_copy:
         a = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
         b = torch.empty_like(a)
         b.copy_(a)
         torch.cuda.synchronize()
+        del a, b
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(shape, cfg, t, args.cpu_tokens)
+        res["cpu_baseline"] = cpu_baseline(shape, cfg, t, args.cpu_tokens, args.cpu_tokens_1)
+    if not args.no_others and args.capacity is None:
+        others = []
+        del t
+        torch.cuda.empty_cache()
+        for name in ("cfg2", "cfg3", "cfg4", "cfg5"):
+            if name == args.config:
+                continue
+            sh = I.CONFIGS[name]
+            tt = I.make_inputs(sh, dev)
+            for cap in (sh.capacity_sweep or (None,)):
+                c = B.make_config(sh, capacity=cap)
+                mm = measure_forward(sh, c, tt, args.other_steps, 5, dev)
+                others.append({
+                    "workload": workload_name(sh, c), "kept_rows": mm["rows"], "steps": args.other_steps,
+                    "ms_per_step": round(mm["ms_per_step"], 4), "tokens_per_s": round(mm["tokens_per_s"], 1),
+                    "ffn_gate_up_TFLOPs": round(mm["gemm1_TFLOPs"], 1),
+                    "ffn_gate_up_frac": round(mm["gemm1_TFLOPs"] / mm["peak"], 4),
+                    "ffn_down_TFLOPs": round(mm["gemm2_TFLOPs"], 1) if mm["gemm2_TFLOPs"] else None,
+                    "ffn_down_frac": round(mm["gemm2_TFLOPs"] / mm["peak"], 4) if mm["gemm2_TFLOPs"] else None,
+                    "stage_ms": mm["stage_ms"], "stage_alone": mm["stage_alone"]})
+            del tt
+            torch.cuda.empty_cache()
+        res["other_workloads"] = others
     print(json.dumps(res), flush=True)
 
 

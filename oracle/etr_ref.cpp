@@ -745,5 +745,13 @@ int etr_ref_num_threads(void) {
     return 1;
 #endif
 }
+// Number of OpenMP threads the loops above run on from now on (timing on one core; no arithmetic changes).
+void etr_ref_set_num_threads(int n) {
+#ifdef _OPENMP
+    omp_set_num_threads(n < 1 ? 1 : n);
+#else
+    (void)n;
+#endif
+}
 
 }  // extern "C"

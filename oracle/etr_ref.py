@@ -62,6 +62,11 @@ def num_threads() -> int:
     return int(lib().etr_ref_num_threads())
 
 
+def set_num_threads(n: int) -> None:
+    """Threads the oracle's loops use from now on (for the single-core timing of the benchmark)."""
+    lib().etr_ref_set_num_threads(int(n))
+
+
 def double_to_bf16(v: float) -> int:
     return int(lib().etr_ref_double_to_bf16(float(v)))
 

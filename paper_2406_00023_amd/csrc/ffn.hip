@@ -1123,13 +1123,17 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist64_kernel(GemmParams p) 
 // Fragment reads of the next substep are issued after the first four MFMAs of the current one, so the wait in
 // front of a substep's first MFMA only ever covers reads that are 12 MFMAs old.
 // ---------------------------------------------------------------------------------------
-template <bool GLU, bool DUAL = false, bool KEEP = false>
-__global__ __launch_bounds__(256) void gemm_bf16_persist128_kernel(GemmParams p) {
+template <bool GLU, bool DUAL = false, bool KEEP = false, int NW = 4, int SP = 2>
+__global__ __launch_bounds__(NW * 64) void gemm_bf16_persist128_kernel(GemmParams p) {
     static_assert(!KEEP || (GLU && !DUAL), "the pre-activations are kept by the SwiGLU epilogue only");
+    static_assert(NW == 4 || NW == 8, "one or two waves per SIMD");
+    static_assert(SP >= 1 && SP <= 3, "substeps the copies of a k-tile are spread over");
     constexpr int BM = 256, BR = 256, CPR = 8, SWZ = 1;
     constexpr int BN = GLU ? 128 : 256;
     constexpr int STAGE = (BM + BR) * CPR;               // uint4 per LDS buffer (64 KiB)
-    constexpr int WN = 2, NW = 4, TB = 4, NCP = 8;       // NCP: groups of 8 rows each wave copies per operand
+    constexpr int WN = NW / 2, TB = 8 / WN;              // wave grid 2 x WN; weight fragments per wave and k-substep
+    constexpr int NCP = 32 / NW;                         // groups of 8 rows each wave copies per operand
+    constexpr int WROWS = 8 * NCP;                       // staged rows of each operand a wave copies
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     uint4* lds = reinterpret_cast<uint4*>(lds_raw);
     __shared__ int pre[kMaxSuper + 1];
@@ -1145,7 +1149,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist128_kernel(GemmParams p)
 
     const int MG = (p.MT + p.SM - 1) / p.SM, NG = (p.NT + p.SN - 1) / p.SN;
     const int S = p.E * MG * NG;
-    live_tile_prefix<256>(p, BM, MG, NG, pre, wave_tot);
+    live_tile_prefix<NW * 64>(p, BM, MG, NG, pre, wave_tot);
     const int total = pre[S];
     const int GS = gridDim.x >> 3;                       // tiles per group = workgroups per XCD
     const int xcd = blockIdx.x & 7, slot_l = blockIdx.x >> 3;
@@ -1153,13 +1157,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist128_kernel(GemmParams p)
     struct Tile {
         int e, m0, n0, count, KT;
         uint64_t Abase, Bbase;                           // wave-uniform; Bbase includes the wave's first weight row
-        uint32_t offA[NCP];                              // per-lane byte offsets of the 8 token-row groups
+        uint32_t offA[NCP];                              // per-lane byte offsets of the wave's token-row groups
     };
     // row group i of this wave: rows rr0 + 8 i, chunk c0 ^ 4 (i & 1) of the swizzle (8 rows further on flips bit 2)
-    const int rr0 = wave * (NCP * 8) + (lane >> 3);
+    const int rr0 = wave * WROWS + (lane >> 3);
     const int c0 = (lane & 7) ^ ((rr0 >> SWZ) & 7);
-    const uint32_t laneB[2] = {(static_cast<uint32_t>(lane >> 3) * KCB + c0) * 16u,
-                               (static_cast<uint32_t>(lane >> 3) * KCB + (c0 ^ 4)) * 16u};
+    const uint32_t laneB[2] = {(static_cast<uint32_t>(lane >> 3) * KCB + ((lane & 7) ^ ((lane >> 4) & 7))) * 16u,
+                               (static_cast<uint32_t>(lane >> 3) * KCB + ((lane & 7) ^ ((lane >> 4) & 7) ^ 4)) * 16u};
     const uint64_t strideB8 = static_cast<uint64_t>(8) * KCB * 16;      // 8 weight rows further on
 
     auto decode = [&](int q, Tile& t) {                  // scalar part of the tile with list index q
@@ -1178,17 +1182,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist128_kernel(GemmParams p)
         t.count = group_rows(p, e);
         t.KT = group_k(p, e) / 64;
         t.Abase = reinterpret_cast<uint64_t>(p.A) + (gather ? 0 : static_cast<uint64_t>(e) * p.capacity * KCA * 16);
-        // this wave's 64 staged weight rows: GLU stages 128 gate rows, then the 128 up rows of the same columns
-        const int nrow = t.n0 + (GLU ? (wave & 1) * 64 : wave * 64);
+        // this wave's staged weight rows: GLU stages 128 gate rows, then the 128 up rows of the same columns
+        const int nrow = t.n0 + (GLU ? (wave % (NW / 2)) * WROWS : wave * WROWS);
         t.Bbase = reinterpret_cast<uint64_t>((GLU && wave >= NW / 2) ? p.B1 : p.B0) +
                   (static_cast<uint64_t>(e) * p.N + nrow) * KCB * 16;
     };
-    // asynchronous copy of the tile's row indices (this wave's 64 rows) into slot `slot`
+    // asynchronous copy of the tile's row indices into slot `slot` (waves 0..3, 64 rows each)
     auto request_rows = [&](const Tile& t, int slot) {
-        int m = t.m0 + wave * 64 + lane;
-        m = m < t.count ? m : t.count - 1;               // rows past the count replay a valid row; never stored
-        const int32_t* src = p.row_index + static_cast<size_t>(t.e) * p.capacity + m;
-        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(&row_ids[slot][wave * 64]), 4, 0, 0);
+        if (wave < 4) {
+            int m = t.m0 + wave * 64 + lane;
+            m = m < t.count ? m : t.count - 1;           // rows past the count replay a valid row; never stored
+            const int32_t* src = p.row_index + static_cast<size_t>(t.e) * p.capacity + m;
+            __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(&row_ids[slot][wave * 64]), 4, 0, 0);
+        }
     };
     // per-lane offsets of the token rows; with `gather` the indices have landed in slot `slot`
     auto finish = [&](Tile& t, int slot) {
@@ -1244,6 +1250,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist128_kernel(GemmParams p)
         for (int j = 0; j < TB; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
     };
+    // Which copies go out behind MFMA row `i` of a substep.  Token-row groups: all in the releasing (fourth)
+    // substep, NCP / 4 per row.  Weight-row groups: SP = 1 in the fourth substep as well; SP = 2 in the first
+    // substep of the next step; SP = 3 half there, half in the second substep.
+    constexpr int APR = NCP / 4 > 0 ? NCP / 4 : 1;       // token-row groups per MFMA row (NW = 8: NCP = 4 -> 1)
+    auto copies_a = [&](uint64_t abase, const uint32_t* off, int buf, int i) {
+#pragma unroll
+        for (int c = 0; c < APR; ++c) copy_a(abase, off[i * APR + c], buf, i * APR + c);
+    };
+    auto copies_b = [&](uint64_t bbase, int buf, int i, int part, int parts) {   // behind row i of substep `part` of `parts`
+        if (parts == 1) {
+#pragma unroll
+            for (int c = 0; c < APR; ++c) copy_b(bbase, buf, i * APR + c);
+        } else if ((i & 1) == part) {                     // two substeps: the even rows carry the first half
+#pragma unroll
+            for (int c = 0; c < APR; ++c) copy_b(bbase, buf, part * (NCP / 2) + (i >> 1) * APR + c);
+        }
+    };
 
     int q = xcd * GS + slot_l;                           // first pass over the list
     if (q >= total) return;                              // uniform: nothing for this workgroup
@@ -1257,6 +1280,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist128_kernel(GemmParams p)
             request_rows(nxt, 1);
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, false));
+        __builtin_amdgcn_s_barrier();                    // NW = 8: the indices were fetched by other waves
     }
     finish(cur, 0);
     int g = 0;                                           // global step: buffer g & 1
@@ -1302,24 +1326,31 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist128_kernel(GemmParams p)
 #pragma unroll
             for (int i = 0; i < NCP; ++i) offs[i] = from_next ? nxt.offA[i] : cur.offA[i];
             const int buf = g & 1;
-            // substep 0, with the weight rows of k-tile g + 1 into the other buffer
+            // substep 0 (SP >= 2: with weight rows of k-tile g + 1 into the other buffer)
             __builtin_amdgcn_sched_barrier(0);
             mfma_row(0, 0);
-            copy_b(lateB, buf ^ 1, 0); copy_b(lateB, buf ^ 1, 1);
+            if constexpr (SP >= 2) copies_b(lateB, buf ^ 1, 0, 0, SP - 1);
             __builtin_amdgcn_sched_barrier(0);
             load_frags(1, buf, 1);
 #pragma unroll
             for (int i = 1; i < 4; ++i) {
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_row(0, i);
-                copy_b(lateB, buf ^ 1, 2 * i); copy_b(lateB, buf ^ 1, 2 * i + 1);
+                if constexpr (SP >= 2) copies_b(lateB, buf ^ 1, i, 0, SP - 1);
             }
-            // substeps 1 and 2
+            // substep 1 (SP = 3: with the other half of those weight rows)
             __builtin_amdgcn_sched_barrier(0);
             mfma_row(1, 0);
+            if constexpr (SP == 3) copies_b(lateB, buf ^ 1, 0, 1, 2);
             __builtin_amdgcn_sched_barrier(0);
             load_frags(0, buf, 2);
-            mfma_row(1, 1); mfma_row(1, 2); mfma_row(1, 3);
+#pragma unroll
+            for (int i = 1; i < 4; ++i) {
+                if constexpr (SP == 3) __builtin_amdgcn_sched_barrier(0);
+                mfma_row(1, i);
+                if constexpr (SP == 3) copies_b(lateB, buf ^ 1, i, 1, 2);
+            }
+            // substep 2
             __builtin_amdgcn_sched_barrier(0);
             mfma_row(0, 0);
             __builtin_amdgcn_sched_barrier(0);
@@ -1332,14 +1363,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist128_kernel(GemmParams p)
             // substep 3, with the token rows of k-tile g + 2 into the buffer just released
             __builtin_amdgcn_sched_barrier(0);
             mfma_row(1, 0);
-            copy_a(baseA, offs[0], buf, 0); copy_a(baseA, offs[1], buf, 1);
+            copies_a(baseA, offs, buf, 0);
+            if constexpr (SP == 1) copies_b(baseB, buf, 0, 0, 1);
             __builtin_amdgcn_sched_barrier(0);
             load_frags(0, buf ^ 1, 0);
 #pragma unroll
             for (int i = 1; i < 4; ++i) {
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_row(1, i);
-                copy_a(baseA, offs[2 * i], buf, 2 * i); copy_a(baseA, offs[2 * i + 1], buf, 2 * i + 1);
+                copies_a(baseA, offs, buf, i);
+                if constexpr (SP == 1) copies_b(baseB, buf, i, 0, 1);
             }
             __builtin_amdgcn_sched_barrier(0);
             lateB = baseB;
@@ -1491,15 +1524,15 @@ hipError_t launch_bf16_persist64(GemmParams p, hipStream_t st, int n_cu) {
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(512), lds, st, p);
     return hipGetLastError();
 }
-template <bool GLU, bool DUAL = false, bool KEEP = false>
+template <bool GLU, bool DUAL = false, bool KEEP = false, int NW = 4, int SP = 2>
 hipError_t launch_bf16_persist128(GemmParams p, hipStream_t st, int n_cu) {
     constexpr size_t lds = 2ull * 512 * 64 * 2;                             // two buffers of 256 + 256 rows x 64 bf16
     plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_persist128_kernel<GLU, DUAL, KEEP>;
+    auto kern = gemm_bf16_persist128_kernel<GLU, DUAL, KEEP, NW, SP>;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(256), lds, st, p);
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(NW * 64), lds, st, p);
     return hipGetLastError();
 }
 // the four-wave kernel also wants whole column tiles (its weight-row addresses are not clamped)
