@@ -11,6 +11,9 @@
  *    global state.  All arrays are dense, row-major, innermost index contiguous.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls only enqueue work; they never synchronise with the host.
+ *  - Stream capture: every entry point may be captured into a HIP graph, with one rule: the FIRST call of an
+ *    entry point for a given shape on a device must happen outside capture (it may raise a kernel's
+ *    dynamic-LDS limit and query the device once; later calls only launch kernels).
  *  - Arguments are checked on the host before anything is launched; on error
  *    nothing is launched and a status is returned:
  *      ETR_ERR_NULL         a required pointer is NULL
@@ -70,7 +73,9 @@ typedef struct {
 } etr_config;
 
 /* Bytes of device workspace for this config: etr_workspace_bytes is what
- * etr_moe_forward needs (it covers the two stage calls as well);
+ * etr_moe_forward needs (it covers the two stage calls as well; the permuted
+ * token buffer is part of it only where the fused call cannot gather the rows
+ * inside the first GEMM, i.e. fp32 and odd widths);
  * etr_select_workspace_bytes and etr_ffn_workspace_bytes are the smaller
  * amounts that etr_select and etr_expert_ffn need when called on their own.
  * Each returns 0 for an invalid config. Host-only, launches nothing. */

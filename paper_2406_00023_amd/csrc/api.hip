@@ -2,8 +2,55 @@
 // of the whole layer (Sec. Model Architecture, Eqs. 1-6).  Nothing here computes.
 #include <cmath>
 #include <cstdint>
+#include <mutex>
+#include <vector>
 
 #include "etr_internal.h"
+
+namespace etr {
+
+namespace {
+constexpr int kMaxDevices = 64;
+int current_device() {
+    int dev = 0;
+    return (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) ? dev : -1;
+}
+}  // namespace
+
+int cu_count() {
+    static std::mutex mu;
+    static int cached[kMaxDevices] = {};
+    const int dev = current_device();
+    if (dev < 0) return 256;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes) {
+    if (bytes <= 64 * 1024) return hipSuccess;
+    struct Entry { const void* kernel; int dev; size_t bytes; };
+    static std::mutex mu;
+    static std::vector<Entry> set;
+    const int dev = current_device();
+    std::lock_guard<std::mutex> lock(mu);
+    for (Entry& e : set)
+        if (e.kernel == kernel && e.dev == dev) {
+            if (e.bytes >= bytes) return hipSuccess;
+            const hipError_t err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+            if (err == hipSuccess) e.bytes = bytes;
+            return err;
+        }
+    const hipError_t err = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+    if (err == hipSuccess && dev >= 0) set.push_back({kernel, dev, bytes});
+    return err;
+}
+
+}  // namespace etr
 
 namespace {
 
@@ -48,7 +95,9 @@ ForwardWs forward_layout(const etr_config& c) {
     w.slot_token = take(EC * 4);
     w.counts = take(static_cast<size_t>(c.E) * 4);
     w.select = take(select_ws_bytes(c.T, c.E));
-    w.xp = take(EC * c.d * elt_bytes(c.dtype));
+    // the permuted token buffer exists only where the fused call really dispatches (fp32 / fall-back shapes):
+    // with the rows gathered inside GEMM-1 it is never written
+    w.xp = take(ffn_can_gather(c) ? 0 : EC * c.d * elt_bytes(c.dtype));
     w.yp = take(EC * c.d * elt_bytes(c.dtype));
     w.hidden = take(ffn_ws_bytes(c));
     w.total = off;

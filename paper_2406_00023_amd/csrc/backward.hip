@@ -8,9 +8,12 @@
 //   2. element-wise: h = SiLU(a) b, da = gate u b SiLU'(a), db = gate u SiLU(a), <u, h> per row (= d out / d gate)
 //   3. dXp = da Wg + db Wu;  dWd = (gate dOut_p)^T h;  dWg = da^T Xp;  dWu = db^T Xp
 //   4. dx[t] = sum_e dXp[e][slot] + sum_e dscore[t][e] * d score[t][e] / d x[t]  (softmax and Eq. 4 differentiated)
-// Every matrix product runs on the grouped "NT" kernel of ffn.hip (both operands contiguous along
-// the contraction), so operands whose contraction index is the slow one are transposed first:
-// the weights once per call, the per-row quantities straight out of the element-wise kernel.
+// Every matrix product runs on the grouped kernels of ffn.hip.  Operands whose contraction index is the
+// slow one in memory (Wd for u, Wg / Wu for dXp, the row-major activations for the weight gradients) are
+// read as they lie: the persistent kernel stages such k-tiles k-major in LDS and takes its MFMA fragments
+// through transposing LDS reads, so nothing is transposed in memory.  Only shapes that kernel does not take
+// (fp32, H % 64 != 0, fewer than 128 padded rows) go through the fall-back that transposes the weights once per
+// call and has the element-wise kernel write transposed copies of the per-row quantities.
 #include "etr_internal.h"
 
 namespace etr {
@@ -515,9 +518,7 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
     const int P = d / c.D;
     const size_t lds = (static_cast<size_t>(E) * P + E + 4 * (2 * P + 2 * E)) * 4;
     auto kern = dx_kernel<T>;
-    if (lds > 64 * 1024)
-        ETR_BW(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   static_cast<int>(lds)));
+    ETR_BW(ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds));
     hipLaunchKernelGGL(kern, dim3((Tn + 3) / 4), dim3(256), lds, st, static_cast<const T*>(x), w_emb, score, gate, slot_of,
                        dgate_part, static_cast<int>(cH), at(L.dxp), static_cast<T*>(dx), dgate, dscore,
                        Tn, d, E, c.D, C, static_cast<int>(c.cos), static_cast<int>(c.gate_norm), dxp_rows);

@@ -95,6 +95,14 @@ hipError_t launch_route_stats(const etr_config& c, const float* gate, const int3
 hipError_t launch_capacity_lower_bound(const etr_config& c, const float* score, float* dmax, int32_t* capacity,
                                        void* ws, hipStream_t st);
 
+// Host-side launch helpers (api.hip).  Both remember their answer per device, so a steady-state call issues no
+// runtime call besides its launches.
+//   cu_count            compute units of the current device (256 if the query fails)
+//   ensure_dynamic_lds  raises a kernel's dynamic-LDS limit to `bytes` unless a limit at least that large has
+//                       already been set for this (device, kernel); limits up to 64 KiB need no call at all
+int cu_count();
+hipError_t ensure_dynamic_lds(const void* kernel, size_t bytes);
+
 inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline size_t elt_bytes(int dtype) { return dtype == ETR_F32 ? 4 : 2; }
 

@@ -8,7 +8,7 @@
 // with an XOR swizzle, double-buffered.  GEMM-1 computes the gate and the up projection
 // of the same output tile so that SiLU(g)*u is its epilogue and the hidden activation
 // crosses HBM once, in bf16.  The kernel the layer launches is the persistent one
-// (gemm_bf16_persist_kernel: one workgroup per CU walks the live tiles, the copy ring runs
+// (gemm_bf16_persistent_kernel: one workgroup per CU walks the live tiles, the copies run on
 // across tile boundaries); the per-tile kernels size the grid for `capacity` and a workgroup
 // whose row tile starts past counts[e] exits at once.  Either way counts never leave the device.
 // fp32: plain LDS-tiled FMA kernels (parity path for small layers).
@@ -852,19 +852,6 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
     }
 }
 
-// ---------------------------------------------------------------------------------------
-// Persistent kernel with 64-wide k-tiles for row-major operands: the same tile list and the same
-// run-on across tile boundaries as above, but every copy instruction fetches whole 128-byte lines
-// (8 rows x 128 bytes instead of 16 rows x 64 bytes).  Measured on a copy-only loop over L2-resident
-// data the line-sized pieces move 1.6 times the bytes per cycle of the half-line ones, and in the
-// ring kernel above the copies, not the matrix pipe, set the cycle count.
-//
-// Two LDS buffers of 64 KiB.  Step g multiplies buffer g & 1 in four k-substeps; after the third
-// substep's fragments are in registers nobody reads that buffer any more, so behind one wait
-// (all copies landed, all own LDS reads done) and one barrier the eight copies of step g + 2 are
-// issued into it, interleaved with the MFMAs of the fourth substep.  They have three quarters of a
-// step to land.  Past the end of a tile step g + 2 is the first or second k-tile of the next one.
-// ---------------------------------------------------------------------------------------
 __device__ __forceinline__ int live_row_tiles(const GemmParams& p, int e, int mg, int BM) {
     const int mtv = (group_rows(p, e) + BM - 1) / BM;
     return min(max(mtv - mg * p.SM, 0), p.SM);
@@ -907,224 +894,41 @@ __device__ __forceinline__ void live_tile_prefix(const GemmParams& p, int BM, in
     __syncthreads();
 }
 
-template <bool GLU, bool DUAL = false>
-__global__ __launch_bounds__(512) void gemm_bf16_persist64_kernel(GemmParams p) {
-    constexpr int BM = 256, BR = 256, CPR = 8, SWZ = 1;
-    constexpr int BN = GLU ? 128 : 256;
-    constexpr int STAGE = (BM + BR) * CPR;               // uint4 per LDS buffer (64 KiB)
-    constexpr int WN = 4, NW = 8, TB = 2, NCP = 4;       // NCP: groups of 8 rows each wave copies per operand
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    uint4* lds = reinterpret_cast<uint4*>(lds_raw);
-    __shared__ int pre[kMaxSuper + 1];
-    __shared__ int wave_tot[NW];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
-    const int r32 = lane & 31, half = lane >> 5;
-    const int KCA = (p.lda ? p.lda : p.K) / 8, KCB = (p.ldb ? p.ldb : p.K) / 8;
-
-    const int MG = (p.MT + p.SM - 1) / p.SM, NG = (p.NT + p.SN - 1) / p.SN;
-    const int S = p.E * MG * NG;
-    live_tile_prefix(p, BM, MG, NG, pre, wave_tot);
-    const int total = pre[S];
-    const int GS = gridDim.x >> 3;                       // tiles per group = workgroups per XCD
-    const int xcd = blockIdx.x & 7, slot_l = blockIdx.x >> 3;
-
-    struct Tile {
-        int e, m0, n0, count, KT;
-        const char* Abase;
-        const char* Bbase;
-        uint32_t off[2 * NCP];
-    };
-    auto setup = [&](int q, Tile& t) {
-        int lo = 0, hi = S;                              // largest s with pre[s] <= q
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (pre[mid] <= q) lo = mid; else hi = mid;
-        }
-        const int s = __builtin_amdgcn_readfirstlane(lo);
-        const int u = __builtin_amdgcn_readfirstlane(q - pre[s]);
-        const int e = s / (MG * NG), r = s - e * (MG * NG);
-        const int mg = r % MG, ng = r / MG;
-        const int vm = live_row_tiles(p, e, mg, BM);
-        const int mt = mg * p.SM + u % vm, nt = ng * p.SN + u / vm;
-        t.e = e; t.m0 = mt * BM; t.n0 = nt * BN;
-        t.count = group_rows(p, e);
-        t.KT = group_k(p, e) / 64;
-        t.Abase = reinterpret_cast<const char*>(p.A) + (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KCA * 16);
-        t.Bbase = reinterpret_cast<const char*>((GLU && wave >= NW / 2) ? p.B1 : p.B0) + static_cast<size_t>(e) * p.N * KCB * 16;
-#pragma unroll
-        for (int i = 0; i < NCP; ++i) {
-            const int rr = (wave * NCP + i) * 8 + (lane >> 3);
-            const int c = (lane & 7) ^ ((rr >> SWZ) & 7);
-            int m = t.m0 + rr;
-            m = m < t.count ? m : t.count - 1;           // rows past the count replay a valid row; never stored
-            const int row = p.row_index ? min(max(p.row_index[static_cast<size_t>(e) * p.capacity + m], 0), p.a_rows - 1) : m;
-            t.off[i] = (static_cast<uint32_t>(row) * KCA + c) * 16u;
-            int n = t.n0 + (GLU ? (rr & 127) : rr);
-            n = n < p.N ? n : p.N - 1;
-            t.off[NCP + i] = (static_cast<uint32_t>(n) * KCB + c) * 16u;
-        }
-    };
-    // copy j (0..NCP-1: A row groups, NCP..2NCP-1: B row groups) of the k-tile at abase / bbase into buffer buf
-    auto issue_copy = [&](uint64_t abase, uint64_t bbase, uint32_t off, int buf, int j) {
-        uint4* dst = lds + buf * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
-        const uint64_t b64 = j < NCP ? abase : bbase;
-        const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
-        const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
-        const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
-        __builtin_amdgcn_global_load_lds((global_cptr)(base + off), (lds_ptr)dst, 16, 0, 0);
-    };
-
-    const int sw = (r32 >> SWZ) & 7;
-    int a_row[4], b_row[TB];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a_row[i] = (wm * 128 + i * 32 + r32) * CPR;
-#pragma unroll
-    for (int j = 0; j < TB; ++j) {
-        const int br = GLU ? ((j / (TB / 2)) * 128 + wn * (16 * TB) + (j % (TB / 2)) * 32) : (wn * (32 * TB) + j * 32);
-        b_row[j] = BM * CPR + (br + r32) * CPR;
-    }
-    int ck[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) ck[ks] = (ks * 2 + half) ^ sw;
-
-    f32x16 acc[4][TB];
-    bf16x8 fa[2][4], fb[2][TB];
-    auto load_frags = [&](int set, int buf, int ks) {
-        const uint4* base = lds + buf * STAGE + ck[ks];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
-#pragma unroll
-        for (int j = 0; j < TB; ++j) fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
-    };
-    auto mfma_block = [&](int set) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < TB; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
-    };
-
-    int q = xcd * GS + slot_l;                           // first pass over the list
-    if (q >= total) return;                              // uniform: nothing for this workgroup
-    Tile cur, nxt;
-    setup(q, cur);
-    int g = 0;                                           // global step: buffer g & 1
-    for (int t = 0; t < 2; ++t)                          // KT >= 2 is a launch condition
-#pragma unroll
-        for (int j = 0; j < 2 * NCP; ++j)
-            issue_copy(reinterpret_cast<uint64_t>(cur.Abase) + t * 128, reinterpret_cast<uint64_t>(cur.Bbase) + t * 128, cur.off[j], t, j);
-    __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * NCP, false));             // the first k-tile (copies retire in order)
-    __builtin_amdgcn_s_barrier();
-    load_frags(0, 0, 0);
-
-    for (;;) {
-        const int qn = q + 8 * GS;                       // same XCD, next round
-        const bool has_next = qn < total;
-        if (has_next) setup(qn, nxt);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < TB; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-        const int KT = cur.KT;
-        // Fetching part: k-tile kt + 2, which past KT is a k-tile of the next tile; the source is chosen with
-        // selects outside the unrolled MFMA sequences, which carry no branches.
-        const int kt_fetch = has_next ? KT : KT - 2;
-        int kt = 0;
-        for (; kt < kt_fetch; ++kt, ++g) {
-            const bool in_cur = kt + 2 < KT;
-            const int kf = in_cur ? kt + 2 : kt + 2 - KT;
-            const uint64_t baseA = reinterpret_cast<uint64_t>(in_cur ? cur.Abase : nxt.Abase) + kf * 128;
-            const uint64_t baseB = reinterpret_cast<uint64_t>(in_cur ? cur.Bbase : nxt.Bbase) + kf * 128;
-            uint32_t offs[2 * NCP];
-#pragma unroll
-            for (int j = 0; j < 2 * NCP; ++j) offs[j] = in_cur ? cur.off[j] : nxt.off[j];
-            const int buf = g & 1;
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(1, buf, 1);
-            mfma_block(0);
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(0, buf, 2);
-            mfma_block(1);
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(1, buf, 3);
-            mfma_block(0);
-            __builtin_amdgcn_sched_barrier(0);
-            // k-tile g + 1 has landed and this wave's reads of buffer buf are done; past the barrier that holds for all
-            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(0, buf ^ 1, 0);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-#pragma unroll
-                for (int j = 0; j < TB; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][j], fa[1][i], acc[i][j], 0, 0, 0);
-                    issue_copy(baseA, baseB, offs[i * TB + j], buf, i * TB + j);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        for (; kt < KT; ++kt, ++g) {                     // the last two steps of this workgroup's last tile: nothing to fetch
-            const int buf = g & 1;
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(1, buf, 1);
-            mfma_block(0);
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(0, buf, 2);
-            mfma_block(1);
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(1, buf, 3);
-            mfma_block(0);
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            if (kt + 1 < KT) load_frags(0, buf ^ 1, 0);
-            mfma_block(1);
-        }
-        // ---- epilogue of cur (the copies of the next tile are in flight)
-        constexpr int TO = GLU ? TB / 2 : TB;
-        if (GLU && !DUAL && p.C3)
-            store_blocks<GLU, DUAL, 4, TB, GLU && !DUAL>(p, acc, cur.e, cur.m0 + wm * 128, cur.n0 + wn * (32 * TO), cur.count, r32, half);
-        else
-            store_blocks<GLU, DUAL, 4, TB>(p, acc, cur.e, cur.m0 + wm * 128, cur.n0 + wn * (32 * TO), cur.count, r32, half);
-        if (!has_next) break;
-        cur = nxt;
-        q = qn;
-    }
-}
-
 // ---------------------------------------------------------------------------------------
-// Four-wave form of the 64-wide persistent kernel: the same 256 x 256 tile, tile list, run-on across tile
-// boundaries and epilogue, but one wave per SIMD with a 128 x 128 accumulator slice (256 accumulator registers).
-// Per k-substep a wave reads 4 + 4 fragments for 16 MFMAs instead of 4 + 2 for 8: a third fewer bytes leave
-// LDS per flop, and there is one barrier per 64 MFMAs of a wave instead of one per 32.
+// Persistent kernel with 64-wide k-tiles for row-major operands (the one the forward pass and every row-major
+// product of the backward pass run): the tile list and the run-on across tile boundaries of the ring form above,
+// but every copy instruction fetches whole 128-byte lines (8 rows x 128 bytes instead of 16 rows x 64 bytes).
+// Measured on a copy-only loop over L2-resident data the line-sized pieces move 1.6 times the bytes per cycle of
+// the half-line ones, and in the ring kernel the copies, not the matrix pipe, set the cycle count.
 //
-// Copies.  Buffer g & 1 is released by the barrier before the fourth substep of step g.  A wave's copies of
-// k-tile g + 2 are spread over two substeps: its 8 groups of token rows go out between the MFMAs of that fourth
-// substep, its 8 groups of weight rows between the MFMAs of the first substep of step g + 1 (64 KiB inside one
-// substep is twice what a CU's address unit takes in that time, and a wave that waits for a slot there issues no
-// MFMA either).  All of them land before the barrier of step g + 1, two substeps later.  The weight rows of a
-// tile are N-aligned (a launch condition), so their addresses are a wave-uniform base plus one of two per-lane
-// offsets that never change; only the token rows carry per-tile lane offsets.  There is always something to
-// copy: past the end of a workgroup's list the last k-tile is fetched again into a buffer nobody reads any more,
-// which keeps the unrolled MFMA sequences free of branches.
+// Two LDS buffers of 64 KiB (256 token rows + 256 weight rows x 128 bytes).  Step g multiplies buffer g & 1 in four
+// k-substeps.  When the fourth substep's fragments have been asked for nobody reads that buffer any more: behind
+// one wait (all copies landed, all own LDS reads done) and one barrier it is released.
 //
-// Gathered token rows (row_index).  The 256 row indices of a tile travel through LDS as well: one 4-byte
-// asynchronous copy per wave, requested two tiles ahead, so no wave ever waits for a global load while it sets up
-// a tile.  Three slots rotate; a slot is read one tile after it was requested (at least two barriers with
+// Copies.  A wave's copies of k-tile g + 2 are spread over SP k-substeps: its groups of token rows go out between
+// the MFMAs of the fourth substep of step g, its groups of weight rows between the MFMAs of the first substep of
+// step g + 1 (SP = 2; SP = 1 puts everything into the fourth substep, SP = 3 moves half of the weight rows on into
+// the second substep).  64 KiB inside one substep is twice what a CU's address unit takes in that time, and a wave
+// that waits for a slot there issues no MFMA either; all of them land before the barrier of step g + 1.  The weight
+// rows of a tile are whole column tiles (a launch condition), so their addresses are a wave-uniform base plus one
+// of two per-lane offsets that never change; only the token rows carry per-tile lane offsets.  There is always
+// something to copy: past the end of a workgroup's list the last k-tile is fetched again into a buffer nobody
+// reads any more, which keeps the unrolled MFMA sequences free of branches.
+//
+// Gathered token rows (row_index).  The 256 row indices of a tile travel through LDS as well: 4-byte
+// asynchronous copies by waves 0..3, requested two tiles ahead, so no wave ever waits for a global load while it
+// sets up a tile.  Three slots rotate; a slot is read one tile after it was requested (at least two barriers with
 // vmcnt(0) lie in between) and rewritten two tiles after it was read.
 //
-// Fragment reads of the next substep are issued after the first four MFMAs of the current one, so the wait in
-// front of a substep's first MFMA only ever covers reads that are 12 MFMAs old.
+// Fragment reads of the next substep are issued after the first MFMA row of the current one, so the wait in
+// front of a substep's first MFMA only ever covers reads that are most of a substep old.
+//
+// NW = 8 (two waves per SIMD, a 128 x 64 accumulator slice each) is what is launched.  NW = 4 (one wave per SIMD,
+// 128 x 128 slices in 256 accumulator registers, a third fewer LDS bytes per flop and half the barriers) was
+// measured 1-5 % slower on every workload: with one wave per SIMD nothing covers a wave's own waits.
 // ---------------------------------------------------------------------------------------
-template <bool GLU, bool DUAL = false, bool KEEP = false, int NW = 4, int SP = 2>
-__global__ __launch_bounds__(NW * 64) void gemm_bf16_persist128_kernel(GemmParams p) {
+template <bool GLU, bool DUAL = false, bool KEEP = false, int NW = 8, int SP = 2>
+__global__ __launch_bounds__(NW * 64) void gemm_bf16_persistent_kernel(GemmParams p) {
     static_assert(!KEEP || (GLU && !DUAL), "the pre-activations are kept by the SwiGLU epilogue only");
     static_assert(NW == 4 || NW == 8, "one or two waves per SIMD");
     static_assert(SP >= 1 && SP <= 3, "substeps the copies of a k-tile are spread over");
@@ -1479,11 +1283,8 @@ hipError_t launch_bf16(GemmParams p, hipStream_t st) {
     constexpr size_t lds = 2ull * (BM + BROWS) * BK * 2;
     const long long blocks = plan_tiles(p, BM, BN);
     auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, GLU, SWZ, DUAL>;
-    if (lds > 64 * 1024) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (err != hipSuccess) return err;
-    }
+    hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
+    if (err != hipSuccess) return err;
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(blocks)), dim3(WGM * WGN * 64), lds, st, p);
     return hipGetLastError();
 }
@@ -1493,8 +1294,7 @@ hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
     constexpr size_t lds = static_cast<size_t>(NBUF) * 512 * 32 * 2;        // NBUF buffers of 256 + 256 rows x 32 bf16
     const long long blocks = plan_tiles(p, 256, GLU ? 128 : 256);
     auto kern = gemm_bf16_ring_kernel<GLU, WN, DUAL, NBUF>;
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(blocks)), dim3(128 * WN), lds, st, p);
     return hipGetLastError();
@@ -1507,36 +1307,23 @@ hipError_t launch_bf16_persist(GemmParams p, hipStream_t st, int n_cu) {
     constexpr size_t lds = 4ull * 512 * 32 * 2;
     plan_tiles(p, 256, GLU ? 128 : 256);
     auto kern = gemm_bf16_persist_kernel<GLU, DUAL, TRA, TRB>;
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(512), lds, st, p);
     return hipGetLastError();
 }
-template <bool GLU, bool DUAL = false>
-hipError_t launch_bf16_persist64(GemmParams p, hipStream_t st, int n_cu) {
+template <bool GLU, bool DUAL = false, bool KEEP = false, int NW = 8, int SP = 2>
+hipError_t launch_bf16_persistent(GemmParams p, hipStream_t st, int n_cu) {
     constexpr size_t lds = 2ull * 512 * 64 * 2;                             // two buffers of 256 + 256 rows x 64 bf16
     plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_persist64_kernel<GLU, DUAL>;
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-    if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(512), lds, st, p);
-    return hipGetLastError();
-}
-template <bool GLU, bool DUAL = false, bool KEEP = false, int NW = 4, int SP = 2>
-hipError_t launch_bf16_persist128(GemmParams p, hipStream_t st, int n_cu) {
-    constexpr size_t lds = 2ull * 512 * 64 * 2;                             // two buffers of 256 + 256 rows x 64 bf16
-    plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_persist128_kernel<GLU, DUAL, KEEP, NW, SP>;
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    auto kern = gemm_bf16_persistent_kernel<GLU, DUAL, KEEP, NW, SP>;
+    hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(NW * 64), lds, st, p);
     return hipGetLastError();
 }
-// the four-wave kernel also wants whole column tiles (its weight-row addresses are not clamped)
-inline bool persist128_ok(const GemmParams& g, bool glu) { return g.N % (glu ? 128 : 256) == 0; }
+// the 64-wide persistent kernel also wants whole column tiles (its weight-row addresses are not clamped)
+inline bool whole_column_tiles(const GemmParams& g, bool glu) { return g.N % (glu ? 128 : 256) == 0; }
 inline bool persist_ok(const GemmParams& g, bool glu) {
     GemmParams t = g;
     plan_tiles(t, 256, glu ? 128 : 256);
@@ -1560,13 +1347,6 @@ size_t ffn_ws_bytes(const etr_config& c) {
 
 // The pipelined kernels need K % 64 == 0 (copies cannot zero-fill a K tail) and 32-bit byte
 // offsets inside one operand; everything else takes the register-staged kernel.
-static int cu_count() {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8)
-        return 256;
-    return n;
-}
-
 static bool pipelined_ok(const GemmParams& g, size_t a_rows) {
     const size_t a_row_bytes = static_cast<size_t>(g.lda ? g.lda : g.K) * 2, b_row_bytes = static_cast<size_t>(g.ldb ? g.ldb : g.K) * 2;
     return g.K % 64 == 0 && a_row_bytes % 16 == 0 && b_row_bytes % 16 == 0 && a_rows * a_row_bytes < (1ull << 32) &&
@@ -1611,13 +1391,12 @@ hipError_t launch_grouped_gemm(const GroupedGemm& q, hipStream_t st) {
     if (q.dtype == ETR_BF16) {
         if (q.K % 8 != 0 || (q.lda ? q.lda : q.K) % 8 != 0 || (q.ldb ? q.ldb : q.K) % 8 != 0) return hipErrorInvalidValue;
         const bool ring = pipelined_ok(g, q.row_index ? static_cast<size_t>(q.a_rows) : static_cast<size_t>(q.M));
-        if (ring && persist_ok(g, q.epilogue != GEMM_PLAIN)) {
+        if (ring && persist_ok(g, q.epilogue != GEMM_PLAIN) && whole_column_tiles(g, q.epilogue != GEMM_PLAIN)) {
             const int n_cu = cu_count();
-            const bool wide = persist128_ok(g, q.epilogue != GEMM_PLAIN);
             switch (q.epilogue) {
-                case GEMM_PLAIN: return wide ? launch_bf16_persist128<false>(g, st, n_cu) : launch_bf16_persist64<false>(g, st, n_cu);
-                case GEMM_SWIGLU: return wide ? launch_bf16_persist128<true>(g, st, n_cu) : launch_bf16_persist64<true>(g, st, n_cu);
-                case GEMM_DUAL: return wide ? launch_bf16_persist128<true, true>(g, st, n_cu) : launch_bf16_persist64<true, true>(g, st, n_cu);
+                case GEMM_PLAIN: return launch_bf16_persistent<false>(g, st, n_cu);
+                case GEMM_SWIGLU: return launch_bf16_persistent<true>(g, st, n_cu);
+                case GEMM_DUAL: return launch_bf16_persistent<true, true>(g, st, n_cu);
             }
         }
         switch (q.epilogue) {
@@ -1655,16 +1434,13 @@ hipError_t launch_expert_ffn(const etr_config& c, const void* xp, const int32_t*
         if (gather_rows && !ffn_can_gather(c)) return hipErrorInvalidValue;
         const bool pipe1 = pipelined_ok(g1, gather_rows ? static_cast<size_t>(c.T) : static_cast<size_t>(c.capacity));
         const int n_cu = cu_count();
-        if (pipe1 && persist_ok(g1, true)) {
-            if (!persist128_ok(g1, true)) err = launch_bf16_persist64<true>(g1, st, n_cu);
-            else err = g1.C3 ? launch_bf16_persist128<true, false, true>(g1, st, n_cu) : launch_bf16_persist128<true>(g1, st, n_cu);
-        }
+        if (pipe1 && persist_ok(g1, true) && whole_column_tiles(g1, true))
+            err = g1.C3 ? launch_bf16_persistent<true, false, true>(g1, st, n_cu) : launch_bf16_persistent<true>(g1, st, n_cu);
         else err = (pipe1 && !g1.C3) ? launch_bf16_ring<true, 4>(g1, st) : launch_bf16<128, 64, 64, 2, 2, true, 1>(g1, st);
         if (err != hipSuccess) return err;
         if (between && (err = hipEventRecord(between, st)) != hipSuccess) return err;
         if (!pipelined_ok(g2, c.capacity)) return launch_bf16<128, 128, 64, 2, 2, false, 1>(g2, st);
-        if (persist_ok(g2, false))
-            return persist128_ok(g2, false) ? launch_bf16_persist128<false>(g2, st, n_cu) : launch_bf16_persist64<false>(g2, st, n_cu);
+        if (persist_ok(g2, false) && whole_column_tiles(g2, false)) return launch_bf16_persistent<false>(g2, st, n_cu);
         return launch_bf16_ring<false, 4>(g2, st);
     }
     if (gather_rows) return hipErrorInvalidValue;

@@ -267,11 +267,8 @@ hipError_t launch_route(const etr_config& c, const void* x, const float* w_emb, 
     const bool fast = p.R > 0 && p.d / V <= kWave * kUnroll;
     auto kern = c.dtype == ETR_BF16 ? (fast ? route_kernel<true, true> : route_kernel<true, false>)
                                     : (fast ? route_kernel<false, true> : route_kernel<false, false>);
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (e != hipSuccess) return e;
-    }
+    hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(blocks), dim3(kRouteThreads), lds, st, p, x, w_emb, score, gate);
     return hipGetLastError();
 }
