@@ -23,6 +23,8 @@
  *      ETR_ERR_WORKSPACE    ws_bytes smaller than the matching *_workspace_bytes(cfg)
  *      ETR_ERR_ALIGN        a pointer is not 16-byte aligned
  *      ETR_ERR_HIP          the HIP runtime reported an error at launch
+ *      ETR_ERR_TOO_LARGE    (etr_select_noalloc only) the configuration needs more scratch than the
+ *                           library's static array holds
  *  - capacity > T is legal: selection keeps min(capacity, #candidates) tokens
  *    and the buffers keep the stride `capacity`.
  *  - Ties are broken towards the lowest index (expert index in the token's
@@ -44,7 +46,7 @@ extern "C" {
 
 typedef enum {
     ETR_OK = 0, ETR_ERR_NULL = 1, ETR_ERR_SHAPE = 2, ETR_ERR_UNSUPPORTED = 3,
-    ETR_ERR_WORKSPACE = 4, ETR_ERR_ALIGN = 5, ETR_ERR_HIP = 6
+    ETR_ERR_WORKSPACE = 4, ETR_ERR_ALIGN = 5, ETR_ERR_HIP = 6, ETR_ERR_TOO_LARGE = 7
 } etr_status;
 
 typedef enum { ETR_F32 = 0, ETR_BF16 = 1 } etr_dtype;
@@ -122,6 +124,22 @@ etr_status etr_route(const etr_config* cfg, const void* x, const float* w_emb,
 etr_status etr_select(const etr_config* cfg, const float* score, int32_t* topk_expert,
                       int32_t* slot_of, int32_t* slot_token, int32_t* counts,
                       void* ws, size_t ws_bytes, void* stream);
+
+/* etr_select for callers that cannot allocate and have no workspace to hand over: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same results, bit for bit; the
+ * scratch that etr_select takes as `ws` lives in a static device array of the library instead
+ * (etr_select_noalloc_max_bytes() = 8 MiB per GPU the library runs on, held until the process ends).
+ *  - etr_select_workspace_bytes(cfg) must not exceed that size, else ETR_ERR_TOO_LARGE and nothing is launched
+ *    (all five workloads of the benchmark fit: the largest needs 4.9 MiB).
+ *  - The call allocates nothing and frees nothing.  Its first call on a device looks the array's address up
+ *    (hipGetSymbolAddress), so make that first call outside stream capture; later calls only launch kernels.
+ *  - Every call on one GPU uses the same array.  Nothing in it has to start at zero (the kernels write every
+ *    word they read), but two calls that overlap in time on one GPU (different streams, or graphs replayed
+ *    concurrently) race on it: serialise them.
+ * Arguments as etr_select, without ws / ws_bytes. */
+size_t etr_select_noalloc_max_bytes(void);
+etr_status etr_select_noalloc(const etr_config* cfg, const float* score, int32_t* topk_expert,
+                              int32_t* slot_of, int32_t* slot_token, int32_t* counts, void* stream);
 
 /* Token rearrangement into capacity-bounded per-expert buffers (the slot table I_{ki} of Eq. 6).
  *   x [T][d] in; slot_token [E][capacity], counts [E] in

@@ -22,7 +22,7 @@ EXPORTS = ("etr_workspace_bytes", "etr_select_workspace_bytes", "etr_ffn_workspa
            "etr_route", "etr_select", "etr_dispatch", "etr_expert_ffn", "etr_combine", "etr_moe_forward",
            "etr_moe_forward_profiled", "etr_select_adaptive", "etr_stats_workspace_bytes", "etr_route_stats",
            "etr_capacity_lower_bound", "etr_backward_workspace_bytes", "etr_moe_backward",
-           "etr_moe_forward_train")
+           "etr_moe_forward_train", "etr_select_noalloc", "etr_select_noalloc_max_bytes")
 N_STAGE_EVENTS = 7
 STAGE_NAMES = ("route", "select", "dispatch", "ffn_gate_up", "ffn_down", "combine")
 
@@ -55,11 +55,14 @@ def load_library():
                  "etr_stats_workspace_bytes", "etr_backward_workspace_bytes"):
         getattr(lib, name).restype = sz
         getattr(lib, name).argtypes = [cp]
+    lib.etr_select_noalloc_max_bytes.restype = sz
+    lib.etr_select_noalloc_max_bytes.argtypes = []
     lib.etr_status_string.restype = ctypes.c_char_p
     lib.etr_status_string.argtypes = [ctypes.c_int]
     sigs = {
         "etr_route": [cp, vp, vp, vp, vp, vp],
         "etr_select": [cp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "etr_select_noalloc": [cp, vp, vp, vp, vp, vp, vp],
         "etr_dispatch": [cp, vp, vp, vp, vp, vp],
         "etr_expert_ffn": [cp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "etr_combine": [cp, vp, vp, vp, vp, vp],
@@ -127,6 +130,15 @@ def etr_route(cfg, x, w_emb, score, gate):
 def etr_select(cfg, score, topk_expert, slot_of, slot_token, counts, ws):
     _check("etr_select", load_library().etr_select(ctypes.byref(cfg), _ptr(score), _ptr(topk_expert), _ptr(slot_of),
                                                    _ptr(slot_token), _ptr(counts), _ptr(ws), _nbytes(ws), _stream()))
+
+
+def etr_select_noalloc_max_bytes() -> int:
+    return int(load_library().etr_select_noalloc_max_bytes())
+
+
+def etr_select_noalloc(cfg, score, topk_expert, slot_of, slot_token, counts):
+    _check("etr_select_noalloc", load_library().etr_select_noalloc(
+        ctypes.byref(cfg), _ptr(score), _ptr(topk_expert), _ptr(slot_of), _ptr(slot_token), _ptr(counts), _stream()))
 
 
 def etr_select_adaptive(cfg, score, capacity_dev, affinity_sum_threshold, topk_expert, slot_of, slot_token, counts, ws):

@@ -131,6 +131,7 @@ const char* etr_status_string(etr_status s) {
         case ETR_ERR_WORKSPACE: return "workspace too small";
         case ETR_ERR_ALIGN: return "pointer not 16-byte aligned";
         case ETR_ERR_HIP: return "HIP runtime error";
+        case ETR_ERR_TOO_LARGE: return "configuration needs more scratch than the allocation-free entry point holds";
     }
     return "unknown status";
 }
@@ -166,6 +167,22 @@ etr_status etr_select(const etr_config* cfg, const float* score, int32_t* topk_e
     ETR_REQUIRE_PTR(score); ETR_REQUIRE_PTR(slot_of); ETR_REQUIRE_PTR(slot_token); ETR_REQUIRE_PTR(counts);
     ETR_REQUIRE_PTR(ws); ETR_OPTIONAL_PTR(topk_expert);
     if (ws_bytes < select_ws_bytes(cfg->T, cfg->E)) return ETR_ERR_WORKSPACE;
+    const SelectWs w = select_ws_carve(ws, cfg->T, cfg->E);
+    ETR_HIP(launch_select(*cfg, score, topk_expert, slot_of, slot_token, counts, w, static_cast<hipStream_t>(stream)));
+    return ETR_OK;
+}
+
+size_t etr_select_noalloc_max_bytes(void) { return kStaticSelectBytes; }
+
+etr_status etr_select_noalloc(const etr_config* cfg, const float* score, int32_t* topk_expert, int32_t* slot_of,
+                              int32_t* slot_token, int32_t* counts, void* stream) {
+    etr_status s = check_config(cfg);
+    if (s != ETR_OK) return s;
+    ETR_REQUIRE_PTR(score); ETR_REQUIRE_PTR(slot_of); ETR_REQUIRE_PTR(slot_token); ETR_REQUIRE_PTR(counts);
+    ETR_OPTIONAL_PTR(topk_expert);
+    if (select_ws_bytes(cfg->T, cfg->E) > kStaticSelectBytes) return ETR_ERR_TOO_LARGE;
+    void* ws = nullptr;
+    ETR_HIP(static_select_scratch(&ws));
     const SelectWs w = select_ws_carve(ws, cfg->T, cfg->E);
     ETR_HIP(launch_select(*cfg, score, topk_expert, slot_of, slot_token, counts, w, static_cast<hipStream_t>(stream)));
     return ETR_OK;

@@ -30,6 +30,9 @@ struct SelectWs {
 constexpr int kSelThreads = 1024;       // threads of the per-expert kernel = max chunks
 size_t select_ws_bytes(int T, int E);
 SelectWs select_ws_carve(void* ws, int T, int E);
+// the allocation-free variant keeps this much scratch in a static device array (select.hip)
+constexpr size_t kStaticSelectBytes = 8u << 20;
+hipError_t static_select_scratch(void** out);    // its device address on the current device
 
 // ---- launchers ---------------------------------------------------------------
 // route.hip

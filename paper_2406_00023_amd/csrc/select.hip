@@ -15,7 +15,14 @@
 //                            emits slot_of / slot_token; coalesced over the expert index
 // All three phases are one algorithm: in TCR every candidate has the same key, so
 // "the C best, lowest token first among equals" is "the first C in token order".
+#include <mutex>
+
 #include "etr_internal.h"
+
+// Scratch of the allocation-free entry point (etr_select_noalloc): device memory that belongs to the library, one
+// copy per GPU the library runs on, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels and copies are given the address that call returns.
+static __device__ __align__(256) unsigned char scratch[etr::kStaticSelectBytes];
 
 namespace etr {
 namespace {
@@ -372,6 +379,27 @@ SelectWs select_ws_carve(void* ws, int T, int E) {
     w.ipt = chunk_tokens(T);
     w.nchunks = (T + w.ipt - 1) / w.ipt;
     return w;
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+hipError_t static_select_scratch(void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptrs[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return err;
+        if (!p) return hipErrorInvalidSymbol;
+        ptrs[dev] = p;
+    }
+    *out = ptrs[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_expert, int32_t* slot_of,

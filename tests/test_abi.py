@@ -37,8 +37,8 @@ def test_config_struct_matches_header():
 
 
 def test_status_strings(lib):
-    texts = {lib.etr_status_string(i).decode() for i in range(7)}
-    assert len(texts) == 7 and "ok" in texts
+    texts = {lib.etr_status_string(i).decode() for i in range(8)}
+    assert len(texts) == 8 and "ok" in texts
 
 
 def test_workspace_queries(lib):
@@ -91,6 +91,23 @@ def test_null_and_alignment(lib):
     assert lib.etr_select(c, ok, null, ok, ok, ok, ok, 16, null) == 4
     assert lib.etr_expert_ffn(c, ok, ok, ok, ok, ok, ok, ok, 16, null) == 4
     assert lib.etr_moe_forward(c, ok, ok, ok, ok, ok, ok, *([null] * 6), ok, 16, null) == 4
+
+
+def test_noalloc_select_validates_before_anything_else(lib):
+    """The allocation-free entry point rejects bad arguments and oversized configurations on the host."""
+    null, ok, odd = ctypes.c_void_p(0), ctypes.c_void_p(4096), ctypes.c_void_p(4100)
+    cfg = B.make_config(I.CONFIGS["cfg1"])
+    c = ctypes.byref(cfg)
+    assert lib.etr_select_noalloc(None, ok, null, ok, ok, ok, null) == 1
+    assert lib.etr_select_noalloc(c, null, null, ok, ok, ok, null) == 1
+    assert lib.etr_select_noalloc(c, ok, null, ok, odd, ok, null) == 5
+    limit = B.etr_select_noalloc_max_bytes()
+    assert limit == 8 << 20
+    for s in I.CONFIGS.values():                       # every benchmark workload fits
+        assert B.etr_select_workspace_bytes(B.make_config(s)) <= limit
+    big = B.make_config(I.CONFIGS["cfg5"].with_(T=1 << 20, capacity=1 << 20))
+    assert B.etr_select_workspace_bytes(big) > limit
+    assert lib.etr_select_noalloc(ctypes.byref(big), ok, null, ok, ok, ok, null) == 7
 
 
 def test_binding_refuses_missing_library(monkeypatch, tmp_path):

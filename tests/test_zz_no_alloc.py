@@ -1,0 +1,60 @@
+"""The allocation-free selection entry point (static device scratch) against etr_select, through the C ABI:
+identical tables, byte for byte, on two calls in a row, the second on a smaller input (the scratch keeps the
+first call's contents)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2406_00023_amd import binding as B
+from paper_2406_00023_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+
+def _tables(shape, score, noalloc):
+    T, E, C, k = shape.T, shape.E, shape.capacity, max(shape.k, 1)
+    cfg = B.make_config(shape)
+    topk = torch.full((T, k), -7, dtype=torch.int32, device="cuda")
+    slot_of = torch.full((T, E), -7, dtype=torch.int32, device="cuda")
+    slot_token = torch.full((E, C), -7, dtype=torch.int32, device="cuda")
+    counts = torch.full((E,), -7, dtype=torch.int32, device="cuda")
+    if noalloc:
+        B.etr_select_noalloc(cfg, score, topk, slot_of, slot_token, counts)
+    else:
+        B.etr_select(cfg, score, topk, slot_of, slot_token, counts,
+                     B.alloc_workspace(B.etr_select_workspace_bytes(cfg)))
+    torch.cuda.synchronize()
+    return topk, slot_of, slot_token, counts
+
+
+@pytest.mark.parametrize("mode", [I.MODE_TCR, I.MODE_ECR, I.MODE_BIDIR, I.MODE_TCR_RANK, I.MODE_BIDIR_STRICT])
+def test_noalloc_select_matches_etr_select_twice(mode):
+    B.load_library()
+    rng = np.random.default_rng(31 + mode)
+    big = I.EtrShape("na_big", 1, T=40000, d=8 * 32, E=32, D=8, k=3, capacity=2100, H=8, dtype=I.DT_F32, mode=mode,
+                     recipe="iso")
+    small = I.EtrShape("na_small", 1, T=777, d=8 * 5, E=5, D=8, k=2, capacity=130, H=8, dtype=I.DT_F32, mode=mode,
+                       recipe="iso")
+    for shape in (big, small):                          # the second call sees what the first left in the scratch
+        print(f"noalloc select mode={mode} T={shape.T} E={shape.E} C={shape.capacity}", flush=True)
+        levels = 40
+        s = (rng.integers(-levels, levels + 1, size=(shape.T, shape.E)) / levels).astype(np.float32)   # many ties
+        score = torch.from_numpy(s).cuda()
+        want = _tables(shape, score, noalloc=False)
+        got = _tables(shape, score, noalloc=True)
+        for name, a, b in zip(("topk", "slot_of", "slot_token", "counts"), got, want):
+            if name == "topk" and mode == I.MODE_ECR:
+                continue
+            assert torch.equal(a, b), name
+
+
+def test_noalloc_select_rejects_oversized_config():
+    B.load_library()
+    shape = I.EtrShape("na_huge", 1, T=1 << 20, d=8 * 8, E=8, D=8, k=1, capacity=4, H=8, dtype=I.DT_F32,
+                       mode=I.MODE_BIDIR, recipe="iso")
+    cfg = B.make_config(shape)
+    assert B.etr_select_workspace_bytes(cfg) > B.etr_select_noalloc_max_bytes()
+    t = torch.zeros(16, dtype=torch.float32, device="cuda")       # never touched: the call fails on the host
+    with pytest.raises(B.EtrError) as ei:
+        B.etr_select_noalloc(cfg, t, None, t, t, t)
+    assert ei.value.status == 7
