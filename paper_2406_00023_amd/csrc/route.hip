@@ -14,6 +14,10 @@ namespace {
 constexpr int kRouteThreads = 256;
 constexpr int kRouteWaves = kRouteThreads / kWave;
 constexpr int kUnroll = 8;
+// Workgroups resident per CU.  Measured on the 32-expert workload (57 us at 4): 5 and 6 per CU need 96 / 80 registers,
+// spill, and take 66 / 99 us; keeping a lane's share of its embedding row in registers (172 registers, two waves
+// per SIMD) takes 83 us.  The kernel lives on loads in flight, but not at the price of spills.
+constexpr int kRouteBlocksPerCU = 4;
 
 // g lives in a per-wave LDS region: a wave's LDS instructions execute in issue order, so ordering
 // them in the instruction stream is all that is needed (no workgroup barrier, no waiting)
@@ -90,7 +94,7 @@ struct RouteParams {
 // FAST: the whole row fits one pass of kUnroll loads per lane and pools with lane shuffles;
 // otherwise the general walk (several passes, or one lane per pooled feature).
 template <bool BF16, bool FAST>
-__global__ __launch_bounds__(kRouteThreads) void route_kernel(RouteParams p, const void* __restrict__ x,
+__global__ __launch_bounds__(kRouteThreads, kRouteBlocksPerCU) void route_kernel(RouteParams p, const void* __restrict__ x,
                                                               const float* __restrict__ w_emb,
                                                               float* __restrict__ score, float* __restrict__ gate) {
     using C = Chunk<BF16>;
@@ -262,7 +266,8 @@ hipError_t launch_route(const etr_config& c, const void* x, const float* w_emb, 
     const size_t lds = sizeof(float) * (static_cast<size_t>(p.E) * p.w_stride + 64 + kRouteWaves * p.P);
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     int blocks = (c.T + kRouteWaves - 1) / kRouteWaves;
-    if (blocks > 256 * 4) blocks = 256 * 4;          // what is resident at once (4 workgroups per CU): the embeddings are staged once per workgroup
+    const int resident = cu_count() * kRouteBlocksPerCU;    // what is resident at once: the embeddings are staged once per workgroup
+    if (blocks > resident) blocks = resident;
     if (blocks < 1) blocks = 1;
     const bool fast = p.R > 0 && p.d / V <= kWave * kUnroll;
     auto kern = c.dtype == ETR_BF16 ? (fast ? route_kernel<true, true> : route_kernel<true, false>)

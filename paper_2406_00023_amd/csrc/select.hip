@@ -2,17 +2,17 @@
 // rules of the pure phases from the Proof of the Theorem, parts 1 and 2) and the
 // prefix-sum permutation tables.
 //
-// Three launches, no atomics, so the result is bit-reproducible:
+// Three launches, no global atomics, integer counting only, so the result is bit-reproducible:
 //   1. token_choice_kernel   one lane per (token, expert): k rounds of arg-max inside a
 //                            lane group give the token's Top-k list (Eq. 5); writes the
 //                            candidate mask and a column-major copy of the selection keys
-//   2. expert_choice_kernel  one 1024-thread workgroup per expert: finds the key tau_e of
-//                            the C-th best candidate by bitwise bisection over the 32-bit
-//                            order-preserving keys held in registers (Eq. 6), then scans
-//                            the (key > tau, key == tau) indicator pairs into per-chunk
-//                            exclusive prefixes
-//   3. slot_kernel           one thread per (chunk, expert) walks its tokens in order and
-//                            emits slot_of / slot_token; coalesced over the expert index
+//   2. expert_choice_kernel  one 1024-thread workgroup per expert, keys in registers: the key tau_e of
+//                            the C-th best candidate (Eq. 6) by a radix search over the bits in which the
+//                            candidates' order-preserving keys differ at all (11 bits per pass, one LDS
+//                            histogram per pass), then the (key > tau, key == tau) indicator pairs are
+//                            scanned into per-chunk exclusive prefixes
+//   3. slot_kernel           one lane per (expert, token): the position inside the chunk comes from a
+//                            ballot, so slot_of / slot_token are written without any serial walk
 // All three phases are one algorithm: in TCR every candidate has the same key, so
 // "the C best, lowest token first among equals" is "the first C in token order".
 #include <mutex>
@@ -105,6 +105,8 @@ __device__ __forceinline__ void block_sum3(int& a, int& b, int& c, int (*red)[3]
     for (int w = 0; w < kSelThreads / kWave; ++w) { a += red[w][0]; b += red[w][1]; c += red[w][2]; }
 }
 
+constexpr int kRadixBits = 11;          // digit width of the threshold search: 2048 bins, two per thread
+
 // IPT > 0: the thread's ipt (<= IPT) keys live in registers.  IPT == 0: streamed from memory.
 template <int IPT>
 __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32_t* __restrict__ keyT, int Tpad, int T,
@@ -118,6 +120,9 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
                                                                     int32_t* __restrict__ counts) {
     __shared__ int red[kSelThreads / kWave][3];
     __shared__ int wave_tot[kSelThreads / kWave][2];
+    __shared__ uint32_t range[kSelThreads / kWave][2];
+    __shared__ uint32_t hist[1 << kRadixBits];
+    __shared__ int sel[2];
     const int e = blockIdx.x, tid = threadIdx.x;
     // a capacity computed on the device (e.g. the lower bound of the Remark) may tighten the host one
     const int capacity = capacity_dev ? min(capacity_host, max(1, *capacity_dev)) : capacity_host;
@@ -215,14 +220,72 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
     } else if (mode == ETR_MODE_TCR) {
         tau = 1u;                                       // every candidate carries key 1
     } else {
-        // largest tau with #(key >= tau) >= n_keep, two bits per round
-        tau = 0u;
-        for (int shift = 30; shift >= 0; shift -= 2) {
-            int c1, c2, c3;
-            count3(tau | (1u << shift), tau | (2u << shift), tau | (3u << shift), c1, c2, c3);
-            uint32_t b = c3 >= n_keep ? 3u : (c2 >= n_keep ? 2u : (c1 >= n_keep ? 1u : 0u));
-            tau |= b << shift;
+        // The n_keep-th largest key, by radix search from the top.  Only the bits in which the candidates differ
+        // have to be resolved (affinities of one expert share sign, exponent and often leading mantissa bits), so
+        // the search starts below the common prefix of the largest and the smallest candidate key.
+        uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+        auto fold = [&](uint32_t key) { if (key != 0u) { kmax = max(kmax, key); kmin = min(kmin, key); } };
+        if constexpr (IPT > 0) {
+#pragma unroll
+            for (int j = 0; j < IPT; ++j) fold(keys[j]);
+        } else {
+            for (int idx = tid; idx < T; idx += kSelThreads) fold(col[idx]);
         }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            kmax = max(kmax, static_cast<uint32_t>(__shfl_xor(static_cast<int>(kmax), m, kWave)));
+            kmin = min(kmin, static_cast<uint32_t>(__shfl_xor(static_cast<int>(kmin), m, kWave)));
+        }
+        __syncthreads();                                // previous readers of range[] / hist[] are done
+        if ((tid & (kWave - 1)) == 0) { range[tid / kWave][0] = kmax; range[tid / kWave][1] = kmin; }
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kSelThreads / kWave; ++w) { kmax = max(kmax, range[w][0]); kmin = min(kmin, range[w][1]); }
+        const uint32_t diff = kmax ^ kmin;
+        int shift = diff ? 32 - __builtin_clz(diff) : 0;             // low bits that vary among the candidates
+        uint32_t prefix = shift >= 32 ? 0u : (kmax >> shift) << shift;
+        int need = n_keep;
+        while (shift > 0) {
+            const int w = shift < kRadixBits ? shift : kRadixBits;
+            shift -= w;
+            const int nb = 1 << w, top = shift + w;                  // bins; bits [31:top] are settled
+            for (int b = tid; b < nb; b += kSelThreads) hist[b] = 0u;
+            __syncthreads();
+            auto bin = [&](uint32_t key) {
+                const bool in = key != 0u && (top >= 32 || (key >> top) == (prefix >> top));
+                if (in) atomicAdd(&hist[(key >> shift) & (nb - 1)], 1u);          // LDS; integer adds, so order-free
+            };
+            if constexpr (IPT > 0) {
+#pragma unroll
+                for (int j = 0; j < IPT; ++j) bin(keys[j]);
+            } else {
+                for (int idx = tid; idx < T; idx += kSelThreads) bin(col[idx]);
+            }
+            __syncthreads();
+            // thread t owns bins nb-1-2t and nb-2-2t; scanning the threads in order walks the digits from the top
+            const int b0 = nb - 1 - 2 * tid, b1 = b0 - 1;
+            const int h0 = b0 >= 0 ? static_cast<int>(hist[b0]) : 0, h1 = b1 >= 0 ? static_cast<int>(hist[b1]) : 0;
+            int inc = h0 + h1;
+            const int lane = tid & (kWave - 1), wave = tid / kWave;
+#pragma unroll
+            for (int m = 1; m < kWave; m <<= 1) {
+                const int o = __shfl_up(inc, m, kWave);
+                if (lane >= m) inc += o;
+            }
+            if (lane == kWave - 1) wave_tot[wave][0] = inc;
+            __syncthreads();
+            int before = inc - (h0 + h1);                            // candidates with a larger digit than b0
+            for (int w2 = 0; w2 < wave; ++w2) before += wave_tot[w2][0];
+            if (before < need && need <= before + h0 + h1) {         // exactly one thread: the digit lies here
+                const bool first = need <= before + h0;
+                sel[0] = first ? b0 : b1;
+                sel[1] = first ? before : before + h0;
+            }
+            __syncthreads();
+            prefix |= static_cast<uint32_t>(sel[0]) << shift;
+            need -= sel[1];
+        }
+        tau = prefix;
     }
 
     // per-thread (= per-chunk) counts in token order, then an exclusive block scan
@@ -307,47 +370,61 @@ __global__ __launch_bounds__(kSelThreads) void strict_filter_kernel(const uint32
 // ---------------------------------------------------------------------------------------
 // 3. slots
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void slot_kernel(const float* __restrict__ score, const uint64_t* __restrict__ cmask,
-                                                   int T, int E, int capacity, int mode, int ipt, int nchunks,
+// G = lanes per chunk (power of two >= ipt, at most 64; chunks longer than 64 tokens are walked 64 at a time).
+// Lane -> (expert, chunk, token inside the chunk), token fastest: the keys are read coalesced from the
+// column-major copy, and the number of kept tokens in front of a token inside its chunk is a popcount of a ballot.
+__global__ __launch_bounds__(256) void slot_kernel(const uint64_t* __restrict__ cmask, int T, int E, int capacity,
+                                                   int mode, int ipt, int nchunks, int G,
                                                    const uint32_t* __restrict__ tau_in,
                                                    const int32_t* __restrict__ need_eq_in,
                                                    const int32_t* __restrict__ pre_gt,
                                                    const int32_t* __restrict__ pre_eq,
                                                    const int32_t* __restrict__ counts, int32_t* __restrict__ slot_of,
                                                    int32_t* __restrict__ slot_token,
-                                                   const uint32_t* __restrict__ keyT, int Tpad,     // TCR_RANK: keys as stored
+                                                   const uint32_t* __restrict__ keyT, int Tpad,
                                                    const int32_t* __restrict__ pre_kept) {          // STRICT: see strict_filter_kernel
-    const int gid = blockIdx.x * 256 + threadIdx.x;
-    const int c = gid / E, e = gid - c * E;
-    if (c < nchunks) {
-        const uint32_t tau = tau_in[e];
-        const int need = need_eq_in[e];
-        int gt = pre_gt[e * kSelThreads + c], eq = pre_eq[e * kSelThreads + c];
-        int kept = mode == ETR_MODE_BIDIR_STRICT ? pre_kept[e * kSelThreads + c] : 0;
-        const int t_end = min(T, (c + 1) * ipt);
-        for (int t = c * ipt; t < t_end; ++t) {
-            const float s = score[static_cast<size_t>(t) * E + e];
-            const bool cand = (cmask[t] >> e) & 1ull;
-            const uint32_t key = mode == ETR_MODE_TCR_RANK ? keyT[static_cast<size_t>(e) * Tpad + t]
-                                                           : selection_key(s, cand, mode);
-            int slot = -1;
-            if (key > tau) {
-                slot = gt + min(eq, need);
-                ++gt;
-            } else if (key == tau && key != 0u) {
-                if (eq < need) slot = gt + eq;
-                ++eq;
-            }
-            if (mode == ETR_MODE_BIDIR_STRICT) slot = (slot >= 0 && cand) ? kept++ : -1;   // renumber inside the chooser set
+    const long long gid = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
+    const long long groups = static_cast<long long>(E) * nchunks;
+    const long long grp = gid / G;
+    const int j = static_cast<int>(gid - grp * G);
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t group_mask = (G >= 64 ? ~0ull : ((1ull << G) - 1ull)) << (lane & ~(G - 1));
+    const uint64_t below = (1ull << lane) - 1ull;
+    const bool live = grp < groups;
+    const int e = live ? static_cast<int>(grp / nchunks) : 0, c = live ? static_cast<int>(grp - static_cast<long long>(e) * nchunks) : 0;
+    const uint32_t tau = tau_in[e];
+    const int need = need_eq_in[e];
+    int gt = live ? pre_gt[e * kSelThreads + c] : 0, eq = live ? pre_eq[e * kSelThreads + c] : 0;
+    int kept = (live && mode == ETR_MODE_BIDIR_STRICT) ? pre_kept[e * kSelThreads + c] : 0;
+    const int t_end = min(T, (c + 1) * ipt);
+    for (int j0 = 0; j0 < ipt; j0 += G) {               // one pass unless the chunk is longer than 64 tokens
+        const int t = c * ipt + j0 + j;
+        const bool on = live && j0 + j < ipt && t < t_end;
+        const uint32_t key = on ? keyT[static_cast<size_t>(e) * Tpad + t] : 0u;
+        const bool is_gt = key > tau, is_eq = key == tau && key != 0u;
+        const uint64_t m_gt = __ballot(is_gt) & group_mask, m_eq = __ballot(is_eq) & group_mask;
+        const int gt_before = gt + __popcll(m_gt & below), eq_before = eq + __popcll(m_eq & below);
+        int slot = -1;
+        if (is_gt) slot = gt_before + min(eq_before, need);
+        else if (is_eq && eq_before < need) slot = gt_before + eq_before;
+        if (mode == ETR_MODE_BIDIR_STRICT) {            // renumber inside the chooser set
+            const bool keep = slot >= 0 && on && ((cmask[t] >> e) & 1ull);
+            const uint64_t m_k = __ballot(keep) & group_mask;
+            slot = keep ? kept + __popcll(m_k & below) : -1;
+            kept += __popcll(m_k);
+        }
+        if (on) {
             slot_of[static_cast<size_t>(t) * E + e] = slot;
             if (slot >= 0) slot_token[static_cast<size_t>(e) * capacity + slot] = t;
         }
+        gt += __popcll(m_gt);
+        eq += __popcll(m_eq);
     }
     // empty slots
-    const int total = gridDim.x * 256;
+    const long long total = static_cast<long long>(gridDim.x) * 256;
     for (long long i = gid; i < static_cast<long long>(E) * capacity; i += total) {
-        const int ee = static_cast<int>(i / capacity), s = static_cast<int>(i - static_cast<long long>(ee) * capacity);
-        if (s >= counts[ee]) slot_token[i] = -1;
+        const int ee = static_cast<int>(i / capacity), sl = static_cast<int>(i - static_cast<long long>(ee) * capacity);
+        if (sl >= counts[ee]) slot_token[i] = -1;
     }
 }
 
@@ -444,10 +521,12 @@ hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    const long long pairs = static_cast<long long>(w.nchunks) * c.E;
-    const int blocks3 = static_cast<int>((pairs + 255) / 256);
-    hipLaunchKernelGGL(slot_kernel, dim3(blocks3), dim3(256), 0, st, score, w.cmask, c.T, c.E, c.capacity, c.mode, w.ipt,
-                       w.nchunks, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts, slot_of, slot_token, w.keyT, w.Tpad,
+    int G3 = 4;                                          // lanes per chunk in slot_kernel
+    while (G3 < w.ipt && G3 < 64) G3 <<= 1;
+    const long long lanes3 = static_cast<long long>(w.nchunks) * c.E * G3;
+    const int blocks3 = static_cast<int>((lanes3 + 255) / 256);
+    hipLaunchKernelGGL(slot_kernel, dim3(blocks3), dim3(256), 0, st, w.cmask, c.T, c.E, c.capacity, c.mode, w.ipt,
+                       w.nchunks, G3, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts, slot_of, slot_token, w.keyT, w.Tpad,
                        w.pre_kept);
     return hipGetLastError();
 }

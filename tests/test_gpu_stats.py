@@ -102,3 +102,26 @@ def test_select_adaptive_token_count(oracle, T, E, k, C, thr, levels):
         np.testing.assert_array_equal(slot_token.cpu().numpy(), o_st)
         if mode != ECR:
             np.testing.assert_array_equal(topk.cpu().numpy(), o_tk)
+
+
+def test_select_adaptive_threshold_reached_exactly(oracle):
+    """Dyadic affinities whose prefix sums hit the threshold exactly, one step below and one step above:
+    the GPU's cut equals the oracle's (which the CPU tests pin to 'reaches' meaning >=)."""
+    S = np.array([[0.5, 0.25], [0.25, 0.5], [0.125, 0.25], [0.0625, 0.125], [-0.5, 0.0625], [0.25, -0.25]], np.float32)
+    T, E, C = S.shape[0], S.shape[1], S.shape[0]
+    Sd = torch.from_numpy(S).cuda()
+    step = 2.0 ** -20
+    for thr in (0.75, 0.75 - step, 0.75 + step, 0.5, 0.5 + step, 1.0, 1.1875, 1.1875 + step):
+        for mode in (ECR, BIDIR):
+            cfg = B.make_config(_shape(T, E, 2, C, mode))
+            slot_of = torch.empty(T, E, dtype=torch.int32, device="cuda")
+            slot_token = torch.empty(E, C, dtype=torch.int32, device="cuda")
+            counts = torch.empty(E, dtype=torch.int32, device="cuda")
+            topk = torch.empty(T, 2, dtype=torch.int32, device="cuda")
+            sws = B.alloc_workspace(B.etr_select_workspace_bytes(cfg))
+            B.etr_select_adaptive(cfg, Sd, None, float(np.float32(thr)), topk, slot_of, slot_token, counts, sws)
+            torch.cuda.synchronize()
+            _, o_so, o_st, o_c = oracle.select_adaptive(S, 2, C, mode, float(np.float32(thr)))
+            np.testing.assert_array_equal(counts.cpu().numpy(), o_c, err_msg=f"thr={thr} mode={mode}")
+            np.testing.assert_array_equal(slot_of.cpu().numpy(), o_so)
+            np.testing.assert_array_equal(slot_token.cpu().numpy(), o_st)

@@ -231,6 +231,52 @@ def test_adaptive_worked_example(oracle):
     np.testing.assert_array_equal(oracle.select_adaptive(S, 2, 2, TCR, 0.3)[1], oracle.select(S, 2, 2, TCR)[1])
 
 
+def test_adaptive_threshold_reached_exactly(oracle):
+    """"Reaches the threshold" is >=, pinned with dyadic affinities whose sums are exact in every arithmetic:
+    expert 0 sees 0.5, 0.25, 0.125, 0.0625 (descending): the prefix sums are 0.5, 0.75, 0.875, 0.9375."""
+    S = np.array([[0.5], [0.25], [0.125], [0.0625], [-0.5]], np.float32)
+    step = 2.0 ** -20                                   # far above the 2^-30 quantum, exact in fp32 next to 0.75
+    for thr, want in ((0.75, 2),                        # 0.5 + 0.25 == 0.75: the second token completes the prefix
+                      (0.75 - step, 2),                 # just below: still two (0.5 alone is not enough)
+                      (0.75 + step, 3),                 # just above: the third token is needed
+                      (0.5, 1), (0.5 + step, 2), (0.9375, 4),
+                      (0.9375 + step, 5)):              # the positive affinities never get there: all five candidates
+        counts = oracle.select_adaptive(S, 1, 5, ECR, np.float32(thr))[3]
+        assert counts.tolist() == [want], (thr, counts)
+    # same sums with the order of the tokens reversed: the cut is a property of the sorted candidates
+    counts = oracle.select_adaptive(S[::-1].copy(), 1, 5, ECR, np.float32(0.75))[3]
+    assert counts.tolist() == [2]
+    # the kept tokens are the highest ones, and ties (two tokens at 0.25) go to the lower index
+    S2 = np.array([[0.25], [0.5], [0.25], [0.125]], np.float32)
+    _, _, st, c = oracle.select_adaptive(S2, 1, 4, ECR, np.float32(0.75))
+    assert c.tolist() == [2] and sorted(st[0, :2].tolist()) == [0, 1]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_adaptive_fixed_point_cut_is_the_double_precision_cut(oracle, seed):
+    """The oracle sums round(s * 2^30) in integers so that a parallel sum gives the same cut.  What the paper's
+    sentence describes is the running sum of the affinities themselves: computed here in float64 over the sorted
+    candidates, it must give the same token count, except when it passes within T * 2^-30 of the threshold
+    (the most the T roundings can move the sum)."""
+    rng = np.random.default_rng(900 + seed)
+    T, E = 400, 3
+    S = rng.uniform(-1, 1, size=(T, E)).astype(np.float32)
+    C = T
+    checked = 0
+    for thr in rng.uniform(0.5, 60.0, size=12).astype(np.float32):
+        counts = oracle.select_adaptive(S, 1, C, ECR, thr)[3]
+        for e in range(E):
+            col = np.sort(S[:, e].astype(np.float64))[::-1]
+            run = np.cumsum(np.where(col > 0, col, 0.0))
+            hit = np.flatnonzero((run >= np.float64(thr)) & (col > 0))
+            ell = int(hit[0]) + 1 if hit.size else T
+            near = np.min(np.abs(run[: int((col > 0).sum())] - np.float64(thr))) <= T * 2.0 ** -30
+            if not near:
+                assert counts[e] == min(C, ell), (thr, e, counts[e], ell)
+                checked += 1
+    assert checked >= 30                                # the exception is rare: nearly every case is compared
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_adaptive_brute_force(oracle, seed):
     rng = np.random.default_rng(300 + seed)
