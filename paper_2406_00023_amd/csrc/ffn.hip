@@ -342,6 +342,37 @@ __device__ __forceinline__ void store_block_staged(const uint2 (&pk)[4], uint16_
     wave_lds_order();                                    // the next block overwrites the patch
 }
 
+// Two horizontally adjacent 32 x 32 blocks (64 columns = one 128-byte line per row), 16 rows at a time: the half of
+// the lanes that owns those rows writes them to the patch (row stride 144 bytes), then eight lanes read one row
+// back and a store instruction writes 8 rows x 128 bytes: whole lines (down projection of the 8-expert workload
+// another 1.5 % over the 64-byte pieces).
+constexpr int kPairStride = 144;
+static_assert(16 * kPairStride <= kStageBytes, "the pair patch must fit the per-wave patch");
+__device__ __forceinline__ void store_block_pair_staged(const uint2 (&pk0)[4], const uint2 (&pk1)[4], uint16_t* dst, int ldc,
+                                                        int rows_live, unsigned char* stage, int lane) {
+    const int r32 = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        if ((r32 >> 4) == pass) {
+            unsigned char* row = stage + (r32 & 15) * kPairStride + half * 8;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                *reinterpret_cast<uint2*>(row + q * 16) = pk0[q];
+                *reinterpret_cast<uint2*>(row + 64 + q * 16) = pk1[q];
+            }
+        }
+        wave_lds_order();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int r = h * 8 + (lane >> 3), ch = lane & 7;
+            const uint4 v = *reinterpret_cast<const uint4*>(stage + r * kPairStride + ch * 16);
+            const int row = pass * 16 + r;
+            if (row < rows_live) *reinterpret_cast<uint4*>(dst + static_cast<size_t>(row) * ldc + ch * 8) = v;
+        }
+        wave_lds_order();
+    }
+}
+
 template <bool GLU, bool DUAL, int TI, int TB, bool KEEP = false>
 __device__ __forceinline__ void store_blocks_staged(const GemmParams& p, const f32x16 (&acc)[TI][TB], int e, int m_base,
                                                     int n_base, int count, int lane, unsigned char* stage) {
@@ -355,6 +386,20 @@ __device__ __forceinline__ void store_blocks_staged(const GemmParams& p, const f
         const int mb = m_base + i * 32;
         const int live = count - mb;                     // rows of this block that exist (may be <= 0 or > 32)
         if (live <= 0) continue;                         // wave-uniform
+        if constexpr (!GLU && TO % 2 == 0) {               // plain product: pairs of blocks leave as whole lines
+#pragma unroll
+            for (int j = 0; j < TO; j += 2) {
+                uint2 pk0[4], pk1[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    pk0[q] = pack_bf16x4(acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+                    pk1[q] = pack_bf16x4(acc[i][j + 1][q * 4], acc[i][j + 1][q * 4 + 1], acc[i][j + 1][q * 4 + 2], acc[i][j + 1][q * 4 + 3]);
+                }
+                store_block_pair_staged(pk0, pk1, Cg + static_cast<size_t>(mb) * p.N + n_base + j * 32, p.N, live, stage, lane);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            continue;
+        }
 #pragma unroll
         for (int j = 0; j < TO; ++j) {
             const size_t o = static_cast<size_t>(mb) * p.N + n_base + j * 32;

@@ -71,12 +71,16 @@ SMALL = {
     "cfg3s": lambda: I.small_variant(I.CONFIGS["cfg3"], T=900, d=1024, H=1032),
     "cfg4s": lambda: I.small_variant(I.CONFIGS["cfg4"], T=1500, d=1024, H=328),
     "cfg5s": lambda: I.small_variant(I.CONFIGS["cfg5"], T=700, H=200),
+    # whole column tiles (H % 128 == 0, d % 256 == 0): the recomputation and the training forward run on the
+    # 64-wide persistent kernel (two-product and pre-activation-keeping epilogues, rows gathered through LDS)
+    "cfg2w": lambda: I.small_variant(I.CONFIGS["cfg2"], T=1300, d=512, H=640),
+    "cfg5w": lambda: I.small_variant(I.CONFIGS["cfg5"], T=900, H=256),
 }
 
 
 @pytest.mark.parametrize("name,mode,cos", [("cfg1", TCR, FULL), ("cfg1", ECR, POOLED), ("cfg1", BIDIR, FULL),
                                            ("cfg2s", TCR, FULL), ("cfg3s", ECR, FULL), ("cfg4s", BIDIR, POOLED),
-                                           ("cfg5s", BIDIR, FULL)])
+                                           ("cfg5s", BIDIR, FULL), ("cfg2w", TCR, FULL), ("cfg5w", BIDIR, POOLED)])
 def test_backward_small_all_gradients(H, oracle, name, mode, cos):
     shape = SMALL[name]()
     _say(f"backward case {name} mode={mode} cos={cos} T={shape.T} d={shape.d} E={shape.E} C={shape.capacity} H={shape.H}")
@@ -148,7 +152,7 @@ def test_backward_full_size_sampled(H, oracle, name):
     assert e4 <= tol and e5 <= tol and e6 <= tol
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2s", "cfg3s", "odd"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2s", "cfg3s", "odd", "cfg2w", "cfg5w"])
 def test_training_forward_keeps_pre_activations(H, oracle, name):
     """etr_moe_forward_train gives the bytes of etr_moe_forward, and the backward fed with the kept
     pre-activations gives the bytes of the backward that recomputes them."""
