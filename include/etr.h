@@ -130,7 +130,7 @@ etr_status etr_select(const etr_config* cfg, const float* score, int32_t* topk_e
  * scratch that etr_select takes as `ws` lives in a static device array of the library instead
  * (etr_select_noalloc_max_bytes() = 8 MiB per GPU the library runs on, held until the process ends).
  *  - etr_select_workspace_bytes(cfg) must not exceed that size, else ETR_ERR_TOO_LARGE and nothing is launched
- *    (all five workloads of the benchmark fit: the largest needs 4.9 MiB).
+ *    (all five workloads of the benchmark fit: the largest needs 6.7 MiB).
  *  - The call allocates nothing and frees nothing.  Its first call on a device looks the array's address up
  *    (hipGetSymbolAddress), so make that first call outside stream capture; later calls only launch kernels.
  *  - Every call on one GPU uses the same array.  Nothing in it has to start at zero (the kernels write every

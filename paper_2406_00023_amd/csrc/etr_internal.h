@@ -23,6 +23,9 @@ struct SelectWs {
     int32_t*  pre_gt;    // [E][kMaxChunks] kept-for-sure (key > tau) tokens before the chunk
     int32_t*  pre_eq;    // [E][kMaxChunks] key == tau tokens before the chunk
     int32_t*  pre_kept;  // [E][kMaxChunks] strict-intersection variant: surviving tokens before the chunk
+    uint32_t* hist1;     // [E][n_slices][2048] first radix digit counted per slice of the column (long columns only)
+    int       n_slices;  // 0: no such pre-pass
+    int       slice;     // tokens per slice (multiple of 4)
     int       Tpad;      // row stride of keyT
     int       ipt;       // tokens per chunk (= per thread of the per-expert kernel)
     int       nchunks;

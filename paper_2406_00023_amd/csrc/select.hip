@@ -11,6 +11,8 @@
 //                            candidates' order-preserving keys differ at all (11 bits per pass, one LDS
 //                            histogram per pass), then the (key > tau, key == tau) indicator pairs are
 //                            scanned into per-chunk exclusive prefixes
+//                            (long columns: the first digit is counted beforehand by key_histogram_kernel,
+//                            up to 16 workgroups per expert)
 //   3. slot_kernel           one lane per (expert, token): the position inside the chunk comes from a
 //                            ballot, so slot_of / slot_token are written without any serial walk
 // All three phases are one algorithm: in TCR every candidate has the same key, so
@@ -85,6 +87,33 @@ __global__ __launch_bounds__(256) void token_choice_kernel(const float* __restri
 }
 
 // ---------------------------------------------------------------------------------------
+// 2a. first radix digit, spread over the chip (long columns only): workgroup (slice, expert) counts the top
+// kRadixBits bits of the candidate keys of its slice of the column; expert_choice_kernel<IPT, true> adds the
+// slices up instead of walking all of its keys once more (its per-key work is what bounds it: one CU per expert).
+// Integer counts, so the result does not depend on the split.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void key_histogram_kernel(const uint32_t* __restrict__ keyT, int Tpad, int T,
+                                                            int slice, uint32_t* __restrict__ hist1) {
+    constexpr int NBINS = 1 << 11;
+    __shared__ uint32_t h[NBINS];
+    const int b = blockIdx.x, e = blockIdx.y, nb = gridDim.x, tid = threadIdx.x;
+    for (int i = tid; i < NBINS; i += 256) h[i] = 0u;
+    __syncthreads();
+    const uint32_t* col = keyT + static_cast<size_t>(e) * Tpad;
+    const int t_end = min(T, (b + 1) * slice);
+    for (int t = b * slice + tid * 4; t < t_end; t += 1024) {       // slice and Tpad are multiples of 4
+        const uint4 v = *reinterpret_cast<const uint4*>(col + t);
+        const uint32_t k4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (t + j < T && k4[j] != 0u) atomicAdd(&h[k4[j] >> (32 - 11)], 1u);
+    }
+    __syncthreads();
+    uint32_t* out = hist1 + (static_cast<size_t>(e) * nb + b) * NBINS;
+    for (int i = tid; i < NBINS; i += 256) out[i] = h[i];
+}
+
+// ---------------------------------------------------------------------------------------
 // 2. expert choice: threshold search + chunk prefixes
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ int wave_sum_i(int v) {
@@ -108,7 +137,8 @@ __device__ __forceinline__ void block_sum3(int& a, int& b, int& c, int (*red)[3]
 constexpr int kRadixBits = 11;          // digit width of the threshold search: 2048 bins, two per thread
 
 // IPT > 0: the thread's ipt (<= IPT) keys live in registers.  IPT == 0: streamed from memory.
-template <int IPT>
+// PRE: the histogram of the first digit (the top kRadixBits bits) comes from key_histogram_kernel (hist1, n_slices).
+template <int IPT, bool PRE = false>
 __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32_t* __restrict__ keyT, int Tpad, int T,
                                                                     int ipt, int capacity_host, int mode,
                                                                     const int32_t* __restrict__ capacity_dev,
@@ -117,7 +147,8 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
                                                                     int32_t* __restrict__ need_eq_out,
                                                                     int32_t* __restrict__ pre_gt,
                                                                     int32_t* __restrict__ pre_eq,
-                                                                    int32_t* __restrict__ counts) {
+                                                                    int32_t* __restrict__ counts,
+                                                                    const uint32_t* __restrict__ hist1, int n_slices) {
     __shared__ int red[kSelThreads / kWave][3];
     __shared__ int wave_tot[kSelThreads / kWave][2];
     __shared__ uint32_t range[kSelThreads / kWave][2];
@@ -160,7 +191,20 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
     };
 
     int ncand, d1, d2;
-    count3(1u, 0xFFFFFFFFu, 0xFFFFFFFFu, ncand, d1, d2);
+    int pre_h0 = 0, pre_h1 = 0;                         // PRE: this thread's two bins of the first digit, top down
+    if constexpr (PRE) {
+        static_assert(kSelThreads * 2 == (1 << kRadixBits), "two bins of the first digit per thread");
+        const uint32_t* hp = hist1 + static_cast<size_t>(e) * n_slices * (1 << kRadixBits) + ((1 << kRadixBits) - 2 - 2 * tid);
+        for (int b = 0; b < n_slices; ++b) {
+            const uint2 v = *reinterpret_cast<const uint2*>(hp + static_cast<size_t>(b) * (1 << kRadixBits));
+            pre_h0 += static_cast<int>(v.y);            // bin 2047 - 2 tid
+            pre_h1 += static_cast<int>(v.x);            // bin 2046 - 2 tid
+        }
+        ncand = pre_h0 + pre_h1; d1 = d2 = 0;
+        block_sum3(ncand, d1, d2, red);
+    } else {
+        count3(1u, 0xFFFFFFFFu, 0xFFFFFFFFu, ncand, d1, d2);
+    }
     int n_keep = ncand < capacity ? ncand : capacity;
 
     // Adaptive token count (Sec. Routing Strategy: "l is determined by a threshold of the sum of
@@ -223,48 +267,59 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
         // The n_keep-th largest key, by radix search from the top.  Only the bits in which the candidates differ
         // have to be resolved (affinities of one expert share sign, exponent and often leading mantissa bits), so
         // the search starts below the common prefix of the largest and the smallest candidate key.
-        uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
-        auto fold = [&](uint32_t key) { if (key != 0u) { kmax = max(kmax, key); kmin = min(kmin, key); } };
-        if constexpr (IPT > 0) {
+        int shift = 32;                                              // low bits still to resolve
+        uint32_t prefix = 0u;
+        if constexpr (!PRE) {
+            uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+            auto fold = [&](uint32_t key) { if (key != 0u) { kmax = max(kmax, key); kmin = min(kmin, key); } };
+            if constexpr (IPT > 0) {
 #pragma unroll
-            for (int j = 0; j < IPT; ++j) fold(keys[j]);
-        } else {
-            for (int idx = tid; idx < T; idx += kSelThreads) fold(col[idx]);
+                for (int j = 0; j < IPT; ++j) fold(keys[j]);
+            } else {
+                for (int idx = tid; idx < T; idx += kSelThreads) fold(col[idx]);
+            }
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) {
+                kmax = max(kmax, static_cast<uint32_t>(__shfl_xor(static_cast<int>(kmax), m, kWave)));
+                kmin = min(kmin, static_cast<uint32_t>(__shfl_xor(static_cast<int>(kmin), m, kWave)));
+            }
+            __syncthreads();                            // previous readers of range[] / hist[] are done
+            if ((tid & (kWave - 1)) == 0) { range[tid / kWave][0] = kmax; range[tid / kWave][1] = kmin; }
+            __syncthreads();
+#pragma unroll
+            for (int w = 0; w < kSelThreads / kWave; ++w) { kmax = max(kmax, range[w][0]); kmin = min(kmin, range[w][1]); }
+            const uint32_t diff = kmax ^ kmin;
+            shift = diff ? 32 - __builtin_clz(diff) : 0;             // low bits that vary among the candidates
+            prefix = shift >= 32 ? 0u : (kmax >> shift) << shift;
         }
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) {
-            kmax = max(kmax, static_cast<uint32_t>(__shfl_xor(static_cast<int>(kmax), m, kWave)));
-            kmin = min(kmin, static_cast<uint32_t>(__shfl_xor(static_cast<int>(kmin), m, kWave)));
-        }
-        __syncthreads();                                // previous readers of range[] / hist[] are done
-        if ((tid & (kWave - 1)) == 0) { range[tid / kWave][0] = kmax; range[tid / kWave][1] = kmin; }
-        __syncthreads();
-#pragma unroll
-        for (int w = 0; w < kSelThreads / kWave; ++w) { kmax = max(kmax, range[w][0]); kmin = min(kmin, range[w][1]); }
-        const uint32_t diff = kmax ^ kmin;
-        int shift = diff ? 32 - __builtin_clz(diff) : 0;             // low bits that vary among the candidates
-        uint32_t prefix = shift >= 32 ? 0u : (kmax >> shift) << shift;
         int need = n_keep;
         while (shift > 0) {
             const int w = shift < kRadixBits ? shift : kRadixBits;
+            const bool from_pre = PRE && shift == 32;                // the first digit was counted by the slices
             shift -= w;
             const int nb = 1 << w, top = shift + w;                  // bins; bits [31:top] are settled
-            for (int b = tid; b < nb; b += kSelThreads) hist[b] = 0u;
-            __syncthreads();
-            auto bin = [&](uint32_t key) {
-                const bool in = key != 0u && (top >= 32 || (key >> top) == (prefix >> top));
-                if (in) atomicAdd(&hist[(key >> shift) & (nb - 1)], 1u);          // LDS; integer adds, so order-free
-            };
-            if constexpr (IPT > 0) {
-#pragma unroll
-                for (int j = 0; j < IPT; ++j) bin(keys[j]);
-            } else {
-                for (int idx = tid; idx < T; idx += kSelThreads) bin(col[idx]);
-            }
-            __syncthreads();
             // thread t owns bins nb-1-2t and nb-2-2t; scanning the threads in order walks the digits from the top
             const int b0 = nb - 1 - 2 * tid, b1 = b0 - 1;
-            const int h0 = b0 >= 0 ? static_cast<int>(hist[b0]) : 0, h1 = b1 >= 0 ? static_cast<int>(hist[b1]) : 0;
+            int h0, h1;
+            if (from_pre) {
+                h0 = pre_h0; h1 = pre_h1;
+                __syncthreads();                                     // previous readers of wave_tot[] / sel[] are done
+            } else {
+                for (int b = tid; b < nb; b += kSelThreads) hist[b] = 0u;
+                __syncthreads();
+                auto bin = [&](uint32_t key) {
+                    const bool in = key != 0u && (top >= 32 || (key >> top) == (prefix >> top));
+                    if (in) atomicAdd(&hist[(key >> shift) & (nb - 1)], 1u);      // LDS; integer adds, so order-free
+                };
+                if constexpr (IPT > 0) {
+#pragma unroll
+                    for (int j = 0; j < IPT; ++j) bin(keys[j]);
+                } else {
+                    for (int idx = tid; idx < T; idx += kSelThreads) bin(col[idx]);
+                }
+                __syncthreads();
+                h0 = b0 >= 0 ? static_cast<int>(hist[b0]) : 0; h1 = b1 >= 0 ? static_cast<int>(hist[b1]) : 0;
+            }
             int inc = h0 + h1;
             const int lane = tid & (kWave - 1), wave = tid / kWave;
 #pragma unroll
@@ -436,10 +491,19 @@ static int chunk_tokens(int T) {
     return ipt < 4 ? 4 : ipt;
 }
 
+// Long columns (more than 16 keys per thread of the per-expert kernel) get their first radix digit counted by
+// up to 16 workgroups per expert.
+static int select_slices(int T) {
+    if (chunk_tokens(T) <= 16) return 0;
+    const int n = (T + 4095) / 4096;
+    return n > 16 ? 16 : n;
+}
+
 size_t select_ws_bytes(int T, int E) {
     const size_t Tpad = align_up(static_cast<size_t>(T), 64);
     return align_up(sizeof(uint64_t) * T) + align_up(sizeof(uint32_t) * E * Tpad) + 2 * align_up(sizeof(int32_t) * E) +
-           3 * align_up(sizeof(int32_t) * E * kSelThreads);
+           3 * align_up(sizeof(int32_t) * E * kSelThreads) +
+           align_up(sizeof(uint32_t) * E * select_slices(T) * 2048);
 }
 
 SelectWs select_ws_carve(void* ws, int T, int E) {
@@ -452,13 +516,15 @@ SelectWs select_ws_carve(void* ws, int T, int E) {
     w.need_eq = reinterpret_cast<int32_t*>(p); p += align_up(sizeof(int32_t) * E);
     w.pre_gt = reinterpret_cast<int32_t*>(p);  p += align_up(sizeof(int32_t) * E * kSelThreads);
     w.pre_eq = reinterpret_cast<int32_t*>(p);  p += align_up(sizeof(int32_t) * E * kSelThreads);
-    w.pre_kept = reinterpret_cast<int32_t*>(p);
+    w.pre_kept = reinterpret_cast<int32_t*>(p); p += align_up(sizeof(int32_t) * E * kSelThreads);
+    w.hist1 = reinterpret_cast<uint32_t*>(p);
     w.ipt = chunk_tokens(T);
     w.nchunks = (T + w.ipt - 1) / w.ipt;
+    w.n_slices = select_slices(T);
+    w.slice = w.n_slices ? ((T + w.n_slices - 1) / w.n_slices + 3) / 4 * 4 : 0;
     return w;
 }
 
-// Device address of `scratch` on the current device, looked up once per device.
 hipError_t static_select_scratch(void** out) {
     constexpr int kMaxDevices = 64;
     static std::mutex mu;
@@ -502,15 +568,24 @@ hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
 
-#define ETR_EC(II)                                                                                               \
-    hipLaunchKernelGGL(expert_choice_kernel<II>, dim3(c.E), dim3(kSelThreads), 0, st, w.keyT, w.Tpad, c.T, w.ipt, \
-                       c.capacity, c.mode, capacity_dev, sum_need, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts)
-    if (w.ipt <= 4) ETR_EC(4);
-    else if (w.ipt <= 8) ETR_EC(8);
-    else if (w.ipt <= 16) ETR_EC(16);
-    else if (w.ipt <= 32) ETR_EC(32);
-    else if (w.ipt <= 64) ETR_EC(64);
-    else ETR_EC(0);
+    // TCR keeps by position and searches nothing, so it skips the pre-pass
+    const bool pre = w.n_slices > 0 && c.mode != ETR_MODE_TCR;
+    if (pre) {
+        hipLaunchKernelGGL(key_histogram_kernel, dim3(w.n_slices, c.E), dim3(256), 0, st, w.keyT, w.Tpad, c.T, w.slice,
+                           w.hist1);
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+#define ETR_EC(II, PP)                                                                                                \
+    hipLaunchKernelGGL((expert_choice_kernel<II, PP>), dim3(c.E), dim3(kSelThreads), 0, st, w.keyT, w.Tpad, c.T, w.ipt, \
+                       c.capacity, c.mode, capacity_dev, sum_need, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts, w.hist1, \
+                       w.n_slices)
+    if (w.ipt <= 4) ETR_EC(4, false);
+    else if (w.ipt <= 8) ETR_EC(8, false);
+    else if (w.ipt <= 16) ETR_EC(16, false);                // (no pre-pass up to here, see select_slices)
+    else if (w.ipt <= 32) { if (pre) ETR_EC(32, true); else ETR_EC(32, false); }
+    else if (w.ipt <= 64) { if (pre) ETR_EC(64, true); else ETR_EC(64, false); }
+    else { if (pre) ETR_EC(0, true); else ETR_EC(0, false); }
 #undef ETR_EC
     err = hipGetLastError();
     if (err != hipSuccess) return err;

@@ -31,7 +31,7 @@ def _tables(shape, score, noalloc):
 def test_noalloc_select_matches_etr_select_twice(mode):
     B.load_library()
     rng = np.random.default_rng(31 + mode)
-    big = I.EtrShape("na_big", 1, T=40000, d=8 * 32, E=32, D=8, k=3, capacity=2100, H=8, dtype=I.DT_F32, mode=mode,
+    big = I.EtrShape("na_big", 1, T=36000, d=8 * 32, E=32, D=8, k=3, capacity=2100, H=8, dtype=I.DT_F32, mode=mode,
                      recipe="iso")
     small = I.EtrShape("na_small", 1, T=777, d=8 * 5, E=5, D=8, k=2, capacity=130, H=8, dtype=I.DT_F32, mode=mode,
                        recipe="iso")
