@@ -20,6 +20,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 struct GemmParams {
     const void* A;        // [E][capacity][K]
@@ -307,15 +308,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
     }
 }
 
-// The same epilogue with the output passed through a small per-wave LDS patch, so that memory sees 64-byte pieces
-// of a row instead of 8-byte ones.  In the accumulator layout a lane owns four separate groups of four columns of
-// ONE row, so a direct store instruction writes 32 rows x 16 bytes: for a 256 x 256 tile that is 8192 write
-// requests next to the 512 read requests of each k-step, a third of all requests of a product with a short
-// contraction.  Here a 32 x 32 block is written to LDS as it lies in the registers (row stride 80 bytes), read
-// back with four lanes per row (16 bytes each) and stored as 16 rows x 64 bytes per instruction: a quarter of the
-// write requests and half of the store instructions (measured: the down projection of the 8-expert workload, whose
-// contraction is 22 k-steps, 1009 -> 1119 TFLOP/s; 1-4 % elsewhere).  The patch belongs to the wave (LDS instructions of one
-// wave execute in order), so there is no barrier.  Requires whole column tiles (no column mask).
+// The epilogue of the persistent 64-wide kernel: the output passes through a small per-wave LDS patch, so that
+// memory sees whole or half lines of a row instead of 8-byte pieces.  In the accumulator layout a lane owns four
+// consecutive columns of one row, so a direct store instruction writes 16 rows x 32 bytes (32 x 16 with the
+// 32x32x16 accumulators this was first built for): for a 256 x 256 tile that is thousands of write requests next to
+// the 512 read requests of each k-step, a third of all requests of a product with a short contraction.  Here a
+// 32 x 32 block is written to LDS as it lies in the registers (row stride 80 bytes), read back with four lanes per
+// row (16 bytes each) and stored as 16 rows x 64 bytes per instruction (measured when it went in: the down
+// projection of the 8-expert workload, whose contraction is 22 k-steps, 1009 -> 1119 TFLOP/s; 1-4 % elsewhere).
+// The patch belongs to the wave (LDS instructions of one wave execute in order), so there is no barrier.  Requires
+// whole column tiles (no column mask).
 constexpr int kStageStride = 80;                         // bytes per staged row: 64 of data + 16 so that rows spread over the banks
 constexpr int kStageBytes = 32 * kStageStride;           // per wave
 
@@ -325,13 +327,15 @@ __device__ __forceinline__ void wave_lds_order() {       // orders this wave's L
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// one 32 x 32 block: pk[q] = this lane's four columns 8 q + 4 half .. + 3 of row r32; dst = the block's first element
-__device__ __forceinline__ void store_block_staged(const uint2 (&pk)[4], uint16_t* dst, int ldc, int rows_live,
-                                                   unsigned char* stage, int lane) {
-    const int r32 = lane & 31, half = lane >> 5;
+// One 32 x 32 output block = four 16 x 16 accumulators (bi, bj) of v_mfma_f32_16x16x32_bf16; in each, lane l holds
+// row 16 bi + l % 16 and the four columns 16 bj + 4 (l / 16) .. + 3: pk[2 bi + bj] is that group packed.
+// dst = the block's first element.
+__device__ __forceinline__ void store_block_staged16(const uint2 (&pk)[4], uint16_t* dst, int ldc, int rows_live,
+                                                     unsigned char* stage, int lane) {
+    const int l16 = lane & 15, kq = lane >> 4;
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-        *reinterpret_cast<uint2*>(stage + r32 * kStageStride + q * 16 + half * 8) = pk[q];
+    for (int b = 0; b < 4; ++b)
+        *reinterpret_cast<uint2*>(stage + ((b >> 1) * 16 + l16) * kStageStride + (b & 1) * 32 + kq * 8) = pk[b];
     wave_lds_order();
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
@@ -342,93 +346,82 @@ __device__ __forceinline__ void store_block_staged(const uint2 (&pk)[4], uint16_
     wave_lds_order();                                    // the next block overwrites the patch
 }
 
-// Two horizontally adjacent 32 x 32 blocks (64 columns = one 128-byte line per row), 16 rows at a time: the half of
-// the lanes that owns those rows writes them to the patch (row stride 144 bytes), then eight lanes read one row
-// back and a store instruction writes 8 rows x 128 bytes: whole lines (down projection of the 8-expert workload
-// another 1.5 % over the 64-byte pieces).
+// Two horizontally adjacent 32 x 32 blocks (64 columns = one 128-byte line per row), 16 rows at a time (row stride
+// 144 bytes): eight lanes read one row back and a store instruction writes 8 rows x 128 bytes, whole lines (down
+// projection of the 8-expert workload another 1.5 % over the 64-byte pieces).
 constexpr int kPairStride = 144;
 static_assert(16 * kPairStride <= kStageBytes, "the pair patch must fit the per-wave patch");
-__device__ __forceinline__ void store_block_pair_staged(const uint2 (&pk0)[4], const uint2 (&pk1)[4], uint16_t* dst, int ldc,
-                                                        int rows_live, unsigned char* stage, int lane) {
-    const int r32 = lane & 31, half = lane >> 5;
+__device__ __forceinline__ void store_block_pair_staged16(const uint2 (&pk0)[4], const uint2 (&pk1)[4], uint16_t* dst, int ldc,
+                                                          int rows_live, unsigned char* stage, int lane) {
+    const int l16 = lane & 15, kq = lane >> 4;
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-        if ((r32 >> 4) == pass) {
-            unsigned char* row = stage + (r32 & 15) * kPairStride + half * 8;
+    for (int pass = 0; pass < 2; ++pass) {                // rows 16 pass .. + 15: every lane owns a piece of them
+        unsigned char* row = stage + l16 * kPairStride + kq * 8;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                *reinterpret_cast<uint2*>(row + q * 16) = pk0[q];
-                *reinterpret_cast<uint2*>(row + 64 + q * 16) = pk1[q];
-            }
+        for (int bj = 0; bj < 2; ++bj) {
+            *reinterpret_cast<uint2*>(row + bj * 32) = pk0[pass * 2 + bj];
+            *reinterpret_cast<uint2*>(row + 64 + bj * 32) = pk1[pass * 2 + bj];
         }
         wave_lds_order();
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int r = h * 8 + (lane >> 3), ch = lane & 7;
             const uint4 v = *reinterpret_cast<const uint4*>(stage + r * kPairStride + ch * 16);
-            const int row = pass * 16 + r;
-            if (row < rows_live) *reinterpret_cast<uint4*>(dst + static_cast<size_t>(row) * ldc + ch * 8) = v;
+            const int rr = pass * 16 + r;
+            if (rr < rows_live) *reinterpret_cast<uint4*>(dst + static_cast<size_t>(rr) * ldc + ch * 8) = v;
         }
         wave_lds_order();
     }
 }
-
-template <bool GLU, bool DUAL, int TI, int TB, bool KEEP = false>
-__device__ __forceinline__ void store_blocks_staged(const GemmParams& p, const f32x16 (&acc)[TI][TB], int e, int m_base,
-                                                    int n_base, int count, int lane, unsigned char* stage) {
-    constexpr int TO = GLU ? TB / 2 : TB;
+// acc[i][j]: token block i (16 rows) x weight block j (16 rows of the staged weights; SwiGLU: 0, 1 gate and 2, 3 up
+// rows of the same 32 columns; plain: 64 columns)
+template <bool GLU, bool DUAL, bool KEEP = false>
+__device__ __forceinline__ void store_blocks_staged16(const GemmParams& p, const f32x4 (&acc)[8][4], int e, int m_base,
+                                                      int n_base, int count, int lane, unsigned char* stage) {
     const size_t eoff = static_cast<size_t>(e) * p.capacity * p.N;
     uint16_t* Cg = reinterpret_cast<uint16_t*>(p.C) + eoff;
     uint16_t* C2g = (GLU && (DUAL || KEEP)) ? reinterpret_cast<uint16_t*>(p.C2) + eoff : nullptr;
     uint16_t* C3g = (GLU && !DUAL && KEEP) ? reinterpret_cast<uint16_t*>(p.C3) + eoff : nullptr;
+    auto pack4 = [](const f32x4& v) { return pack_bf16x4(v[0], v[1], v[2], v[3]); };
 #pragma unroll
-    for (int i = 0; i < TI; ++i) {
-        const int mb = m_base + i * 32;
-        const int live = count - mb;                     // rows of this block that exist (may be <= 0 or > 32)
+    for (int ib = 0; ib < 4; ++ib) {
+        const int mb = m_base + ib * 32;
+        const int live = count - mb;
         if (live <= 0) continue;                         // wave-uniform
-        if constexpr (!GLU && TO % 2 == 0) {               // plain product: pairs of blocks leave as whole lines
+        const size_t o = static_cast<size_t>(mb) * p.N + n_base;
+        uint2 pk[4], pk1[4];
+        if constexpr (!GLU) {
 #pragma unroll
-            for (int j = 0; j < TO; j += 2) {
-                uint2 pk0[4], pk1[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    pk0[q] = pack_bf16x4(acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
-                    pk1[q] = pack_bf16x4(acc[i][j + 1][q * 4], acc[i][j + 1][q * 4 + 1], acc[i][j + 1][q * 4 + 2], acc[i][j + 1][q * 4 + 3]);
-                }
-                store_block_pair_staged(pk0, pk1, Cg + static_cast<size_t>(mb) * p.N + n_base + j * 32, p.N, live, stage, lane);
+            for (int b = 0; b < 4; ++b) {
+                pk[b] = pack4(acc[2 * ib + (b >> 1)][b & 1]);
+                pk1[b] = pack4(acc[2 * ib + (b >> 1)][2 + (b & 1)]);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            continue;
-        }
+            store_block_pair_staged16(pk, pk1, Cg + o, p.N, live, stage, lane);
+        } else {
+            if constexpr (!DUAL) {
 #pragma unroll
-        for (int j = 0; j < TO; ++j) {
-            const size_t o = static_cast<size_t>(mb) * p.N + n_base + j * 32;
-            const f32x16& g0 = acc[i][j];
-            uint2 pk[4];
-            if constexpr (GLU && !DUAL) {
-                const f32x16& g1 = acc[i][TO + j];
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    pk[q] = pack_bf16x4(silu(g0[q * 4]) * g1[q * 4], silu(g0[q * 4 + 1]) * g1[q * 4 + 1],
-                                        silu(g0[q * 4 + 2]) * g1[q * 4 + 2], silu(g0[q * 4 + 3]) * g1[q * 4 + 3]);
+                for (int b = 0; b < 4; ++b) {
+                    const f32x4& g0 = acc[2 * ib + (b >> 1)][b & 1];
+                    const f32x4& g1 = acc[2 * ib + (b >> 1)][2 + (b & 1)];
+                    pk[b] = pack_bf16x4(silu(g0[0]) * g1[0], silu(g0[1]) * g1[1], silu(g0[2]) * g1[2], silu(g0[3]) * g1[3]);
+                }
             } else {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) pk[q] = pack_bf16x4(g0[q * 4], g0[q * 4 + 1], g0[q * 4 + 2], g0[q * 4 + 3]);
+                for (int b = 0; b < 4; ++b) pk[b] = pack4(acc[2 * ib + (b >> 1)][b & 1]);
             }
-            store_block_staged(pk, Cg + o, p.N, live, stage, lane);
-            if constexpr (GLU && (DUAL || KEEP)) {           // the two products themselves
-                const f32x16& g1 = acc[i][TO + j];
+            store_block_staged16(pk, Cg + o, p.N, live, stage, lane);
+            if constexpr (DUAL || KEEP) {                    // the two products themselves
                 if constexpr (KEEP) {
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) pk[q] = pack_bf16x4(g0[q * 4], g0[q * 4 + 1], g0[q * 4 + 2], g0[q * 4 + 3]);
-                    store_block_staged(pk, C2g + o, p.N, live, stage, lane);
+                    for (int b = 0; b < 4; ++b) pk[b] = pack4(acc[2 * ib + (b >> 1)][b & 1]);
+                    store_block_staged16(pk, C2g + o, p.N, live, stage, lane);
                 }
 #pragma unroll
-                for (int q = 0; q < 4; ++q) pk[q] = pack_bf16x4(g1[q * 4], g1[q * 4 + 1], g1[q * 4 + 2], g1[q * 4 + 3]);
-                store_block_staged(pk, (KEEP ? C3g : C2g) + o, p.N, live, stage, lane);
+                for (int b = 0; b < 4; ++b) pk[b] = pack4(acc[2 * ib + (b >> 1)][2 + (b & 1)]);
+                store_block_staged16(pk, (KEEP ? C3g : C2g) + o, p.N, live, stage, lane);
             }
         }
-        __builtin_amdgcn_sched_barrier(0);               // one row of blocks at a time: keeps the live set small
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -1027,41 +1020,50 @@ __device__ __forceinline__ void live_tile_prefix(const GemmParams& p, int BM, in
 // Measured on a copy-only loop over L2-resident data the line-sized pieces move 1.6 times the bytes per cycle of
 // the half-line ones, and in the ring kernel the copies, not the matrix pipe, set the cycle count.
 //
-// Two LDS buffers of 64 KiB (256 token rows + 256 weight rows x 128 bytes).  Step g multiplies buffer g & 1 in four
-// k-substeps.  When the fourth substep's fragments have been asked for nobody reads that buffer any more: behind
-// one wait (all copies landed, all own LDS reads done) and one barrier it is released.
+// Matrix instruction: v_mfma_f32_16x16x32_bf16.  The part is power-limited under this kernel, and a register-
+// resident loop on random operands sustains 2.0 PFLOP/s with this shape against 1.77 with 32x32x16 (a fifth fewer
+// register operands per flop).  Eight waves, two per SIMD; a wave's 128 x 64 slice of the 256 x 256 tile is 8 x 4
+// accumulators of 16 x 16 (128 registers).  In an accumulator lane l holds token row l % 16 and the four output
+// columns 4 (l / 16) .. + 3 (the weight fragment is the row operand).
 //
-// Copies.  A wave's copies of k-tile g + 2 are spread over SP k-substeps: its groups of token rows go out between
-// the MFMAs of the fourth substep of step g, its groups of weight rows between the MFMAs of the first substep of
-// step g + 1 (SP = 2; SP = 1 puts everything into the fourth substep, SP = 3 moves half of the weight rows on into
-// the second substep).  64 KiB inside one substep is twice what a CU's address unit takes in that time, and a wave
-// that waits for a slot there issues no MFMA either; all of them land before the barrier of step g + 1.  The weight
-// rows of a tile are whole column tiles (a launch condition), so their addresses are a wave-uniform base plus one
-// of two per-lane offsets that never change; only the token rows carry per-tile lane offsets.  There is always
-// something to copy: past the end of a workgroup's list the last k-tile is fetched again into a buffer nobody
-// reads any more, which keeps the unrolled MFMA sequences free of branches.
+// Two LDS buffers of 64 KiB (256 token rows + 256 weight rows x 128 bytes).  Step g multiplies buffer g & 1: two
+// k-steps of 32 (ks), each split into the token blocks 0..3 and 4..7 (h), four substeps u = 2 ks + h of 16 MFMAs.
+// Fragments: lane l reads row l % 16 of a 16-row block and the 16-byte chunk 4 ks + l / 16 of the k-tile (the
+// chunk index is XORed with bits of the row on the copy's source side, which keeps each group of 16 lanes on 64
+// distinct banks).  Token fragments are double-buffered by h, weight fragments by ks; every fragment read sits
+// behind one MFMA of the substep before the one that needs it.  When the fourth substep's fragments have been asked
+// for nobody reads that buffer any more: behind one wait (all copies landed, all own LDS reads done) and one
+// barrier it is released.
+//
+// Copies (global_load_lds, no registers).  A wave's copies of k-tile g + 2 go out behind every other MFMA of the
+// first half of two substeps: its groups of token rows in the fourth substep of step g (right behind the barrier),
+// its groups of weight rows in the first substep of step g + 1.  All eight in one substep is twice what a CU's
+// address unit takes in that time, and a wave that waits for a slot there issues no MFMA either (7 % slower); half
+// a substep later in each costs 1-4 %.  All of them land before the barrier of step g + 1.  The weight rows of a
+// tile are whole column tiles (a launch condition), so their addresses are a wave-uniform base plus one of two
+// per-lane offsets that never change; only the token rows carry per-tile lane offsets.  There is always something
+// to copy: past the end of a workgroup's list the last k-tile is fetched again into a buffer nobody reads any
+// more, which keeps the unrolled MFMA sequences free of branches.
 //
 // Gathered token rows (row_index).  The 256 row indices of a tile travel through LDS as well: 4-byte
 // asynchronous copies by waves 0..3, requested two tiles ahead, so no wave ever waits for a global load while it
 // sets up a tile.  Three slots rotate; a slot is read one tile after it was requested (at least two barriers with
 // vmcnt(0) lie in between) and rewritten two tiles after it was read.
 //
-// Fragment reads of the next substep are issued after the first MFMA row of the current one, so the wait in
-// front of a substep's first MFMA only ever covers reads that are most of a substep old.
-//
-// NW = 8 (two waves per SIMD, a 128 x 64 accumulator slice each) is what is launched.  NW = 4 (one wave per SIMD,
-// 128 x 128 slices in 256 accumulator registers, a third fewer LDS bytes per flop and half the barriers) was
-// measured 1-5 % slower on every workload: with one wave per SIMD nothing covers a wave's own waits.
+// Measured and not kept in this kernel (per-wave cycle stamps around the barrier, 16-expert 11008-wide workload):
+// a step of the 32x32x16 form took 2900 cycles for 2048 cycles of MFMA work at 1.67 GHz, 320 of them waiting for
+// copies.  Staging the operands through registers (plain loads issued a whole step ahead and evenly spread, LDS
+// writes behind the barrier) removed that wait and brought the step to 2540 cycles, and the clock fell to
+// 1.49 GHz: the same time.  One wave per SIMD with 128 x 128 slices (a third fewer LDS bytes per flop) needs
+// 2700-2900 cycles of issue alone.  One memory instruction behind each MFMA instead of groups: the same time.
 // ---------------------------------------------------------------------------------------
-template <bool GLU, bool DUAL = false, bool KEEP = false, int NW = 8, int SP = 2>
-__global__ __launch_bounds__(NW * 64) void gemm_bf16_persistent_kernel(GemmParams p) {
+template <bool GLU, bool DUAL = false, bool KEEP = false>
+__global__ __launch_bounds__(512) void gemm_bf16_persistent_kernel(GemmParams p) {
     static_assert(!KEEP || (GLU && !DUAL), "the pre-activations are kept by the SwiGLU epilogue only");
-    static_assert(NW == 4 || NW == 8, "one or two waves per SIMD");
-    static_assert(SP >= 1 && SP <= 3, "substeps the copies of a k-tile are spread over");
+    constexpr int NW = 8;                                // waves: 2 (token halves) x 4 (weight quarters)
     constexpr int BM = 256, BR = 256, CPR = 8, SWZ = 1;
     constexpr int BN = GLU ? 128 : 256;
     constexpr int STAGE = (BM + BR) * CPR;               // uint4 per LDS buffer (64 KiB)
-    constexpr int WN = NW / 2, TB = 8 / WN;              // wave grid 2 x WN; weight fragments per wave and k-substep
     constexpr int NCP = 32 / NW;                         // groups of 8 rows each wave copies per operand
     constexpr int WROWS = 8 * NCP;                       // staged rows of each operand a wave copies
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -1073,8 +1075,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_persistent_kernel(GemmParam
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
-    const int r32 = lane & 31, half = lane >> 5;
+    const int wm = wave >> 2, wn = wave & 3;
     const int KCA = (p.lda ? p.lda : p.K) / 8, KCB = (p.ldb ? p.ldb : p.K) / 8;
     const bool gather = p.row_index != nullptr;
 
@@ -1154,48 +1155,34 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_persistent_kernel(GemmParam
         copy_to(bbase + i * strideB8, laneB[i & 1], lds + buf * STAGE + BM * CPR + (wave * NCP + i) * 64);
     };
 
-    const int sw = (r32 >> SWZ) & 7;
-    int a_row[4], b_row[TB];
+    // fragments: fah[h][i] = token block 4 h + i, fbk[ks][j] = weight block j of k-step ks
+    f32x4 acc[8][4];
+    bf16x8 fah[2][4], fbk[2][4];
+    const int l16 = lane & 15, kq = lane >> 4;
+    const int a_row = (wm * 128 + l16) * CPR;
+    int b_row[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) a_row[i] = (wm * 128 + i * 32 + r32) * CPR;
-#pragma unroll
-    for (int j = 0; j < TB; ++j) {
-        const int br = GLU ? ((j / (TB / 2)) * 128 + wn * (16 * TB) + (j % (TB / 2)) * 32) : (wn * (32 * TB) + j * 32);
-        b_row[j] = BM * CPR + (br + r32) * CPR;
+    for (int j = 0; j < 4; ++j) {
+        // SwiGLU: blocks 0, 1 are gate rows and 2, 3 the up rows of the same 32 output columns; plain: 64 columns
+        const int br = GLU ? ((j >> 1) * 128 + wn * 32 + (j & 1) * 16) : (wn * 64 + j * 16);
+        b_row[j] = BM * CPR + (br + l16) * CPR;
     }
-    int ck[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) ck[ks] = (ks * 2 + half) ^ sw;
-
-    f32x16 acc[4][TB];
-    bf16x8 fa[2][4], fb[2][TB];
-    auto load_frags = [&](int set, int buf, int ks) {
-        const uint4* base = lds + buf * STAGE + ck[ks];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) fa[set][i] = __builtin_bit_cast(bf16x8, base[a_row[i]]);
-#pragma unroll
-        for (int j = 0; j < TB; ++j) fb[set][j] = __builtin_bit_cast(bf16x8, base[b_row[j]]);
+    const int ck[2] = {kq ^ ((l16 >> SWZ) & 7), (4 + kq) ^ ((l16 >> SWZ) & 7)};
+    auto read_a = [&](int buf, int ks, int h, int idx) {
+        fah[h][idx] = __builtin_bit_cast(bf16x8, lds[buf * STAGE + a_row + (4 * h + idx) * 16 * CPR + ck[ks]]);
     };
-    auto mfma_row = [&](int set, int i) {
-#pragma unroll
-        for (int j = 0; j < TB; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
+    auto read_b = [&](int buf, int ks, int idx) {
+        fbk[ks][idx] = __builtin_bit_cast(bf16x8, lds[buf * STAGE + b_row[idx] + ck[ks]]);
     };
-    // Which copies go out behind MFMA row `i` of a substep.  Token-row groups: all in the releasing (fourth)
-    // substep, NCP / 4 per row.  Weight-row groups: SP = 1 in the fourth substep as well; SP = 2 in the first
-    // substep of the next step; SP = 3 half there, half in the second substep.
-    constexpr int APR = NCP / 4 > 0 ? NCP / 4 : 1;       // token-row groups per MFMA row (NW = 8: NCP = 4 -> 1)
-    auto copies_a = [&](uint64_t abase, const uint32_t* off, int buf, int i) {
+    // substep u = 2 ks + h; `mem(m)` is the memory work behind its m-th MFMA
+    auto substep = [&](int u, auto&& mem) {
+        const int ks = u >> 1, h = u & 1;
 #pragma unroll
-        for (int c = 0; c < APR; ++c) copy_a(abase, off[i * APR + c], buf, i * APR + c);
-    };
-    auto copies_b = [&](uint64_t bbase, int buf, int i, int part, int parts) {   // behind row i of substep `part` of `parts`
-        if (parts == 1) {
-#pragma unroll
-            for (int c = 0; c < APR; ++c) copy_b(bbase, buf, i * APR + c);
-        } else if ((i & 1) == part) {                     // two substeps: the even rows carry the first half
-#pragma unroll
-            for (int c = 0; c < APR; ++c) copy_b(bbase, buf, part * (NCP / 2) + (i >> 1) * APR + c);
+        for (int m = 0; m < 16; ++m) {
+            const int i = m >> 2, j = m & 3;
+            acc[4 * h + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fbk[ks][j], fah[h][i], acc[4 * h + i][j], 0, 0, 0);
+            mem(m);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -1211,7 +1198,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_persistent_kernel(GemmParam
             request_rows(nxt, 1);
         }
         __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, false));
-        __builtin_amdgcn_s_barrier();                    // NW = 8: the indices were fetched by other waves
+        __builtin_amdgcn_s_barrier();                    // the indices were fetched by other waves
     }
     finish(cur, 0);
     int g = 0;                                           // global step: buffer g & 1
@@ -1223,7 +1210,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_persistent_kernel(GemmParam
     }
     __builtin_amdgcn_s_waitcnt(waitcnt_imm(2 * NCP, false));             // the first k-tile (copies retire in order)
     __builtin_amdgcn_s_barrier();
-    load_frags(0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { read_a(0, 0, 0, i); read_b(0, 0, i); }
     uint64_t lateB = cur.Bbase + 128;                    // weight rows still owed to the other buffer (none yet:
                                                          // the second k-tile's own once more)
     for (;;) {
@@ -1240,11 +1228,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_persistent_kernel(GemmParam
             }
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-            for (int j = 0; j < TB; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+                for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
         const int KT = cur.KT;
         for (int kt = 0; kt < KT; ++kt, ++g) {
             // k-tile g + 2: of this tile, else of the next one, else (nothing left) this tile's last one again
@@ -1257,61 +1245,33 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_persistent_kernel(GemmParam
 #pragma unroll
             for (int i = 0; i < NCP; ++i) offs[i] = from_next ? nxt.offA[i] : cur.offA[i];
             const int buf = g & 1;
-            // substep 0 (SP >= 2: with weight rows of k-tile g + 1 into the other buffer)
             __builtin_amdgcn_sched_barrier(0);
-            mfma_row(0, 0);
-            if constexpr (SP >= 2) copies_b(lateB, buf ^ 1, 0, 0, SP - 1);
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(1, buf, 1);
-#pragma unroll
-            for (int i = 1; i < 4; ++i) {
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_row(0, i);
-                if constexpr (SP >= 2) copies_b(lateB, buf ^ 1, i, 0, SP - 1);
-            }
-            // substep 1 (SP = 3: with the other half of those weight rows)
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_row(1, 0);
-            if constexpr (SP == 3) copies_b(lateB, buf ^ 1, 0, 1, 2);
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(0, buf, 2);
-#pragma unroll
-            for (int i = 1; i < 4; ++i) {
-                if constexpr (SP == 3) __builtin_amdgcn_sched_barrier(0);
-                mfma_row(1, i);
-                if constexpr (SP == 3) copies_b(lateB, buf ^ 1, i, 1, 2);
-            }
-            // substep 2
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_row(0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(1, buf, 3);
-            mfma_row(0, 1); mfma_row(0, 2); mfma_row(0, 3);
-            __builtin_amdgcn_sched_barrier(0);
+            substep(0, [&](int m) {                      // token blocks 4..7 of this k-step, half of the next k-step's weights,
+                if (m < 4) read_a(buf, 0, 1, m);         // and the weight rows of k-tile g + 1 into the other buffer
+                else if (m < 6) read_b(buf, 1, m - 4);
+                if (m < 8 && (m & 1)) copy_b(lateB, buf ^ 1, m >> 1);
+            });
+            substep(1, [&](int m) {
+                if (m < 4) read_a(buf, 1, 0, m);
+                else if (m < 6) read_b(buf, 1, m - 2);
+            });
+            substep(2, [&](int m) {
+                if (m < 4) read_a(buf, 1, 1, m);
+            });
             // k-tile g + 1 has landed and this wave's reads of buffer buf are done; past the barrier that holds for all
             __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, true));
             __builtin_amdgcn_s_barrier();
-            // substep 3, with the token rows of k-tile g + 2 into the buffer just released
             __builtin_amdgcn_sched_barrier(0);
-            mfma_row(1, 0);
-            copies_a(baseA, offs, buf, 0);
-            if constexpr (SP == 1) copies_b(baseB, buf, 0, 0, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(0, buf ^ 1, 0);
-#pragma unroll
-            for (int i = 1; i < 4; ++i) {
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_row(1, i);
-                copies_a(baseA, offs, buf, i);
-                if constexpr (SP == 1) copies_b(baseB, buf, i, 0, 1);
-            }
-            __builtin_amdgcn_sched_barrier(0);
+            substep(3, [&](int m) {                      // the next k-tile's first fragments, and the token rows of k-tile
+                if (m < 4) read_a(buf ^ 1, 0, 0, m);     // g + 2 into the buffer just released
+                else if (m < 8) read_b(buf ^ 1, 0, m - 4);
+                if (m < 8 && (m & 1)) copy_a(baseA, offs[m >> 1], buf, m >> 1);
+            });
             lateB = baseB;
         }
         // ---- epilogue of cur (the copies of the next tile are in flight)
-        constexpr int TO = GLU ? TB / 2 : TB;
-        store_blocks_staged<GLU, DUAL, 4, TB, KEEP>(p, acc, cur.e, cur.m0 + wm * 128, cur.n0 + wn * (32 * TO), cur.count, lane,
-                                                    stage_all + wave * kStageBytes);
+        store_blocks_staged16<GLU, DUAL, KEEP>(p, acc, cur.e, cur.m0 + wm * 128, cur.n0 + wn * (GLU ? 32 : 64), cur.count, lane,
+                                               stage_all + wave * kStageBytes);
         if (!has_next) break;
         cur = nxt;
         q = qn;
@@ -1440,14 +1400,14 @@ hipError_t launch_bf16_persist(GemmParams p, hipStream_t st, int n_cu) {
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(512), lds, st, p);
     return hipGetLastError();
 }
-template <bool GLU, bool DUAL = false, bool KEEP = false, int NW = 8, int SP = 2>
+template <bool GLU, bool DUAL = false, bool KEEP = false>
 hipError_t launch_bf16_persistent(GemmParams p, hipStream_t st, int n_cu) {
     constexpr size_t lds = 2ull * 512 * 64 * 2;                             // two buffers of 256 + 256 rows x 64 bf16
     plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_persistent_kernel<GLU, DUAL, KEEP, NW, SP>;
+    auto kern = gemm_bf16_persistent_kernel<GLU, DUAL, KEEP>;
     hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(NW * 64), lds, st, p);
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(512), lds, st, p);
     return hipGetLastError();
 }
 // the 64-wide persistent kernel also wants whole column tiles (its weight-row addresses are not clamped)
