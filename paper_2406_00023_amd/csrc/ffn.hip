@@ -3,7 +3,8 @@
 // Experimental Setup: Mixtral experts).  This is the one dense contraction of the layer
 // and the operator the paper reports as dominant ("FFN MatMul").
 //
-// bf16: two grouped "NT" GEMMs on the MFMA units (v_mfma_f32_32x32x16_bf16), fp32
+// bf16: two grouped "NT" GEMMs on the MFMA units (v_mfma_f32_16x16x32_bf16 in the persistent
+// kernel the layer launches, v_mfma_f32_32x32x16_bf16 in the other forms), fp32
 // accumulation.  Both operands are K-contiguous, staged through LDS in 16-byte chunks
 // with an XOR swizzle, double-buffered.  GEMM-1 computes the gate and the up projection
 // of the same output tile so that SiLU(g)*u is its epilogue and the hidden activation

@@ -75,12 +75,17 @@ SMALL = {
     # 64-wide persistent kernel (two-product and pre-activation-keeping epilogues, rows gathered through LDS)
     "cfg2w": lambda: I.small_variant(I.CONFIGS["cfg2"], T=1300, d=512, H=640),
     "cfg5w": lambda: I.small_variant(I.CONFIGS["cfg5"], T=900, H=256),
+    # a capacity of 8192 rows and whole 256-column tiles for both u and the input gradient: the two products against
+    # a weight matrix run on the row-major kernel with the weight transposed once (the overloaded experts of this
+    # recipe keep a few thousand rows, the others few)
+    "cfg2r": lambda: I.CONFIGS["cfg2"].with_(T=12000, d=256, H=256, capacity=8192, name="cfg2-rows"),
 }
 
 
 @pytest.mark.parametrize("name,mode,cos", [("cfg1", TCR, FULL), ("cfg1", ECR, POOLED), ("cfg1", BIDIR, FULL),
                                            ("cfg2s", TCR, FULL), ("cfg3s", ECR, FULL), ("cfg4s", BIDIR, POOLED),
-                                           ("cfg5s", BIDIR, FULL), ("cfg2w", TCR, FULL), ("cfg5w", BIDIR, POOLED)])
+                                           ("cfg5s", BIDIR, FULL), ("cfg2w", TCR, FULL), ("cfg5w", BIDIR, POOLED),
+                                           ("cfg2r", TCR, FULL)])
 def test_backward_small_all_gradients(H, oracle, name, mode, cos):
     shape = SMALL[name]()
     _say(f"backward case {name} mode={mode} cos={cos} T={shape.T} d={shape.d} E={shape.E} C={shape.capacity} H={shape.H}")
