@@ -322,10 +322,20 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_bf16_kernel(GemmParams p) 
 constexpr int kStageStride = 80;                         // bytes per staged row: 64 of data + 16 so that rows spread over the banks
 constexpr int kStageBytes = 32 * kStageStride;           // per wave
 
-__device__ __forceinline__ void wave_lds_order() {       // orders this wave's LDS accesses in the instruction stream
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+// The patch is written and read back in assembly.  Through ordinary LDS accesses the compiler puts a vmcnt(0) in
+// front of every one of them while asynchronous copies into LDS are in flight (it cannot tell that the next tile's
+// k-tiles land elsewhere), and that wait also covers the stores this epilogue has just issued: every block then
+// waited for the previous block's stores to reach memory, 4-7 thousand cycles per tile.  LDS instructions of one
+// wave execute in order, so a write followed by a read needs no wait in between; each statement ends with its
+// own lgkmcnt(0), so its outputs are ordinary, fully written registers.
+typedef int epi_v2i __attribute__((ext_vector_type(2)));
+typedef int epi_v4i __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const char*)p));
+}
+__device__ __forceinline__ epi_v2i as_v2i(const uint2& v) { return epi_v2i{static_cast<int>(v.x), static_cast<int>(v.y)}; }
+__device__ __forceinline__ uint4 as_uint4(const epi_v4i& v) {
+    return make_uint4(static_cast<uint32_t>(v.x), static_cast<uint32_t>(v.y), static_cast<uint32_t>(v.z), static_cast<uint32_t>(v.w));
 }
 
 // One 32 x 32 output block = four 16 x 16 accumulators (bi, bj) of v_mfma_f32_16x16x32_bf16; in each, lane l holds
@@ -334,17 +344,24 @@ __device__ __forceinline__ void wave_lds_order() {       // orders this wave's L
 __device__ __forceinline__ void store_block_staged16(const uint2 (&pk)[4], uint16_t* dst, int ldc, int rows_live,
                                                      unsigned char* stage, int lane) {
     const int l16 = lane & 15, kq = lane >> 4;
-#pragma unroll
-    for (int b = 0; b < 4; ++b)
-        *reinterpret_cast<uint2*>(stage + ((b >> 1) * 16 + l16) * kStageStride + (b & 1) * 32 + kq * 8) = pk[b];
-    wave_lds_order();
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-        const int row = pass * 16 + (lane >> 2), ch = lane & 3;
-        const uint4 v = *reinterpret_cast<const uint4*>(stage + row * kStageStride + ch * 16);
-        if (row < rows_live) *reinterpret_cast<uint4*>(dst + static_cast<size_t>(row) * ldc + ch * 8) = v;
-    }
-    wave_lds_order();                                    // the next block overwrites the patch
+    const uint32_t wa = lds_address(stage) + l16 * kStageStride + kq * 8;          // + 32 bj + 16 rows * bi
+    const uint32_t ra = lds_address(stage) + (lane >> 2) * kStageStride + (lane & 3) * 16;
+    epi_v4i v0, v1;
+    static_assert(16 * kStageStride == 1280, "offsets in the statement below");
+    asm volatile(
+        "ds_write_b64 %2, %4\n\t"
+        "ds_write_b64 %2, %5 offset:32\n\t"
+        "ds_write_b64 %2, %6 offset:1280\n\t"
+        "ds_write_b64 %2, %7 offset:1312\n\t"
+        "ds_read_b128 %0, %3\n\t"
+        "ds_read_b128 %1, %3 offset:1280\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(v0), "=&v"(v1)
+        : "v"(wa), "v"(ra), "v"(as_v2i(pk[0])), "v"(as_v2i(pk[1])), "v"(as_v2i(pk[2])), "v"(as_v2i(pk[3]))
+        : "memory");
+    const int row = lane >> 2, ch = lane & 3;
+    if (row < rows_live) *reinterpret_cast<uint4*>(dst + static_cast<size_t>(row) * ldc + ch * 8) = as_uint4(v0);
+    if (row + 16 < rows_live) *reinterpret_cast<uint4*>(dst + static_cast<size_t>(row + 16) * ldc + ch * 8) = as_uint4(v1);
 }
 
 // Two horizontally adjacent 32 x 32 blocks (64 columns = one 128-byte line per row), 16 rows at a time (row stride
@@ -355,23 +372,27 @@ static_assert(16 * kPairStride <= kStageBytes, "the pair patch must fit the per-
 __device__ __forceinline__ void store_block_pair_staged16(const uint2 (&pk0)[4], const uint2 (&pk1)[4], uint16_t* dst, int ldc,
                                                           int rows_live, unsigned char* stage, int lane) {
     const int l16 = lane & 15, kq = lane >> 4;
+    const uint32_t wa = lds_address(stage) + l16 * kPairStride + kq * 8;
+    const uint32_t ra = lds_address(stage) + (lane >> 3) * kPairStride + (lane & 7) * 16;
+    static_assert(8 * kPairStride == 1152, "offset in the statement below");
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {                // rows 16 pass .. + 15: every lane owns a piece of them
-        unsigned char* row = stage + l16 * kPairStride + kq * 8;
-#pragma unroll
-        for (int bj = 0; bj < 2; ++bj) {
-            *reinterpret_cast<uint2*>(row + bj * 32) = pk0[pass * 2 + bj];
-            *reinterpret_cast<uint2*>(row + 64 + bj * 32) = pk1[pass * 2 + bj];
-        }
-        wave_lds_order();
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int r = h * 8 + (lane >> 3), ch = lane & 7;
-            const uint4 v = *reinterpret_cast<const uint4*>(stage + r * kPairStride + ch * 16);
-            const int rr = pass * 16 + r;
-            if (rr < rows_live) *reinterpret_cast<uint4*>(dst + static_cast<size_t>(rr) * ldc + ch * 8) = v;
-        }
-        wave_lds_order();
+        epi_v4i v0, v1;
+        asm volatile(
+            "ds_write_b64 %2, %4\n\t"
+            "ds_write_b64 %2, %5 offset:32\n\t"
+            "ds_write_b64 %2, %6 offset:64\n\t"
+            "ds_write_b64 %2, %7 offset:96\n\t"
+            "ds_read_b128 %0, %3\n\t"
+            "ds_read_b128 %1, %3 offset:1152\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(v0), "=&v"(v1)
+            : "v"(wa), "v"(ra), "v"(as_v2i(pk0[pass * 2])), "v"(as_v2i(pk0[pass * 2 + 1])), "v"(as_v2i(pk1[pass * 2])),
+              "v"(as_v2i(pk1[pass * 2 + 1]))
+            : "memory");
+        const int r = pass * 16 + (lane >> 3), ch = lane & 7;
+        if (r < rows_live) *reinterpret_cast<uint4*>(dst + static_cast<size_t>(r) * ldc + ch * 8) = as_uint4(v0);
+        if (r + 8 < rows_live) *reinterpret_cast<uint4*>(dst + static_cast<size_t>(r + 8) * ldc + ch * 8) = as_uint4(v1);
     }
 }
 // acc[i][j]: token block i (16 rows) x weight block j (16 rows of the staged weights; SwiGLU: 0, 1 gate and 2, 3 up
