@@ -179,10 +179,13 @@ def test_select_external_scores(H, oracle, T, E, k, C, levels):
     # while it is still inside the first tile's prologue (GEMM-1 in the first case, GEMM-2 in the second)
     (I.DT_BF16, 8, 2048, 128, 1024, [2048, 1500, 2048, 300, 2047, 1025, 2048, 1800]),
     (I.DT_BF16, 8, 2048, 2048, 128, [2048, 1500, 0, 300, 2047, 1025, 2048, 1800]),
-    # whole column tiles in both GEMMs (the four-wave kernel): an odd number of k-tiles, an empty expert between
+    # whole column tiles in both GEMMs (the 64-wide persistent kernel): an odd number of k-tiles, an empty expert between
     # live ones, one-row and one-past-a-tile experts; then more live tiles than CUs with a long second contraction
     (I.DT_BF16, 6, 900, 768, 1152, [900, 0, 513, 1, 899, 256]),
     (I.DT_BF16, 8, 1100, 256, 2816, [1100, 700, 1, 1024, 0, 1025, 300, 1100]),
+    # sixteen and more row tiles per expert: the tile list is cut into 8 x 4 super-tiles in the second GEMM
+    # (d = 1024: four column tiles) and into one super-tile per row band in the first (H = 384: three column tiles)
+    (I.DT_BF16, 2, 4200, 1024, 384, [4200, 3333]),
 ])
 def test_expert_ffn(H, oracle, dtype, E, C, d, H_, counts):
     _say(f"case ffn dtype={dtype} E={E} C={C} d={d} H={H_} counts={counts}")
