@@ -138,7 +138,7 @@ constexpr int kRadixBits = 11;          // digit width of the threshold search: 
 
 // IPT > 0: the thread's ipt (<= IPT) keys live in registers.  IPT == 0: streamed from memory.
 // PRE: the histogram of the first digit (the top kRadixBits bits) comes from key_histogram_kernel (hist1, n_slices).
-template <int IPT, bool PRE = false>
+template <int IPT, bool PRE = false, bool ADAPT = false>
 __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32_t* __restrict__ keyT, int Tpad, int T,
                                                                     int ipt, int capacity_host, int mode,
                                                                     const int32_t* __restrict__ capacity_dev,
@@ -212,7 +212,7 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
     // prefix whose affinity sum reaches the threshold.  Affinities are summed as fixed-point
     // integers round(clamp(s,-1,1) * 2^30), so the sum of "all candidates with key >= theta" is
     // exact and order-free, and the prefix length follows from a bisection over theta.
-    if (sum_need > 0 && (mode == ETR_MODE_ECR || mode == ETR_MODE_BIDIR) && n_keep > 0) {
+    if constexpr (ADAPT) if (sum_need > 0 && (mode == ETR_MODE_ECR || mode == ETR_MODE_BIDIR) && n_keep > 0) {
         __shared__ long long red_sum[kSelThreads / kWave];
         __shared__ int red_cnt[kSelThreads / kWave];
         // sum and count over the candidates with key >= thr (thr >= key(+0): positive affinities only)
@@ -576,10 +576,14 @@ hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-#define ETR_EC(II, PP)                                                                                                \
-    hipLaunchKernelGGL((expert_choice_kernel<II, PP>), dim3(c.E), dim3(kSelThreads), 0, st, w.keyT, w.Tpad, c.T, w.ipt, \
+    // (the adaptive token count is an instantiation of its own: its double-precision sums over the keys in registers
+    // would otherwise cost the plain search of the long columns 100 spilled registers)
+    const bool adapt = sum_need > 0;
+#define ETR_EC1(II, PP, AA)                                                                                           \
+    hipLaunchKernelGGL((expert_choice_kernel<II, PP, AA>), dim3(c.E), dim3(kSelThreads), 0, st, w.keyT, w.Tpad, c.T, w.ipt, \
                        c.capacity, c.mode, capacity_dev, sum_need, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts, w.hist1, \
                        w.n_slices)
+#define ETR_EC(II, PP) do { if (adapt) ETR_EC1(II, PP, true); else ETR_EC1(II, PP, false); } while (0)
     if (w.ipt <= 4) ETR_EC(4, false);
     else if (w.ipt <= 8) ETR_EC(8, false);
     else if (w.ipt <= 16) ETR_EC(16, false);                // (no pre-pass up to here, see select_slices)
@@ -587,6 +591,7 @@ hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_
     else if (w.ipt <= 64) { if (pre) ETR_EC(64, true); else ETR_EC(64, false); }
     else { if (pre) ETR_EC(0, true); else ETR_EC(0, false); }
 #undef ETR_EC
+#undef ETR_EC1
     err = hipGetLastError();
     if (err != hipSuccess) return err;
 
