@@ -122,6 +122,30 @@ __device__ __forceinline__ int wave_sum_i(int v) {
     return v;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave, lane 0 first, by data-parallel-primitive moves: shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes (a lane whose source lies outside its row adds nothing), then lane 15 of
+// row 0 / 2 is added to all of row 1 / 3 and lane 31 to all of rows 2 and 3.  Call with all lanes active.
+__device__ __forceinline__ int wave_scan_incl(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);   // row_bcast:15 -> rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);   // row_bcast:31 -> rows 2, 3
+    return v;
+}
+
+// Sum over aligned groups of Q lanes (Q = 1, 2, 4, 8, 16), every lane of a group gets the group's total:
+// swaps inside quads, then the mirror images of the half row and of the row.  Call with all lanes active.
+template <int Q>
+__device__ __forceinline__ int lane_group_sum(int v) {
+    if constexpr (Q >= 2) v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);    // quad_perm [1,0,3,2]
+    if constexpr (Q >= 4) v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);    // quad_perm [2,3,0,1]
+    if constexpr (Q >= 8) v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false);   // row_half_mirror
+    if constexpr (Q >= 16) v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, false);  // row_mirror
+    return v;
+}
+
 // Block-wide sums of three counters (all threads get the totals).
 __device__ __forceinline__ void block_sum3(int& a, int& b, int& c, int (*red)[3]) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -134,10 +158,61 @@ __device__ __forceinline__ void block_sum3(int& a, int& b, int& c, int (*red)[3]
     for (int w = 0; w < kSelThreads / kWave; ++w) { a += red[w][0]; b += red[w][1]; c += red[w][2]; }
 }
 
-constexpr int kRadixBits = 11;          // digit width of the threshold search: 2048 bins, two per thread
+constexpr int kRadixBits = 11;           // digit width of the threshold search
+constexpr int kBins = 1 << kRadixBits;   // 2048 bins: 32 per lane of a wave
+constexpr int kMaxDigits = 3;            // 32 key bits in digits of at most 11
+constexpr int kMaxSlices = 16;           // workgroups per expert that count the first digit of a long column
 
-// IPT > 0: the thread's ipt (<= IPT) keys live in registers.  IPT == 0: streamed from memory.
+// A wave's view of one histogram of kBins counters in LDS (narrower digits leave the upper bins zero), walked
+// from the largest digit down: lane g owns the 32 bins [kBins - 32 (g + 1), kBins - 32 g).  Every wave of the
+// workgroup takes the same view by itself, so no barrier is needed between the histogram and its use.
+struct DigitView {
+    int own;       // candidates in this lane's 32 bins
+    int upto;      // candidates in the bins of lanes 0..g (inclusive scan)
+    int total;     // candidates in all bins
+};
+
+__device__ __forceinline__ DigitView digit_view(const uint32_t* hist) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint4* q4 = reinterpret_cast<const uint4*>(hist) + 8 * (kWave - 1 - lane);
+    int s = 0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {                       // the lane's eight quads, rotated by the lane: no bank conflicts
+        const uint4 v = q4[(q + lane) & 7];
+        s += static_cast<int>(v.x + v.y + v.z + v.w);
+    }
+    DigitView d;
+    d.own = s;
+    d.upto = wave_scan_incl(s);
+    d.total = __builtin_amdgcn_readlane(d.upto, kWave - 1);
+    return d;
+}
+
+// The digit that holds the need-th largest candidate (1 <= need <= total) and the number of candidates with a
+// larger digit.
+__device__ __forceinline__ void digit_pick(const uint32_t* hist, const DigitView& d, int need, int& digit, int& above) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint64_t m1 = __ballot(d.upto >= need);
+    const int g = m1 ? __builtin_ctzll(m1) : kWave - 1;                       // the lane whose bins hold it
+    const int before = __builtin_amdgcn_readlane(d.upto - d.own, g);
+    const int h = lane < 32 ? static_cast<int>(hist[kBins - 1 - 32 * g - lane]) : 0;   // its bins, largest first
+    const int upto = wave_scan_incl(h);
+    const uint64_t m2 = __ballot(before + upto >= need);
+    const int j = m2 ? __builtin_ctzll(m2) : 31;
+    digit = kBins - 1 - 32 * g - j;
+    above = before + __builtin_amdgcn_readlane(upto - h, j);
+}
+
+// One 1024-thread workgroup per expert.
+// IPT > 0 (4, 8, 16, 32, 64; equal to ipt): the column's keys live in registers.  Wave w holds the 64 chunks
+//   [64 w, 64 w + 64) of IPT tokens each, as IPT/4 rows of 64 pieces of four keys: row r, lane l is piece
+//   64 r + l of the wave's stretch of the column, so every load instruction reads 1 KiB in one piece.  The search
+//   does not care which lane holds which key; only the last step, the per-chunk counts, puts the pieces of a
+//   chunk (IPT/4 neighbouring lanes of one row) together.
+// IPT == 0: keys streamed from memory, thread t owns chunk t (columns longer than 64 keys per thread).
 // PRE: the histogram of the first digit (the top kRadixBits bits) comes from key_histogram_kernel (hist1, n_slices).
+// ADAPT: with the adaptive token count (an instantiation of its own: its double-precision sums over the keys in
+//   registers would otherwise cost the plain search of the long columns a hundred spilled registers).
 template <int IPT, bool PRE = false, bool ADAPT = false>
 __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32_t* __restrict__ keyT, int Tpad, int T,
                                                                     int ipt, int capacity_host, int mode,
@@ -149,61 +224,68 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
                                                                     int32_t* __restrict__ pre_eq,
                                                                     int32_t* __restrict__ counts,
                                                                     const uint32_t* __restrict__ hist1, int n_slices) {
+    constexpr int Q = IPT > 0 ? IPT / 4 : 1;            // rows of a wave = pieces of a chunk
+    static_assert(IPT == 0 || (IPT >= 4 && IPT <= 64 && (IPT & (IPT - 1)) == 0), "chunk lengths held in registers");
     __shared__ int red[kSelThreads / kWave][3];
     __shared__ int wave_tot[kSelThreads / kWave][2];
     __shared__ uint32_t range[kSelThreads / kWave][2];
-    __shared__ uint32_t hist[1 << kRadixBits];
-    __shared__ int sel[2];
+    __shared__ __attribute__((aligned(16))) uint32_t hist[kMaxDigits][kBins];
+    __shared__ int chunk_cnt[kSelThreads / kWave][kWave];
     const int e = blockIdx.x, tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
     // a capacity computed on the device (e.g. the lower bound of the Remark) may tighten the host one
     const int capacity = capacity_dev ? min(capacity_host, max(1, *capacity_dev)) : capacity_host;
     const uint32_t* col = keyT + static_cast<size_t>(e) * Tpad;
-    const int base = tid * ipt;
 
     uint32_t keys[IPT > 0 ? IPT : 1];
     if constexpr (IPT > 0) {
+        const int seg = wave * kWave * IPT;             // first token of the wave's stretch
 #pragma unroll
-        for (int j = 0; j < IPT; j += 4) {
-            const int idx = base + j;
+        for (int r = 0; r < Q; ++r) {
+            const int idx = seg + (r * kWave + lane) * 4;
             uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (j < ipt && idx < Tpad) v = *reinterpret_cast<const uint4*>(col + idx);   // ipt, Tpad multiples of 4
-            keys[j + 0] = idx + 0 < T ? v.x : 0u;
-            keys[j + 1] = idx + 1 < T ? v.y : 0u;
-            keys[j + 2] = idx + 2 < T ? v.z : 0u;
-            keys[j + 3] = idx + 3 < T ? v.w : 0u;
+            if (idx < Tpad) v = *reinterpret_cast<const uint4*>(col + idx);     // Tpad is a multiple of 4
+            keys[4 * r + 0] = idx + 0 < T ? v.x : 0u;
+            keys[4 * r + 1] = idx + 1 < T ? v.y : 0u;
+            keys[4 * r + 2] = idx + 2 < T ? v.z : 0u;
+            keys[4 * r + 3] = idx + 3 < T ? v.w : 0u;
         }
     }
-    // count_ge of up to three thresholds at once, over the whole column
-    auto count3 = [&](uint32_t t1, uint32_t t2, uint32_t t3, int& c1, int& c2, int& c3) {
-        c1 = c2 = c3 = 0;
+    // The histograms of all digits start at zero; the first barrier below lies between this and their first use.
+    if constexpr (PRE) {
+        // first digit: the slices' counts of this thread's two bins, added up (integer sums, any order)
+        static_assert(kSelThreads * 2 == kBins, "two bins of the first digit per thread");
+        const uint32_t* hp = hist1 + static_cast<size_t>(e) * n_slices * kBins + 2 * tid;
+        uint32_t s0 = 0u, s1 = 0u;
+#pragma unroll
+        for (int b = 0; b < kMaxSlices; ++b) {          // all loads in flight at once; slices past the last count as zero
+            const uint2 v = *reinterpret_cast<const uint2*>(hp + static_cast<size_t>(b < n_slices ? b : 0) * kBins);
+            const uint32_t on = b < n_slices ? 0xFFFFFFFFu : 0u;
+            s0 += v.x & on; s1 += v.y & on;
+        }
+        hist[0][2 * tid] = s0; hist[0][2 * tid + 1] = s1;
+    } else {
+        hist[0][2 * tid] = 0u; hist[0][2 * tid + 1] = 0u;
+    }
+#pragma unroll
+    for (int p = 1; p < kMaxDigits; ++p) { hist[p][2 * tid] = 0u; hist[p][2 * tid + 1] = 0u; }
+
+    int ncand;
+    DigitView first{0, 0, 0};                           // PRE: the view of the first digit
+    if constexpr (PRE) {
+        __syncthreads();
+        first = digit_view(hist[0]);
+        ncand = first.total;
+    } else {
+        int d1 = 0, d2 = 0;
+        ncand = 0;
         if constexpr (IPT > 0) {
 #pragma unroll
-            for (int j = 0; j < IPT; ++j) {
-                c1 += keys[j] >= t1; c2 += keys[j] >= t2; c3 += keys[j] >= t3;
-            }
+            for (int j = 0; j < IPT; ++j) ncand += keys[j] != 0u;
         } else {
-            for (int idx = tid; idx < T; idx += kSelThreads) {
-                uint32_t key = col[idx];
-                c1 += key >= t1; c2 += key >= t2; c3 += key >= t3;
-            }
+            for (int idx = tid; idx < T; idx += kSelThreads) ncand += col[idx] != 0u;
         }
-        block_sum3(c1, c2, c3, red);
-    };
-
-    int ncand, d1, d2;
-    int pre_h0 = 0, pre_h1 = 0;                         // PRE: this thread's two bins of the first digit, top down
-    if constexpr (PRE) {
-        static_assert(kSelThreads * 2 == (1 << kRadixBits), "two bins of the first digit per thread");
-        const uint32_t* hp = hist1 + static_cast<size_t>(e) * n_slices * (1 << kRadixBits) + ((1 << kRadixBits) - 2 - 2 * tid);
-        for (int b = 0; b < n_slices; ++b) {
-            const uint2 v = *reinterpret_cast<const uint2*>(hp + static_cast<size_t>(b) * (1 << kRadixBits));
-            pre_h0 += static_cast<int>(v.y);            // bin 2047 - 2 tid
-            pre_h1 += static_cast<int>(v.x);            // bin 2046 - 2 tid
-        }
-        ncand = pre_h0 + pre_h1; d1 = d2 = 0;
         block_sum3(ncand, d1, d2, red);
-    } else {
-        count3(1u, 0xFFFFFFFFu, 0xFFFFFFFFu, ncand, d1, d2);
     }
     int n_keep = ncand < capacity ? ncand : capacity;
 
@@ -234,7 +316,7 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
 #pragma unroll
             for (int m = 32; m >= 1; m >>= 1) { sum += __shfl_xor(sum, m, kWave); cnt += __shfl_xor(cnt, m, kWave); }
             __syncthreads();
-            if ((tid & (kWave - 1)) == 0) { red_sum[tid / kWave] = sum; red_cnt[tid / kWave] = cnt; }
+            if (lane == 0) { red_sum[wave] = sum; red_cnt[wave] = cnt; }
             __syncthreads();
             sum = 0; cnt = 0;
 #pragma unroll
@@ -283,8 +365,7 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
                 kmax = max(kmax, static_cast<uint32_t>(__shfl_xor(static_cast<int>(kmax), m, kWave)));
                 kmin = min(kmin, static_cast<uint32_t>(__shfl_xor(static_cast<int>(kmin), m, kWave)));
             }
-            __syncthreads();                            // previous readers of range[] / hist[] are done
-            if ((tid & (kWave - 1)) == 0) { range[tid / kWave][0] = kmax; range[tid / kWave][1] = kmin; }
+            if (lane == 0) { range[wave][0] = kmax; range[wave][1] = kmin; }
             __syncthreads();
 #pragma unroll
             for (int w = 0; w < kSelThreads / kWave; ++w) { kmax = max(kmax, range[w][0]); kmin = min(kmin, range[w][1]); }
@@ -293,23 +374,21 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
             prefix = shift >= 32 ? 0u : (kmax >> shift) << shift;
         }
         int need = n_keep;
-        while (shift > 0) {
+        for (int p = 0; p < kMaxDigits && shift > 0; ++p) {
             const int w = shift < kRadixBits ? shift : kRadixBits;
-            const bool from_pre = PRE && shift == 32;                // the first digit was counted by the slices
+            const int top = shift;                                   // bits [31:top] are settled
             shift -= w;
-            const int nb = 1 << w, top = shift + w;                  // bins; bits [31:top] are settled
-            // thread t owns bins nb-1-2t and nb-2-2t; scanning the threads in order walks the digits from the top
-            const int b0 = nb - 1 - 2 * tid, b1 = b0 - 1;
-            int h0, h1;
-            if (from_pre) {
-                h0 = pre_h0; h1 = pre_h1;
-                __syncthreads();                                     // previous readers of wave_tot[] / sel[] are done
+            int digit, above;
+            if (PRE && p == 0) {
+                digit_pick(hist[0], first, need, digit, above);      // the first digit was counted by the slices
             } else {
-                for (int b = tid; b < nb; b += kSelThreads) hist[b] = 0u;
-                __syncthreads();
+                // candidates whose settled bits equal the prefix: lo <= key <= lo + span
+                const uint32_t lo = prefix > 1u ? prefix : 1u;
+                const uint32_t span = (top >= 32 ? 0xFFFFFFFFu : prefix + ((1u << top) - 1u)) - lo;
+                const uint32_t dmask = (1u << w) - 1u;
+                uint32_t* h = hist[p];
                 auto bin = [&](uint32_t key) {
-                    const bool in = key != 0u && (top >= 32 || (key >> top) == (prefix >> top));
-                    if (in) atomicAdd(&hist[(key >> shift) & (nb - 1)], 1u);      // LDS; integer adds, so order-free
+                    if (key - lo <= span) atomicAdd(&h[(key >> shift) & dmask], 1u);   // LDS; integer adds, so order-free
                 };
                 if constexpr (IPT > 0) {
 #pragma unroll
@@ -318,50 +397,50 @@ __global__ __launch_bounds__(kSelThreads) void expert_choice_kernel(const uint32
                     for (int idx = tid; idx < T; idx += kSelThreads) bin(col[idx]);
                 }
                 __syncthreads();
-                h0 = b0 >= 0 ? static_cast<int>(hist[b0]) : 0; h1 = b1 >= 0 ? static_cast<int>(hist[b1]) : 0;
+                const DigitView d = digit_view(h);
+                digit_pick(h, d, need, digit, above);
             }
-            int inc = h0 + h1;
-            const int lane = tid & (kWave - 1), wave = tid / kWave;
-#pragma unroll
-            for (int m = 1; m < kWave; m <<= 1) {
-                const int o = __shfl_up(inc, m, kWave);
-                if (lane >= m) inc += o;
-            }
-            if (lane == kWave - 1) wave_tot[wave][0] = inc;
-            __syncthreads();
-            int before = inc - (h0 + h1);                            // candidates with a larger digit than b0
-            for (int w2 = 0; w2 < wave; ++w2) before += wave_tot[w2][0];
-            if (before < need && need <= before + h0 + h1) {         // exactly one thread: the digit lies here
-                const bool first = need <= before + h0;
-                sel[0] = first ? b0 : b1;
-                sel[1] = first ? before : before + h0;
-            }
-            __syncthreads();
-            prefix |= static_cast<uint32_t>(sel[0]) << shift;
-            need -= sel[1];
+            prefix |= static_cast<uint32_t>(digit) << shift;
+            need -= above;
         }
         tau = prefix;
     }
 
-    // per-thread (= per-chunk) counts in token order, then an exclusive block scan
+    // per-chunk counts of (key > tau, key == tau) in token order, then an exclusive block scan
     int gt = 0, eq = 0;
     if constexpr (IPT > 0) {
+        const bool some = tau != 0u;                    // (a key of 0 is no candidate)
+        int cnt[Q];
 #pragma unroll
-        for (int j = 0; j < IPT; ++j) { gt += keys[j] > tau; eq += (keys[j] == tau) && keys[j] != 0u; }
+        for (int r = 0; r < Q; ++r) {
+            int g = 0, q = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { g += keys[4 * r + j] > tau; q += (keys[4 * r + j] == tau) && some; }
+            cnt[r] = lane_group_sum<Q>(g | (q << 16));  // at most 64 each: the halves do not meet
+        }
+        if constexpr (Q > 1) {
+            // row r, lanes [Q c', Q c' + Q) hold chunk r (64 / Q) + c' of the wave; lane c takes chunk c
+            if ((lane & (Q - 1)) == 0) {
+#pragma unroll
+                for (int r = 0; r < Q; ++r) chunk_cnt[wave][r * (kWave / Q) + lane / Q] = cnt[r];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int mine = chunk_cnt[wave][lane];
+            gt = mine & 0xFFFF; eq = mine >> 16;
+        } else {
+            gt = cnt[0] & 0xFFFF; eq = cnt[0] >> 16;
+        }
     } else {
+        const int base = tid * ipt;
         for (int j = 0; j < ipt; ++j) {
             const int idx = base + j;
             uint32_t key = idx < T ? col[idx] : 0u;
             gt += key > tau; eq += (key == tau) && key != 0u;
         }
     }
-    const int lane = tid & (kWave - 1), wave = tid / kWave;
-    int igt = gt, ieq = eq;                             // inclusive scan inside the wave
-#pragma unroll
-    for (int m = 1; m < kWave; m <<= 1) {
-        int a = __shfl_up(igt, m, kWave), b = __shfl_up(ieq, m, kWave);
-        if (lane >= m) { igt += a; ieq += b; }
-    }
+    const int igt = wave_scan_incl(gt), ieq = wave_scan_incl(eq);
     if (lane == kWave - 1) { wave_tot[wave][0] = igt; wave_tot[wave][1] = ieq; }
     __syncthreads();
     int off_gt = 0, off_eq = 0, tot_gt = 0;
@@ -485,10 +564,13 @@ __global__ __launch_bounds__(256) void slot_kernel(const uint64_t* __restrict__ 
 
 }  // namespace
 
+// Tokens per chunk (= per thread of the per-expert kernel): a power of two from 4 to 64 while the column fits
+// that kernel's registers, else a multiple of 4.
 static int chunk_tokens(int T) {
-    int ipt = (T + kSelThreads - 1) / kSelThreads;
-    ipt = (ipt + 3) / 4 * 4;
-    return ipt < 4 ? 4 : ipt;
+    const int ipt = (T + kSelThreads - 1) / kSelThreads;
+    for (int p = 4; p <= 64; p <<= 1)
+        if (ipt <= p) return p;
+    return (ipt + 3) / 4 * 4;
 }
 
 // Long columns (more than 16 keys per thread of the per-expert kernel) get their first radix digit counted by
@@ -496,7 +578,7 @@ static int chunk_tokens(int T) {
 static int select_slices(int T) {
     if (chunk_tokens(T) <= 16) return 0;
     const int n = (T + 4095) / 4096;
-    return n > 16 ? 16 : n;
+    return n > kMaxSlices ? kMaxSlices : n;
 }
 
 size_t select_ws_bytes(int T, int E) {
@@ -576,19 +658,17 @@ hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    // (the adaptive token count is an instantiation of its own: its double-precision sums over the keys in registers
-    // would otherwise cost the plain search of the long columns 100 spilled registers)
     const bool adapt = sum_need > 0;
 #define ETR_EC1(II, PP, AA)                                                                                           \
     hipLaunchKernelGGL((expert_choice_kernel<II, PP, AA>), dim3(c.E), dim3(kSelThreads), 0, st, w.keyT, w.Tpad, c.T, w.ipt, \
                        c.capacity, c.mode, capacity_dev, sum_need, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts, w.hist1, \
                        w.n_slices)
 #define ETR_EC(II, PP) do { if (adapt) ETR_EC1(II, PP, true); else ETR_EC1(II, PP, false); } while (0)
-    if (w.ipt <= 4) ETR_EC(4, false);
-    else if (w.ipt <= 8) ETR_EC(8, false);
-    else if (w.ipt <= 16) ETR_EC(16, false);                // (no pre-pass up to here, see select_slices)
-    else if (w.ipt <= 32) { if (pre) ETR_EC(32, true); else ETR_EC(32, false); }
-    else if (w.ipt <= 64) { if (pre) ETR_EC(64, true); else ETR_EC(64, false); }
+    if (w.ipt == 4) ETR_EC(4, false);                       // (the register variants take exactly their chunk length)
+    else if (w.ipt == 8) ETR_EC(8, false);
+    else if (w.ipt == 16) ETR_EC(16, false);                // (no pre-pass up to here, see select_slices)
+    else if (w.ipt == 32) { if (pre) ETR_EC(32, true); else ETR_EC(32, false); }
+    else if (w.ipt == 64) { if (pre) ETR_EC(64, true); else ETR_EC(64, false); }
     else { if (pre) ETR_EC(0, true); else ETR_EC(0, false); }
 #undef ETR_EC
 #undef ETR_EC1
