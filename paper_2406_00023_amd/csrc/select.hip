@@ -52,38 +52,89 @@ __device__ __forceinline__ uint32_t selection_key(float s, bool cand, int mode, 
 // ---------------------------------------------------------------------------------------
 // 1. token choice
 // ---------------------------------------------------------------------------------------
-template <int G>   // lanes per token, power of two >= E
-__global__ __launch_bounds__(256) void token_choice_kernel(const float* __restrict__ score, int T, int E, int k,
-                                                           int mode, int32_t* __restrict__ topk,
-                                                           uint64_t* __restrict__ cmask,
-                                                           uint32_t* __restrict__ keyT, int Tpad) {
-    const int gid = blockIdx.x * 256 + threadIdx.x;
-    const int t = gid / G, e = gid % G;
-    const bool valid = t < T && e < E;
-    const float val = valid ? score[static_cast<size_t>(t) * E + e] : 0.f;
-    uint64_t mask = 0;
-    int my_rank = 0;
-    if (mode != ETR_MODE_ECR) {
-        int taken = valid ? 0 : 1;
-        for (int r = 0; r < k; ++r) {
-            float bv = val; int bi = e; int bt = taken;
-#pragma unroll
-            for (int m = 1; m < G; m <<= 1) {
-                float ov = __shfl_xor(bv, m, kWave);
-                int oi = __shfl_xor(bi, m, kWave);
-                int ot = __shfl_xor(bt, m, kWave);
-                bool better = (ot < bt) || (ot == bt && (ov > bv || (ov == bv && oi < bi)));
-                if (better) { bv = ov; bi = oi; bt = ot; }
-            }
-            if (bi == e && !taken) { taken = 1; my_rank = r; }
-            mask |= 1ull << bi;
-            if (e == 0 && t < T && topk) topk[static_cast<size_t>(t) * k + r] = bi;
-        }
-    } else {
-        mask = E >= 64 ? ~0ull : ((1ull << E) - 1ull);
+// Maximum (MAX) or minimum over aligned groups of G lanes, every lane of a group gets it: swaps inside quads, the
+// mirror images of the half row and of the row (16 lanes) as data-parallel-primitive moves, then the row-pair and
+// half-wave swaps.  Call with all lanes active.
+template <bool MAX> __device__ __forceinline__ uint32_t pick(uint32_t a, uint32_t b) { return MAX ? max(a, b) : min(a, b); }
+template <bool MAX, int CTRL>
+__device__ __forceinline__ uint32_t dpp_fold(uint32_t v) {
+    return pick<MAX>(v, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(static_cast<int>(v), static_cast<int>(v), CTRL, 0xF, 0xF, false)));
+}
+template <int G, bool MAX>
+__device__ __forceinline__ uint32_t lane_group_fold(uint32_t v) {
+    if constexpr (G >= 2) v = dpp_fold<MAX, 0xB1>(v);        // quad_perm [1,0,3,2]
+    if constexpr (G >= 4) v = dpp_fold<MAX, 0x4E>(v);        // quad_perm [2,3,0,1]
+    if constexpr (G >= 8) v = dpp_fold<MAX, 0x141>(v);       // row_half_mirror
+    if constexpr (G >= 16) v = dpp_fold<MAX, 0x140>(v);      // row_mirror
+    if constexpr (G >= 32) {                                 // odd rows of one copy <-> even rows of the other
+        const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        v = pick<MAX>(r[0], r[1]);
     }
-    if (valid) keyT[static_cast<size_t>(e) * Tpad + t] = selection_key(val, (mask >> e) & 1ull, mode, k, my_rank);
-    if (e == 0 && t < T) cmask[t] = mask;
+    if constexpr (G >= 64) {                                 // upper half of one copy <-> lower half of the other
+        const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+        v = pick<MAX>(r[0], r[1]);
+    }
+    return v;
+}
+
+template <int G> constexpr int token_tile() { return G <= 4 ? 256 / G : 64; }       // tokens per workgroup
+template <int G> constexpr int token_threads() { return G >= 16 ? 1024 : 256; }       // threads per workgroup
+
+// G = lanes per token, a power of two >= E.  A workgroup takes token_tile<G>() tokens in one to four passes, all of
+// whose affinities are requested before the first is used.  Each of the k rounds of Eq. 5 is a maximum over the
+// token's lanes of the order-preserving affinities still in the contest, then a minimum over the experts that hold
+// it (the lower expert wins among equals); the winner leaves the contest.  The keys of the tile go through LDS, so
+// that each column of the column-major copy is written in whole stretches.
+template <int G>
+__global__ __launch_bounds__(token_threads<G>()) void token_choice_kernel(const float* __restrict__ score, int T, int E,
+                                                                          int k, int mode, int32_t* __restrict__ topk,
+                                                                          uint64_t* __restrict__ cmask,
+                                                                          uint32_t* __restrict__ keyT, int Tpad) {
+    constexpr int TT = token_tile<G>(), NT = token_threads<G>();
+    constexpr int PASSES = TT * G / NT;
+    static_assert(PASSES >= 1 && PASSES * NT == TT * G, "whole passes");
+    __shared__ uint32_t tile[G][TT + 1];
+    const int t_base = blockIdx.x * TT;
+    const int e = threadIdx.x % G, tl0 = threadIdx.x / G;      // (NT is a multiple of G: the same expert in every pass)
+    float vals[PASSES];
+#pragma unroll
+    for (int pass = 0; pass < PASSES; ++pass) {
+        const int t = t_base + pass * (NT / G) + tl0;
+        vals[pass] = (t < T && e < E) ? score[static_cast<size_t>(t) * E + e] : 0.f;
+    }
+#pragma unroll
+    for (int pass = 0; pass < PASSES; ++pass) {
+        const int tl = pass * (NT / G) + tl0;
+        const int t = t_base + tl;
+        const bool valid = t < T && e < E;
+        const float val = vals[pass];
+        uint64_t mask = 0;
+        int my_rank = 0, choice = 0;
+        if (mode != ETR_MODE_ECR) {
+            // 0 = out of the contest (no such expert, or already chosen)
+            uint32_t mine = valid ? max(order_key(val), 1u) : 0u;
+            for (int r = 0; r < k; ++r) {
+                const uint32_t best = lane_group_fold<G, true>(mine);
+                const int bi = static_cast<int>(lane_group_fold<G, false>(mine == best && best != 0u ? static_cast<uint32_t>(e) : 255u));
+                if (e == bi) { mine = 0u; my_rank = r; }
+                if (e == r) choice = bi;
+            }
+            // the token's candidate set: the lanes of its group that have left the contest
+            const uint64_t chosen = __ballot(valid && mine == 0u);
+            mask = (chosen >> (threadIdx.x & (kWave - 1) & ~(G - 1))) & (G >= 64 ? ~0ull : ((1ull << G) - 1ull));
+            if (topk && e < k && t < T) topk[static_cast<size_t>(t) * k + e] = choice;
+        } else {
+            mask = E >= 64 ? ~0ull : ((1ull << E) - 1ull);
+        }
+        tile[e][tl] = valid ? selection_key(val, (mask >> e) & 1ull, mode, k, my_rank) : 0u;
+        if (e == 0 && t < T) cmask[t] = mask;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < G * TT; i += NT) {
+        const int ee = i / TT, tl = i % TT;
+        const int t = t_base + tl;
+        if (ee < E && t < T) keyT[static_cast<size_t>(ee) * Tpad + t] = tile[ee][tl];
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -504,11 +555,13 @@ __global__ __launch_bounds__(kSelThreads) void strict_filter_kernel(const uint32
 // ---------------------------------------------------------------------------------------
 // 3. slots
 // ---------------------------------------------------------------------------------------
-// G = lanes per chunk (power of two >= ipt, at most 64; chunks longer than 64 tokens are walked 64 at a time).
-// Lane -> (expert, chunk, token inside the chunk), token fastest: the keys are read coalesced from the
-// column-major copy, and the number of kept tokens in front of a token inside its chunk is a popcount of a ballot.
-__global__ __launch_bounds__(256) void slot_kernel(const uint64_t* __restrict__ cmask, int T, int E, int capacity,
-                                                   int mode, int ipt, int nchunks, int G,
+// A workgroup takes a tile of max(64, ipt) tokens (whole chunks) and all experts, 64 tokens at a time: wave w of W
+// does experts w, w + W, ...  Lane = token, so the keys are read in whole stretches of the column-major copy and the
+// number of kept tokens in front of a token inside its chunk is a popcount of a ballot (chunks longer than 64
+// tokens carry their running counts from one stretch of 64 to the next).  The slots of the 64 x E tile are
+// gathered in LDS and leave as whole rows of slot_of.
+__global__ __launch_bounds__(kSelThreads) void slot_kernel(const uint64_t* __restrict__ cmask, int T, int E, int capacity,
+                                                   int mode, int ipt,
                                                    const uint32_t* __restrict__ tau_in,
                                                    const int32_t* __restrict__ need_eq_in,
                                                    const int32_t* __restrict__ pre_gt,
@@ -517,45 +570,58 @@ __global__ __launch_bounds__(256) void slot_kernel(const uint64_t* __restrict__ 
                                                    int32_t* __restrict__ slot_token,
                                                    const uint32_t* __restrict__ keyT, int Tpad,
                                                    const int32_t* __restrict__ pre_kept) {          // STRICT: see strict_filter_kernel
-    const long long gid = static_cast<long long>(blockIdx.x) * 256 + threadIdx.x;
-    const long long groups = static_cast<long long>(E) * nchunks;
-    const long long grp = gid / G;
-    const int j = static_cast<int>(gid - grp * G);
-    const int lane = threadIdx.x & (kWave - 1);
+    __shared__ int32_t tile[kWave * (kWave + 1)];       // [token][E + 1]
+    __shared__ int carry[kWave][3];                     // per expert: kept-before counts of a long chunk so far
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave, nthreads = blockDim.x;
+    const bool long_chunk = ipt > kWave;
+    const int TT = long_chunk ? ipt : kWave;
+    const int t_tile = blockIdx.x * TT;
+    const int G = long_chunk ? kWave : ipt;             // lanes per chunk inside a stretch (a power of two)
     const uint64_t group_mask = (G >= 64 ? ~0ull : ((1ull << G) - 1ull)) << (lane & ~(G - 1));
     const uint64_t below = (1ull << lane) - 1ull;
-    const bool live = grp < groups;
-    const int e = live ? static_cast<int>(grp / nchunks) : 0, c = live ? static_cast<int>(grp - static_cast<long long>(e) * nchunks) : 0;
-    const uint32_t tau = tau_in[e];
-    const int need = need_eq_in[e];
-    int gt = live ? pre_gt[e * kSelThreads + c] : 0, eq = live ? pre_eq[e * kSelThreads + c] : 0;
-    int kept = (live && mode == ETR_MODE_BIDIR_STRICT) ? pre_kept[e * kSelThreads + c] : 0;
-    const int t_end = min(T, (c + 1) * ipt);
-    for (int j0 = 0; j0 < ipt; j0 += G) {               // one pass unless the chunk is longer than 64 tokens
-        const int t = c * ipt + j0 + j;
-        const bool on = live && j0 + j < ipt && t < t_end;
-        const uint32_t key = on ? keyT[static_cast<size_t>(e) * Tpad + t] : 0u;
-        const bool is_gt = key > tau, is_eq = key == tau && key != 0u;
-        const uint64_t m_gt = __ballot(is_gt) & group_mask, m_eq = __ballot(is_eq) & group_mask;
-        const int gt_before = gt + __popcll(m_gt & below), eq_before = eq + __popcll(m_eq & below);
-        int slot = -1;
-        if (is_gt) slot = gt_before + min(eq_before, need);
-        else if (is_eq && eq_before < need) slot = gt_before + eq_before;
-        if (mode == ETR_MODE_BIDIR_STRICT) {            // renumber inside the chooser set
-            const bool keep = slot >= 0 && on && ((cmask[t] >> e) & 1ull);
-            const uint64_t m_k = __ballot(keep) & group_mask;
-            slot = keep ? kept + __popcll(m_k & below) : -1;
-            kept += __popcll(m_k);
+    const int ld = E + 1;
+    if (tid < kWave) { carry[tid][0] = 0; carry[tid][1] = 0; carry[tid][2] = 0; }
+    __syncthreads();
+    for (int j0 = 0; j0 < TT; j0 += kWave) {
+        const int t = t_tile + j0 + lane;
+        const bool on = t < T && j0 + lane < TT;
+        const int c = long_chunk ? static_cast<int>(blockIdx.x) : t / ipt;
+        for (int e = wave; e < E; e += nthreads / kWave) {
+            const uint32_t tau = tau_in[e];
+            const int need = need_eq_in[e];
+            const int gt = (on ? pre_gt[e * kSelThreads + c] : 0) + carry[e][0];
+            const int eq = (on ? pre_eq[e * kSelThreads + c] : 0) + carry[e][1];
+            const uint32_t key = on ? keyT[static_cast<size_t>(e) * Tpad + t] : 0u;
+            const bool is_gt = key > tau, is_eq = key == tau && key != 0u;
+            const uint64_t w_gt = __ballot(is_gt), w_eq = __ballot(is_eq);
+            const int gt_before = gt + __popcll(w_gt & group_mask & below), eq_before = eq + __popcll(w_eq & group_mask & below);
+            int slot = -1;
+            if (is_gt) slot = gt_before + min(eq_before, need);
+            else if (is_eq && eq_before < need) slot = gt_before + eq_before;
+            uint64_t w_k = 0ull;
+            if (mode == ETR_MODE_BIDIR_STRICT) {        // renumber inside the chooser set
+                const int kept = (on ? pre_kept[e * kSelThreads + c] : 0) + carry[e][2];
+                const bool keep = slot >= 0 && on && ((cmask[t] >> e) & 1ull);
+                w_k = __ballot(keep);
+                slot = keep ? kept + __popcll(w_k & group_mask & below) : -1;
+            }
+            tile[lane * ld + e] = slot;
+            if (on && slot >= 0) slot_token[static_cast<size_t>(e) * capacity + slot] = t;
+            if (long_chunk && lane == 0) {              // (the whole wave is one chunk here)
+                carry[e][0] += __popcll(w_gt); carry[e][1] += __popcll(w_eq); carry[e][2] += __popcll(w_k);
+            }
         }
-        if (on) {
-            slot_of[static_cast<size_t>(t) * E + e] = slot;
-            if (slot >= 0) slot_token[static_cast<size_t>(e) * capacity + slot] = t;
-        }
-        gt += __popcll(m_gt);
-        eq += __popcll(m_eq);
+        __syncthreads();
+        int rows = T - (t_tile + j0);
+        rows = rows < TT - j0 ? rows : TT - j0;
+        rows = rows < kWave ? rows : kWave;
+        int32_t* out = slot_of + static_cast<size_t>(t_tile + j0) * E;
+        for (int i = tid; i < rows * E; i += nthreads) out[i] = tile[(i / E) * ld + i % E];
+        __syncthreads();
     }
     // empty slots
-    const long long total = static_cast<long long>(gridDim.x) * 256;
+    const long long gid = static_cast<long long>(blockIdx.x) * nthreads + tid;
+    const long long total = static_cast<long long>(gridDim.x) * nthreads;
     for (long long i = gid; i < static_cast<long long>(E) * capacity; i += total) {
         const int ee = static_cast<int>(i / capacity), sl = static_cast<int>(i - static_cast<long long>(ee) * capacity);
         if (sl >= counts[ee]) slot_token[i] = -1;
@@ -632,11 +698,10 @@ hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_
                          const int32_t* capacity_dev, long long sum_need) {
     int G = 1;
     while (G < c.E) G <<= 1;
-    const long long lanes = static_cast<long long>(c.T) * G;
-    const int blocks1 = static_cast<int>((lanes + 255) / 256);
 #define ETR_TC(GG)                                                                                              \
-    hipLaunchKernelGGL(token_choice_kernel<GG>, dim3(blocks1), dim3(256), 0, st, score, c.T, c.E, c.k, c.mode, \
-                       topk_expert, w.cmask, w.keyT, w.Tpad)
+    hipLaunchKernelGGL(token_choice_kernel<GG>, dim3((c.T + token_tile<GG>() - 1) / token_tile<GG>()),         \
+                       dim3(token_threads<GG>()), 0, st,                                                        \
+                       score, c.T, c.E, c.k, c.mode, topk_expert, w.cmask, w.keyT, w.Tpad)
     switch (G) {
         case 1: ETR_TC(1); break;
         case 2: ETR_TC(2); break;
@@ -681,13 +746,11 @@ hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_
         err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    int G3 = 4;                                          // lanes per chunk in slot_kernel
-    while (G3 < w.ipt && G3 < 64) G3 <<= 1;
-    const long long lanes3 = static_cast<long long>(w.nchunks) * c.E * G3;
-    const int blocks3 = static_cast<int>((lanes3 + 255) / 256);
-    hipLaunchKernelGGL(slot_kernel, dim3(blocks3), dim3(256), 0, st, w.cmask, c.T, c.E, c.capacity, c.mode, w.ipt,
-                       w.nchunks, G3, w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts, slot_of, slot_token, w.keyT, w.Tpad,
-                       w.pre_kept);
+    const int tile3 = w.ipt > kWave ? w.ipt : kWave;     // tokens per workgroup of slot_kernel
+    const int blocks3 = (c.T + tile3 - 1) / tile3;
+    const int waves3 = c.E < 4 ? 4 : (c.E > 16 ? 16 : c.E);   // one expert per wave up to 16 waves
+    hipLaunchKernelGGL(slot_kernel, dim3(blocks3), dim3(waves3 * kWave), 0, st, w.cmask, c.T, c.E, c.capacity, c.mode, w.ipt,
+                       w.tau, w.need_eq, w.pre_gt, w.pre_eq, counts, slot_of, slot_token, w.keyT, w.Tpad, w.pre_kept);
     return hipGetLastError();
 }
 
