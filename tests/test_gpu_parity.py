@@ -143,6 +143,9 @@ def _scores(seed, T, E, levels):
     (1, 1, 1, 1, None), (6, 3, 2, 2, 4), (64, 8, 1, 5, 3), (1000, 17, 4, 123, 7), (1000, 17, 17, 2000, None),
     (4097, 64, 8, 300, 50), (5000, 2, 1, 1, 2), (20000, 16, 2, 2500, 1000), (70001, 8, 3, 9000, 200),
     (3000, 33, 5, 3000, None),
+    # chunk lengths 16 and 64 of the per-expert search (64 with idle waves at the end of the column); four lanes
+    # per token over many workgroups; 64 lanes per token
+    (12000, 5, 2, 3000, 64), (40000, 4, 2, 15000, None), (33000, 40, 3, 1500, 500),
 ])
 def test_select_external_scores(H, oracle, T, E, k, C, levels):
     S = _scores(T * 31 + E, T, E, levels)
