@@ -2,19 +2,21 @@
 // rules of the pure phases from the Proof of the Theorem, parts 1 and 2) and the
 // prefix-sum permutation tables.
 //
-// Three launches, no global atomics, integer counting only, so the result is bit-reproducible:
-//   1. token_choice_kernel   one lane per (token, expert): k rounds of arg-max inside a
-//                            lane group give the token's Top-k list (Eq. 5); writes the
-//                            candidate mask and a column-major copy of the selection keys
-//   2. expert_choice_kernel  one 1024-thread workgroup per expert, keys in registers: the key tau_e of
-//                            the C-th best candidate (Eq. 6) by a radix search over the bits in which the
-//                            candidates' order-preserving keys differ at all (11 bits per pass, one LDS
-//                            histogram per pass), then the (key > tau, key == tau) indicator pairs are
-//                            scanned into per-chunk exclusive prefixes
+// Three launches (four for long columns), no global atomics, integer counting only, so the result is
+// bit-reproducible:
+//   1. token_choice_kernel   one lane per (token, expert): k rounds of arg-max inside a lane group (DPP folds)
+//                            give the token's Top-k list (Eq. 5); writes the candidate mask and, through an LDS
+//                            tile, a column-major copy of the selection keys
+//   2. expert_choice_kernel  one 1024-thread workgroup per expert, keys in registers as whole rows of the
+//                            column: the key tau_e of the C-th best candidate (Eq. 6) by a radix search over the
+//                            bits in which the candidates' order-preserving keys differ at all (11 bits per
+//                            pass, one LDS histogram per pass, the digit picked by every wave for itself), then
+//                            the (key > tau, key == tau) counts of each chunk are scanned into exclusive prefixes
 //                            (long columns: the first digit is counted beforehand by key_histogram_kernel,
 //                            up to 16 workgroups per expert)
 //   3. slot_kernel           one lane per (expert, token): the position inside the chunk comes from a
-//                            ballot, so slot_of / slot_token are written without any serial walk
+//                            ballot, so slot_of / slot_token are written without any serial walk; the slots of
+//                            64 tokens leave as whole rows of slot_of
 // All three phases are one algorithm: in TCR every candidate has the same key, so
 // "the C best, lowest token first among equals" is "the first C in token order".
 #include <mutex>
@@ -119,7 +121,8 @@ __global__ __launch_bounds__(token_threads<G>()) void token_choice_kernel(const 
                 if (e == bi) { mine = 0u; my_rank = r; }
                 if (e == r) choice = bi;
             }
-            // the token's candidate set: the lanes of its group that have left the contest
+            // the token's candidate set: the lanes of its group that have left the contest (one ballot after the
+            // rounds, not a shifted bit per round)
             const uint64_t chosen = __ballot(valid && mine == 0u);
             mask = (chosen >> (threadIdx.x & (kWave - 1) & ~(G - 1))) & (G >= 64 ? ~0ull : ((1ull << G) - 1ull));
             if (topk && e < k && t < T) topk[static_cast<size_t>(t) * k + e] = choice;
