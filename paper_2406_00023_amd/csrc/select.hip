@@ -642,10 +642,10 @@ static int chunk_tokens(int T) {
     return (ipt + 3) / 4 * 4;
 }
 
-// Long columns (more than 16 keys per thread of the per-expert kernel) get their first radix digit counted by
+// Long columns (more than 32 keys per thread of the per-expert kernel) get their first radix digit counted by
 // up to 16 workgroups per expert.
 static int select_slices(int T) {
-    if (chunk_tokens(T) <= 16) return 0;
+    if (chunk_tokens(T) <= 32) return 0;
     const int n = (T + 4095) / 4096;
     return n > kMaxSlices ? kMaxSlices : n;
 }
@@ -734,8 +734,8 @@ hipError_t launch_select(const etr_config& c, const float* score, int32_t* topk_
 #define ETR_EC(II, PP) do { if (adapt) ETR_EC1(II, PP, true); else ETR_EC1(II, PP, false); } while (0)
     if (w.ipt == 4) ETR_EC(4, false);                       // (the register variants take exactly their chunk length)
     else if (w.ipt == 8) ETR_EC(8, false);
-    else if (w.ipt == 16) ETR_EC(16, false);                // (no pre-pass up to here, see select_slices)
-    else if (w.ipt == 32) { if (pre) ETR_EC(32, true); else ETR_EC(32, false); }
+    else if (w.ipt == 16) ETR_EC(16, false);
+    else if (w.ipt == 32) ETR_EC(32, false);                // (no pre-pass up to here, see select_slices)
     else if (w.ipt == 64) { if (pre) ETR_EC(64, true); else ETR_EC(64, false); }
     else { if (pre) ETR_EC(0, true); else ETR_EC(0, false); }
 #undef ETR_EC
