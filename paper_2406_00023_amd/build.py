@@ -1,9 +1,12 @@
 """Builds the HIP library for gfx950 in-tree (paper_2406_00023_amd/libetr_hip.so)."""
 from __future__ import annotations
 
+import concurrent.futures
 import os
+import re
 import subprocess
 import sys
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -17,6 +20,65 @@ HIPCC_FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
 ]
+
+
+_SHIFT64 = re.compile(r"^\s*(v_lshlrev_b64|v_lshrrev_b64|v_ashrrev_i64)\s+v\[\d+:\d+\],\s*v(\d+),")
+_KERNEL = re.compile(r"^(_Z\S+):")
+_NEXT_FREE = re.compile(r"^\s*\.amdhsa_next_free_vgpr\s+(\d+)")
+
+
+def shift64_last_vgpr_hits(asm: str) -> list:
+    """Finds, in gfx950 device assembly, 64-bit shifts whose shift amount sits in the last vector register the kernel
+    allocates (index 8n+7 with nothing above it).
+
+    Measured on MI355X: such a shift takes a wrong amount whenever a wave of another workgroup shares the SIMD (the
+    register after the last one of the allocation block belongs to that wave); the same instructions with a larger
+    register allocation are correct.  The compiler guards this for gfx90a only, so the build checks its output.
+    Returns (kernel, line number, instruction) triples.
+    """
+    hits, kernel, shifts = [], None, []
+    for ln, line in enumerate(asm.split("\n"), 1):
+        m = _KERNEL.match(line)
+        if m:
+            kernel, shifts = m.group(1), []
+            continue
+        if kernel is None:
+            continue
+        m = _SHIFT64.match(line)
+        if m:
+            shifts.append((ln, int(m.group(2)), line.strip()))
+            continue
+        m = _NEXT_FREE.match(line)
+        if m:
+            last = int(m.group(1)) - 1
+            hits += [(kernel, l, text) for (l, reg, text) in shifts if reg % 8 == 7 and reg == last]
+            kernel = None
+    return hits
+
+
+def device_assembly(source: str) -> str:
+    """gfx950 assembly of one kernel file, with the flags of the library build."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f not in ("-shared",)]
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "k.s")
+        cmd = [hipcc, *flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-S", "--cuda-device-only",
+               os.path.join(CSRC, source), "-o", out]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc -S failed for " + source + ":\n" + res.stderr)
+        with open(out) as f:
+            return f.read()
+
+
+def check_device_code() -> None:
+    """Raises if any kernel of the library holds the 64-bit shift pattern of shift64_last_vgpr_hits."""
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
+        texts = list(pool.map(device_assembly, SOURCES))
+    bad = [(src, *h) for src, asm in zip(SOURCES, texts) for h in shift64_last_vgpr_hits(asm)]
+    if bad:
+        raise RuntimeError("64-bit shift with its amount in the last allocated VGPR (wrong results on MI355X):\n" +
+                           "\n".join(f"  {src}: {k} line {l}: {t}" for src, k, l, t in bad))
 
 
 def build(verbose: bool = False) -> str:
@@ -33,6 +95,7 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if err.strip() and verbose:
         print(err, file=sys.stderr)
+    check_device_code()
     return LIB
 
 

@@ -1,0 +1,45 @@
+"""The build's check of the compiler's output: no kernel of the library may hold a 64-bit shift whose amount sits in
+the last vector register the kernel allocates (measured on MI355X: such a shift reads a wrong amount as soon as a wave of
+another workgroup shares the SIMD). CPU only: the sources are compiled to assembly, nothing runs."""
+import shutil
+
+import pytest
+
+from paper_2406_00023_amd import build
+
+# A kernel body of the shape that went wrong (a fold into v15, then the shift by v15, 16 registers allocated).
+SNIPPET = """
+\t.text
+_Z6kernelPm:                            ; @_Z6kernelPm
+\tv_min_u32_e32 v15, v12, v13
+\tv_lshlrev_b64 v[12:13], {amount}, 1
+\ts_endpgm
+\t.amdhsa_kernel _Z6kernelPm
+\t\t.amdhsa_next_free_vgpr {nfv}
+\t.end_amdhsa_kernel
+"""
+
+
+def test_scanner_flags_the_amount_in_the_last_register():
+    hits = build.shift64_last_vgpr_hits(SNIPPET.format(amount="v15", nfv=16))
+    assert len(hits) == 1 and hits[0][0] == "_Z6kernelPm" and "v_lshlrev_b64" in hits[0][2]
+
+
+@pytest.mark.parametrize("amount,nfv", [("v15", 24),     # registers above it belong to the same wave
+                                        ("v14", 15),     # last register, but not the end of a block of eight
+                                        ("v7", 16),      # end of a block, but not the last register
+                                        ("s4", 16), ("3", 16)])
+def test_scanner_passes_everything_else(amount, nfv):
+    assert build.shift64_last_vgpr_hits(SNIPPET.format(amount=amount, nfv=nfv)) == []
+
+
+def test_scanner_keeps_kernels_apart():
+    two = SNIPPET.format(amount="v15", nfv=24) + SNIPPET.format(amount="v23", nfv=24).replace("kernelPm", "otherPm")
+    hits = build.shift64_last_vgpr_hits(two)
+    assert [h[0] for h in hits] == ["_Z6otherPm"]
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None and not __import__("os").path.exists("/opt/rocm/bin/hipcc"),
+                    reason="needs hipcc")
+def test_library_sources_are_clean():
+    build.check_device_code()
