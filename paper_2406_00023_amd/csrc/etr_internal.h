@@ -27,8 +27,7 @@ struct SelectWs {
     int       n_slices;  // 0: no such pre-pass
     int       slice;     // tokens per slice (multiple of 4)
     int       Tpad;      // row stride of keyT
-    int       ipt;       // tokens per chunk (= per thread of the per-expert kernel)
-    int       nchunks;
+    int       ipt;       // tokens per chunk (= per thread of the per-expert kernel): 4 ... 64 a power of two, else 4 n
 };
 constexpr int kSelThreads = 1024;       // threads of the per-expert kernel = max chunks
 size_t select_ws_bytes(int T, int E);

@@ -670,7 +670,6 @@ SelectWs select_ws_carve(void* ws, int T, int E) {
     w.pre_kept = reinterpret_cast<int32_t*>(p); p += align_up(sizeof(int32_t) * E * kSelThreads);
     w.hist1 = reinterpret_cast<uint32_t*>(p);
     w.ipt = chunk_tokens(T);
-    w.nchunks = (T + w.ipt - 1) / w.ipt;
     w.n_slices = select_slices(T);
     w.slice = w.n_slices ? ((T + w.n_slices - 1) / w.n_slices + 3) / 4 * 4 : 0;
     return w;
