@@ -62,8 +62,9 @@ template <> struct Elt<uint16_t> {          // bf16 bit patterns
 };
 
 // Columns of the transposed per-expert buffers that the weight-gradient products read: the kept rows rounded up
-// to a multiple of 64, at least 128 (the grouped product's rule for per-group contraction lengths), at most Cp.
-__device__ __forceinline__ int padded_rows(int count, int Cp) { return min(max((count + 63) & ~63, 128), Cp); }
+// to a multiple of 64, at least 256 (the grouped product's rule for per-group contraction lengths is 128, or 256
+// where it fetches its rows through an index), at most Cp.
+__device__ __forceinline__ int padded_rows(int count, int Cp) { return min(max((count + 63) & ~63, 256), Cp); }
 
 // A 64 x 64 tile in LDS, stored [row][col] in the tensor's own element type.
 template <typename T> struct Tile { T v[kTile][kTile + Elt<T>::kPad]; };
@@ -149,7 +150,8 @@ __global__ __launch_bounds__(kTileThreads) void gather_transpose_kernel(const T*
 //        dgate_part [H/64][E][C]: this tile's share of <u, h> per row (summed by dx_kernel in tile order)
 // ROWS: no transposed copies; dab and h are [E][Cp][.] row-major with zero rows from counts[e] to padded_rows (the
 // products that contract over the rows read them through transposing LDS reads); hT then is that row-major h.
-template <typename T, bool ROWS>
+// SCALE_H (with ROWS): hT holds gate * h, so that dW_down = dOut_p^T (gate h) needs no scaled copy of dOut's rows.
+template <typename T, bool ROWS, bool SCALE_H = false>
 __global__ __launch_bounds__(kTileThreads) void swiglu_backward_kernel(
     const T* __restrict__ u, const T* __restrict__ a, const T* __restrict__ b, const float* __restrict__ gate,
     const int32_t* __restrict__ slot_token, const int32_t* __restrict__ counts, T* __restrict__ dab, T* __restrict__ daT,
@@ -163,12 +165,12 @@ __global__ __launch_bounds__(kTileThreads) void swiglu_backward_kernel(
     const size_t ebase = static_cast<size_t>(e) * C;
     for (int q = threadIdx.x; q < kTile * CH; q += kTileThreads) {
         const int r = q / CH, cc = (q % CH) * V, s = s0 + r, n = n0 + cc;
-        float hv[V], dav[V], dbv[V], dot = 0.f;
+        float hv[V], dav[V], dbv[V], dot = 0.f, g_row = 0.f;
 #pragma unroll
         for (int i = 0; i < V; ++i) { hv[i] = 0.f; dav[i] = 0.f; dbv[i] = 0.f; }
         if (s < count && n < H) {
             const int t = slot_token[ebase + s];
-            const float g_row = (t >= 0 && t < T_) ? gate[static_cast<size_t>(t) * E + e] : 0.f;
+            g_row = (t >= 0 && t < T_) ? gate[static_cast<size_t>(t) * E + e] : 0.f;
             const size_t idx = (ebase + s) * H + n;
             float uv[V], av[V], bv[V];
             Elt<T>::load_vec(u + idx, uv); Elt<T>::load_vec(a + idx, av); Elt<T>::load_vec(b + idx, bv);
@@ -191,6 +193,10 @@ __global__ __launch_bounds__(kTileThreads) void swiglu_backward_kernel(
             if (s < Cp && n < H) {                                   // (s < padded_rows: the block starts below it)
                 Elt<T>::store_vec(dab + (obase + s) * 2 * H + n, dav);
                 Elt<T>::store_vec(dab + (obase + s) * 2 * H + H + n, dbv);
+                if constexpr (SCALE_H) {
+#pragma unroll
+                    for (int i = 0; i < V; ++i) hv[i] *= g_row;
+                }
                 Elt<T>::store_vec(hT + (obase + s) * H + n, hv);
             }
         } else {
@@ -467,6 +473,14 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
     t6.A = at(L.dab) + H; t6.C = dw_up;
     const bool direct = grouped_gemm_transposed_ok(t2) && grouped_gemm_transposed_ok(t3) && grouped_gemm_transposed_ok(t4) &&
                         grouped_gemm_transposed_ok(t5) && grouped_gemm_transposed_ok(t6);
+    // The same three weight-gradient products with the rows of dOut and x fetched through slot_token by the
+    // products themselves: dWd = dOut_p^T (gate h), dWg = da^T x_p, dWu = db^T x_p.  (da, db, h hold zeros from
+    // counts[e] on, so whatever row an empty slot fetches is multiplied by zero.)
+    GroupedGemm k4 = t4, k5 = t5, k6 = t6;
+    k4.A = dout; k4.k_gather = 1; k5.B0 = x; k5.k_gather = 2; k6.B0 = x; k6.k_gather = 2;
+    for (GroupedGemm* g : {&k4, &k5, &k6}) { g->k_index = slot_token; g->k_index_stride = C; g->k_rows = Tn; }
+    const bool fetch_rows = direct && grouped_gemm_transposed_ok(k4) && grouped_gemm_transposed_ok(k5) &&
+                            grouped_gemm_transposed_ok(k6);
     int dxp_rows = C;
     if (direct) {
         // The two products whose only awkward operand is a weight matrix run faster on the row-major kernel with
@@ -487,14 +501,20 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
         } else {
             ETR_BW(launch_grouped_gemm(t2, st));
         }
-        hipLaunchKernelGGL((swiglu_backward_kernel<T, true>), dim3(cH, cC, E), dim3(kTileThreads), 0, st, at(L.u), pre_a, pre_b,
-                           gate_w, slot_token, counts, at(L.dab), static_cast<T*>(nullptr), static_cast<T*>(nullptr), at(L.hT),
-                           dgate_part, Tn, E, C, Cp, H);
-        const unsigned row_blocks = static_cast<unsigned>((static_cast<long long>(E) * Cp + 3) / 4);
-        hipLaunchKernelGGL((gather_rows_kernel<T, false>), dim3(row_blocks), dim3(256), 0, st, static_cast<const T*>(x),
-                           slot_token, counts, gate, at(L.xpT), Tn, d, E, C, Cp);
-        hipLaunchKernelGGL((gather_rows_kernel<T, true>), dim3(row_blocks), dim3(256), 0, st, static_cast<const T*>(dout),
-                           slot_token, counts, gate_w, at(L.dypT), Tn, d, E, C, Cp);
+        if (fetch_rows) {
+            hipLaunchKernelGGL((swiglu_backward_kernel<T, true, true>), dim3(cH, cC, E), dim3(kTileThreads), 0, st, at(L.u), pre_a,
+                               pre_b, gate_w, slot_token, counts, at(L.dab), static_cast<T*>(nullptr), static_cast<T*>(nullptr),
+                               at(L.hT), dgate_part, Tn, E, C, Cp, H);
+        } else {
+            hipLaunchKernelGGL((swiglu_backward_kernel<T, true>), dim3(cH, cC, E), dim3(kTileThreads), 0, st, at(L.u), pre_a, pre_b,
+                               gate_w, slot_token, counts, at(L.dab), static_cast<T*>(nullptr), static_cast<T*>(nullptr), at(L.hT),
+                               dgate_part, Tn, E, C, Cp, H);
+            const unsigned row_blocks = static_cast<unsigned>((static_cast<long long>(E) * Cp + 3) / 4);
+            hipLaunchKernelGGL((gather_rows_kernel<T, false>), dim3(row_blocks), dim3(256), 0, st, static_cast<const T*>(x),
+                               slot_token, counts, gate, at(L.xpT), Tn, d, E, C, Cp);
+            hipLaunchKernelGGL((gather_rows_kernel<T, true>), dim3(row_blocks), dim3(256), 0, st, static_cast<const T*>(dout),
+                               slot_token, counts, gate_w, at(L.dypT), Tn, d, E, C, Cp);
+        }
         ETR_BW(hipGetLastError());
         if (nt_dxp) {
             hipLaunchKernelGGL(transpose_kernel<T>, dim3(cd, cH, E), dim3(kTileThreads), 0, st, static_cast<const T*>(w_gate),
@@ -507,9 +527,9 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
         } else {
             ETR_BW(launch_grouped_gemm(t3, st));
         }
-        ETR_BW(launch_grouped_gemm(t4, st));
-        ETR_BW(launch_grouped_gemm(t5, st));
-        ETR_BW(launch_grouped_gemm(t6, st));
+        ETR_BW(launch_grouped_gemm(fetch_rows ? k4 : t4, st));
+        ETR_BW(launch_grouped_gemm(fetch_rows ? k5 : t5, st));
+        ETR_BW(launch_grouped_gemm(fetch_rows ? k6 : t6, st));
         dxp_rows = Cp;
     } else {
         // Fallback (fp32, or shapes the transposing kernel does not take): every product on the "NT" kernel, with

@@ -79,6 +79,13 @@ struct GroupedGemm {
     // ta: A is [G][K][lda] holding A[g][m][k] at (k, m); tb: B0 is [G][K][ldb] holding B[g][n][k] at (k, n).
     // With tb and B1 the contraction is split in the middle: B0 and B1 are [G][K/2][ldb] each.
     bool ta = false, tb = false;
+    // With ta and tb, the contraction rows of one operand may come through an index (k_gather 1: A, 2: B0): that
+    // operand is then one [k_rows][ld] matrix for all groups and row k of group g is its row
+    // k_index[g * k_index_stride + min(k, k_index_stride - 1)], clamped into [0, k_rows); the other operand must hold
+    // zeros wherever the index does not name the wanted row (empty slots, padding).  Per-group contraction lengths
+    // are then rounded up to at least 256.
+    const int32_t* k_index = nullptr;
+    int k_index_stride = 0, k_rows = 0, k_gather = 0;
 };
 hipError_t launch_grouped_gemm(const GroupedGemm& g, hipStream_t st);
 bool grouped_gemm_transposed_ok(const GroupedGemm& g);

@@ -40,6 +40,11 @@ struct GemmParams {
                                          // that padding
     void* C2 = nullptr;         // DUAL epilogue: the B1 product goes here, the B0 product to C, no activation
     void* C3 = nullptr;         // SwiGLU epilogue that also keeps the two products: B0 product to C2, B1 product to C3
+    // Contraction rows fetched through an index (transposing kernel only; k_gather 1: A, 2: B0): row k of group g of
+    // that operand is row k_index[g * k_index_stride + min(k, k_index_stride - 1)] of a [k_rows][ld] matrix, clamped
+    // into [0, k_rows).  The per-group contraction length is then at least 256.
+    const int32_t* k_index = nullptr;
+    int k_index_stride = 0, k_rows = 0, k_gather = 0;
 };
 
 // rows of group e (counts may be absent: every group has `capacity` rows) and its contraction length
@@ -47,7 +52,7 @@ __device__ __forceinline__ int group_rows(const GemmParams& p, int e) {
     return p.counts ? min(p.counts[e], p.capacity) : p.capacity;
 }
 __device__ __forceinline__ int group_k(const GemmParams& p, int e) {
-    return p.k_counts ? min(max((max(p.k_counts[e], 0) + 63) & ~63, 128), p.K) : p.K;
+    return p.k_counts ? min(max((max(p.k_counts[e], 0) + 63) & ~63, p.k_gather ? 256 : 128), p.K) : p.K;
 }
 
 // Two fp32 values -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32).
@@ -644,9 +649,19 @@ constexpr int kMaxSuperWide = 2048;      // the same for the 64-wide kernel, who
 // i/4 + 12.  With lane (q = i % 4, j = i / 4) pointing at (k0 + j, r0 + 4 q) lane i receives rows r0 + i at
 // k0 .. k0 + 3: two reads give the 8 consecutive k of one row that the MFMA operand layout wants.  The four k of a
 // group are 64 bytes apart, so 32 lanes cover all 64 banks once: conflict-free without a swizzle.
-template <bool GLU, bool DUAL = false, bool TRA = false, bool TRB = false>
+//
+// KG (1: A, 2: B): the contraction rows of that operand are fetched through p.k_index (a gather along the slow
+// index).  The indices of a k-tile (32 of them) travel like the tiles themselves: wave 0 copies them into a ring
+// of 16 LDS slots seven k-tiles before the tile is multiplied, i.e. four iterations before its copies are issued,
+// so that its wait and the barrier of an earlier iteration have made them visible to every wave by the time a lane
+// reads its row number; the per-lane source address of a copy is then
+// base + row * row bytes + the lane's fixed column offset.  Every row number is clamped into [0, k_rows), so a
+// stale or foreign ring word can at worst fetch a wrong but existing row.
+template <bool GLU, bool DUAL = false, bool TRA = false, bool TRB = false, int KG = 0>
 __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
     static_assert(!(GLU && TRB), "the transposed B operand is for plain products");
+    static_assert(KG == 0 || (KG == 1 && TRA) || (KG == 2 && TRB), "the gathered operand is a transposed one");
+    constexpr int IDX_AHEAD = 7, IDX_SLOTS = 16;        // index prefetch distance in k-tiles, ring slots of 32 indices
     constexpr int BM = 256, BR = 256, CPR = 4, NBUF = 4, AHEAD = NBUF - 1;
     constexpr int BN = GLU ? 128 : 256;
     constexpr int STAGE = (BM + BR) * CPR;
@@ -665,6 +680,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
     const size_t stepA = TRA ? static_cast<size_t>(32) * KCA * 16 : CPR * 16;
     const size_t stepB = TRB ? static_cast<size_t>(32) * KCB * 16 : CPR * 16;
     const bool splitB = TRB && p.B1 != nullptr;
+    const uint32_t kg_row_bytes = static_cast<uint32_t>(KG == 1 ? KCA : KCB) * 16u;
+    int32_t* idx_ring = reinterpret_cast<int32_t*>(lds_raw + static_cast<size_t>(NBUF) * STAGE * 16);
 
     // ---- exclusive prefix of the number of live tiles per super-tile
     const int MG = (p.MT + p.SM - 1) / p.SM, NG = (p.NT + p.SN - 1) / p.SN;
@@ -718,8 +735,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
     };
     // per-lane byte offset inside a k-tile of a [K][rows] operand.  Copy unit u = (block of 32 rows, half of the 32 k):
     // 16 k x 64 bytes, four lanes per k, the access shape of the row-major copies (64-byte pieces of 16 memory rows)
-    auto kmajor_off = [&](int u, int r0, int limit, int kc) -> uint32_t {
-        const int krow = (u & 1) * 16 + (lane >> 2);
+    auto kmajor_off = [&](int u, int r0, int limit, int kc, bool gathered) -> uint32_t {
+        const int krow = gathered ? 0 : (u & 1) * 16 + (lane >> 2);      // (a gathered row comes from the index ring)
         int r = r0 + (u >> 1) * 32 + (lane & 3) * 8;
         r = r + 8 <= limit ? r : limit - 8;              // stay inside the row; such columns are never stored
         return (static_cast<uint32_t>(krow) * kc * 8 + r) * 2u;
@@ -740,10 +757,11 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
         t.e = e; t.m0 = mt * BM; t.n0 = nt * BN;
         t.count = group_rows(p, e);
         t.KT = group_k(p, e) / 32;
-        if constexpr (TRA) t.Abase = reinterpret_cast<const char*>(p.A) + static_cast<size_t>(e) * p.K * KCA * 16;
+        if constexpr (KG == 1) t.Abase = reinterpret_cast<const char*>(p.A);
+        else if constexpr (TRA) t.Abase = reinterpret_cast<const char*>(p.A) + static_cast<size_t>(e) * p.K * KCA * 16;
         else t.Abase = reinterpret_cast<const char*>(p.A) + (p.row_index ? 0 : static_cast<size_t>(e) * p.capacity * KCA * 16);
         if constexpr (TRB) {
-            const size_t per_group = static_cast<size_t>(splitB ? p.K / 2 : p.K) * KCB * 16;
+            const size_t per_group = KG == 2 ? 0 : static_cast<size_t>(splitB ? p.K / 2 : p.K) * KCB * 16;
             t.Bbase = reinterpret_cast<const char*>(p.B0) + e * per_group;
             t.Bbase1 = splitB ? reinterpret_cast<const char*>(p.B1) + e * per_group : t.Bbase;
         } else {
@@ -755,7 +773,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
             const int rr = (wave * NCP + i) * 16 + (lane >> 2);
             const int c = (lane & 3) ^ ((rr >> 2) & 3);
             if constexpr (TRA) {
-                t.off[i] = kmajor_off(wave * NCP + i, t.m0, p.capacity, KCA);
+                t.off[i] = kmajor_off(wave * NCP + i, t.m0, p.capacity, KCA, KG == 1);
             } else {
                 int m = t.m0 + rr;
                 m = m < t.count ? m : t.count - 1;
@@ -763,7 +781,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
                 t.off[i] = (static_cast<uint32_t>(row) * KCA + c) * 16u;
             }
             if constexpr (TRB) {
-                t.off[NCP + i] = kmajor_off(wave * NCP + i, t.n0, p.N, KCB);
+                t.off[NCP + i] = kmajor_off(wave * NCP + i, t.n0, p.N, KCB, KG == 2);
             } else {
                 int n = t.n0 + (GLU ? (rr & 127) : rr);
                 n = n < p.N ? n : p.N - 1;
@@ -779,13 +797,24 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
         return reinterpret_cast<uint64_t>(second ? b1 : b0) + kk * stepB;
     };
     // copy j (0..NCP-1: A row groups, NCP..2NCP-1: B row groups) of k-tile k of tile t into the ring slot of step g
-    auto issue_copy = [&](const Tile& t, int k, int g, int j) {
+    auto issue_copy = [&](const Tile& t, int k, int g, int j, uint32_t row_off) {
         uint4* dst = lds + (g & (NBUF - 1)) * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
-        const uint64_t b64 = j < NCP ? reinterpret_cast<uint64_t>(t.Abase) + k * stepA : b_ktile(t.Bbase, t.Bbase1, t.KT, k);
+        const bool gathered = (KG == 1 && j < NCP) || (KG == 2 && j >= NCP);
+        const uint64_t b64 = gathered ? reinterpret_cast<uint64_t>(j < NCP ? t.Abase : t.Bbase)
+                           : j < NCP ? reinterpret_cast<uint64_t>(t.Abase) + k * stepA : b_ktile(t.Bbase, t.Bbase1, t.KT, k);
         const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
         const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
         const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
-        __builtin_amdgcn_global_load_lds((global_cptr)(base + t.off[j]), (lds_ptr)dst, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_cptr)(base + t.off[j] + row_off), (lds_ptr)dst, 16, 0, 0);
+    };
+    // KG: the 32 row numbers of k-tile kl of group e go to the ring slot of global step gstep (lanes 0..31 of the
+    // calling wave); positions past the index row are clamped onto its last entry
+    auto issue_idx = [&](int e, int kl, int gstep) {
+        int pos = kl * 32 + (lane & 31);
+        pos = pos < p.k_index_stride ? pos : p.k_index_stride - 1;
+        const int32_t* src = p.k_index + static_cast<size_t>(e) * p.k_index_stride + pos;
+        int32_t* dst = idx_ring + (gstep & (IDX_SLOTS - 1)) * 32;
+        if (lane < 32) __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)dst, 4, 0, 0);
     };
 
     const int sw = (r32 >> 2) & 3;
@@ -819,6 +848,21 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
     typedef int v2i __attribute__((ext_vector_type(2)));
     typedef int v4i __attribute__((ext_vector_type(4)));
     const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)lds_raw));
+    // KG: byte offsets of the source rows of this wave's two copies (k rows lane / 4 and 16 + lane / 4) of the k-tile
+    // of global step gstep, from the index ring (its words are visible: see the kernel's header)
+    auto idx_addr = [&](int gstep) -> uint32_t {
+        return lds_base + static_cast<uint32_t>(NBUF) * STAGE * 16 + (gstep & (IDX_SLOTS - 1)) * 128 + (lane >> 2) * 4;
+    };
+    auto idx_rows = [&](int gstep, uint32_t& r0, uint32_t& r1) {
+        const uint32_t a = idx_addr(gstep);
+        int i0, i1;
+        asm volatile("ds_read_b32 %0, %2\n\t"
+                     "ds_read_b32 %1, %2 offset:64\n\t"
+                     "s_waitcnt lgkmcnt(0)"
+                     : "=&v"(i0), "=&v"(i1) : "v"(a));
+        r0 = static_cast<uint32_t>(min(max(i0, 0), p.k_rows - 1)) * kg_row_bytes;
+        r1 = static_cast<uint32_t>(min(max(i1, 0), p.k_rows - 1)) * kg_row_bytes;
+    };
     auto tr_pack = [](v2i lo, v2i hi) -> bf16x8 {          // k .. k+3 and k+4 .. k+7 of one row
         const v4i r = {lo.x, lo.y, hi.x, hi.y};
         return __builtin_bit_cast(bf16x8, r);
@@ -879,6 +923,35 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
         f[0] = tr_pack(x0, x1); f[1] = tr_pack(x2, x3); f[2] = tr_pack(x4, x5); f[3] = tr_pack(x6, x7);
         h[0] = tr_pack(x8, x9); h[1] = tr_pack(x10, x11);
     };
+    // the same with the two row numbers of a gathered operand's next copies riding on the statement's wait
+    auto tr_frags6_idx = [&](bf16x8* f, bf16x8* h, uint32_t slot, const uint32_t* off, const uint32_t* off2, uint32_t ia,
+                             int& i0, int& i1) {
+        const uint32_t a0 = lds_base + slot + off[0], a1 = lds_base + slot + off[1];
+        const uint32_t a2 = lds_base + slot + off[2], a3 = lds_base + slot + off[3];
+        const uint32_t a4 = lds_base + slot + off2[0], a5 = lds_base + slot + off2[1];
+        v2i x0, x1, x2, x3, x4, x5, x6, x7, x8, x9, x10, x11;
+        asm volatile(
+            "ds_read_b64_tr_b16 %0, %14\n\t"
+            "ds_read_b64_tr_b16 %1, %14 offset:256\n\t"
+            "ds_read_b64_tr_b16 %2, %15\n\t"
+            "ds_read_b64_tr_b16 %3, %15 offset:256\n\t"
+            "ds_read_b64_tr_b16 %4, %16\n\t"
+            "ds_read_b64_tr_b16 %5, %16 offset:256\n\t"
+            "ds_read_b64_tr_b16 %6, %17\n\t"
+            "ds_read_b64_tr_b16 %7, %17 offset:256\n\t"
+            "ds_read_b64_tr_b16 %8, %18\n\t"
+            "ds_read_b64_tr_b16 %9, %18 offset:256\n\t"
+            "ds_read_b64_tr_b16 %10, %19\n\t"
+            "ds_read_b64_tr_b16 %11, %19 offset:256\n\t"
+            "ds_read_b32 %12, %20\n\t"
+            "ds_read_b32 %13, %20 offset:64\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(x0), "=&v"(x1), "=&v"(x2), "=&v"(x3), "=&v"(x4), "=&v"(x5), "=&v"(x6), "=&v"(x7), "=&v"(x8),
+              "=&v"(x9), "=&v"(x10), "=&v"(x11), "=&v"(i0), "=&v"(i1)
+            : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "v"(a4), "v"(a5), "v"(ia));
+        f[0] = tr_pack(x0, x1); f[1] = tr_pack(x2, x3); f[2] = tr_pack(x4, x5); f[3] = tr_pack(x6, x7);
+        h[0] = tr_pack(x8, x9); h[1] = tr_pack(x10, x11);
+    };
     static_assert(TB == 2, "tr_frags2 / tr_frags6 read the two weight fragments of a wave");
 
     f32x16 acc[4][TB];
@@ -906,9 +979,21 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
     Tile cur, nxt;
     setup(q, cur);
     int g = 0;                                           // global step (ring position) of the next k-tile to multiply
-    for (int t = 0; t < AHEAD; ++t)                      // KT >= AHEAD is a launch condition
+    if constexpr (KG != 0) {                             // row numbers of k-tiles 0 .. AHEAD + 1, before anything else
+        for (int t = 0; t < AHEAD + 2; ++t) issue_idx(cur.e, t, t);
+        __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, false));
+        __builtin_amdgcn_s_barrier();
+    }
+    for (int t = 0; t < AHEAD; ++t) {                    // KT >= AHEAD is a launch condition (KG: KT >= 8)
+        uint32_t kr[NCP] = {};
+        if constexpr (KG != 0) idx_rows(t, kr[0], kr[1]);
 #pragma unroll
-        for (int j = 0; j < 2 * NCP; ++j) issue_copy(cur, t, t, j);
+        for (int j = 0; j < 2 * NCP; ++j)
+            issue_copy(cur, t, t, j, (KG == 1 && j < NCP) ? kr[j] : (KG == 2 && j >= NCP) ? kr[j - NCP] : 0u);
+        // the order of the steady state: ... tile, tile, indices, tile, indices, so that its wait counts hold from
+        // the first iteration on
+        if constexpr (KG != 0) if (t >= 1 && wave == 0) issue_idx(cur.e, t + AHEAD + 1, t + AHEAD + 1);
+    }
     __builtin_amdgcn_s_waitcnt(waitcnt_imm((AHEAD - 1) * 2 * NCP, false));
     __builtin_amdgcn_s_barrier();
     load_frags(0, 0, ck0);
@@ -939,16 +1024,28 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
             uint32_t offs[2 * NCP];
 #pragma unroll
             for (int j = 0; j < 2 * NCP; ++j) offs[j] = in_cur ? cur.off[j] : nxt.off[j];
+
             auto copy = [&](int j) {
                 uint4* dst = lds + ((g + AHEAD) & (NBUF - 1)) * STAGE + (j / NCP) * (BM * CPR) + (wave * NCP + (j % NCP)) * 64;
-                const uint64_t b64 = j < NCP ? baseA : baseB;
+                const bool gathered = (KG == 1 && j < NCP) || (KG == 2 && j >= NCP);
+                const uint64_t b64 = gathered ? reinterpret_cast<uint64_t>(j < NCP ? srcA : srcB0) : j < NCP ? baseA : baseB;
                 const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64));
                 const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(b64 >> 32));
                 const char* base = reinterpret_cast<const char*>((static_cast<uint64_t>(hi) << 32) | lo);
                 __builtin_amdgcn_global_load_lds((global_cptr)(base + offs[j]), (lds_ptr)dst, 16, 0, 0);
             };
             __builtin_amdgcn_sched_barrier(0);
-            load_frags(1, g, ck1);
+            if constexpr (KG != 0) {
+                // the fragments of the second k-substep and, on the same wait, the rows of the gathered operand for
+                // k-tile step g + AHEAD
+                int i0, i1;
+                tr_frags6_idx(fa[1], fb[1], static_cast<uint32_t>(g & (NBUF - 1)) * (STAGE * 16) + 1024, a_tr, b_tr,
+                              idx_addr(g + AHEAD), i0, i1);
+                offs[(KG - 1) * NCP] += static_cast<uint32_t>(min(max(i0, 0), p.k_rows - 1)) * kg_row_bytes;
+                offs[(KG - 1) * NCP + 1] += static_cast<uint32_t>(min(max(i1, 0), p.k_rows - 1)) * kg_row_bytes;
+            } else {
+                load_frags(1, g, ck1);
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -957,7 +1054,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
                 if (i & 1) copy(i >> 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_s_waitcnt(waitcnt_imm(3 * NCP, true));      // step g+1 is in LDS
+            // step g+1 is in LDS (KG, wave 0: two index copies lie between its tile copies and now)
+            if (KG != 0 && wave == 0) __builtin_amdgcn_s_waitcnt(waitcnt_imm(3 * NCP + 2, true));
+            else __builtin_amdgcn_s_waitcnt(waitcnt_imm(3 * NCP, true));
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             load_frags(0, g + 1, ck0);
@@ -967,6 +1066,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_persist_kernel(GemmParams p) {
                 for (int j = 0; j < TB; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][j], fa[1][i], acc[i][j], 0, 0, 0);
                 if (i & 1) copy(NCP + (i >> 1));
+                if constexpr (KG != 0) {
+                    if (i == 3 && wave == 0) {           // row numbers of the k-tile IDX_AHEAD steps on (one copy per
+                        const bool in7 = kt + IDX_AHEAD < KT;        // iteration, whether anything needs it or not)
+                        const int e7 = in7 ? cur.e : (has_next ? nxt.e : cur.e);
+                        const int k7 = in7 ? kt + IDX_AHEAD : (has_next ? kt + IDX_AHEAD - KT : 0);
+                        issue_idx(e7, k7, g + IDX_AHEAD);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -1423,11 +1530,11 @@ hipError_t launch_bf16_ring(GemmParams p, hipStream_t st) {
 
 // Persistent ring kernel: needs every group's contraction length >= 96 (three k-tiles to prefetch)
 // and the super-tile prefix to fit in LDS.
-template <bool GLU, bool DUAL = false, bool TRA = false, bool TRB = false>
+template <bool GLU, bool DUAL = false, bool TRA = false, bool TRB = false, int KG = 0>
 hipError_t launch_bf16_persist(GemmParams p, hipStream_t st, int n_cu) {
-    constexpr size_t lds = 4ull * 512 * 32 * 2;
+    constexpr size_t lds = 4ull * 512 * 32 * 2 + (KG != 0 ? 16 * 32 * 4 : 0);        // (+ the ring of row numbers)
     plan_tiles(p, 256, GLU ? 128 : 256);
-    auto kern = gemm_bf16_persist_kernel<GLU, DUAL, TRA, TRB>;
+    auto kern = gemm_bf16_persist_kernel<GLU, DUAL, TRA, TRB, KG>;
     hipError_t err = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(512), lds, st, p);
@@ -1479,6 +1586,7 @@ static bool pipelined_ok(const GemmParams& g, size_t a_rows) {
 static GemmParams params_of(const GroupedGemm& q) {
     GemmParams g{q.A, q.B0, q.B1, q.C, q.m_counts, q.G, q.M, q.N, q.K, 0, 0, 0, 0, q.row_index, q.a_rows};
     g.lda = q.lda; g.ldb = q.ldb; g.k_counts = q.k_counts; g.C2 = q.C2;
+    g.k_index = q.k_index; g.k_index_stride = q.k_index_stride; g.k_rows = q.k_rows; g.k_gather = q.k_gather;
     return g;
 }
 
@@ -1496,6 +1604,12 @@ bool grouped_gemm_transposed_ok(const GroupedGemm& q) {
     const size_t a_span = q.ta ? 32ull * lda * 2 : (q.row_index ? static_cast<size_t>(q.a_rows) : static_cast<size_t>(q.M)) * lda * 2;
     const size_t b_span = q.tb ? 32ull * ldb * 2 : static_cast<size_t>(q.N) * ldb * 2;
     if (a_span >= (1ull << 32) || b_span >= (1ull << 32)) return false;
+    if (q.k_gather) {
+        // gathered contraction rows: both operands transposed, eight k-tiles per group at least, 32-bit row offsets
+        if (!(q.ta && q.tb) || (q.k_gather != 1 && q.k_gather != 2) || !q.k_index || q.k_index_stride < 1 || q.k_rows < 1) return false;
+        if (q.K < 256 || q.B1) return false;
+        if (static_cast<size_t>(q.k_rows) * (q.k_gather == 1 ? lda : ldb) * 2 >= (1ull << 32)) return false;
+    }
     return persist_ok(params_of(q), false);
 }
 
@@ -1505,6 +1619,8 @@ hipError_t launch_grouped_gemm(const GroupedGemm& q, hipStream_t st) {
     if (q.ta || q.tb) {
         if (!grouped_gemm_transposed_ok(q)) return hipErrorInvalidValue;
         const int n_cu = cu_count();
+        if (q.k_gather == 1) return launch_bf16_persist<false, false, true, true, 1>(g, st, n_cu);
+        if (q.k_gather == 2) return launch_bf16_persist<false, false, true, true, 2>(g, st, n_cu);
         if (q.ta && q.tb) return launch_bf16_persist<false, false, true, true>(g, st, n_cu);
         if (q.tb) return launch_bf16_persist<false, false, false, true>(g, st, n_cu);
         return launch_bf16_persist<false, false, true, false>(g, st, n_cu);
