@@ -79,13 +79,18 @@ SMALL = {
     # a weight matrix run on the row-major kernel with the weight transposed once (the overloaded experts of this
     # recipe keep a few thousand rows, the others few)
     "cfg2r": lambda: I.CONFIGS["cfg2"].with_(T=12000, d=256, H=256, capacity=8192, name="cfg2-rows"),
+    # from that capacity on the weight-gradient products also fetch the rows of dOut and x through slot_token
+    # themselves; here with a capacity that is no multiple of 64 (row numbers past the end of an expert's slot list),
+    # a ragged last column tile of dW_down and experts of very different sizes
+    "cfg2q": lambda: I.CONFIGS["cfg2"].with_(T=9000, d=256, H=200, capacity=8200, name="cfg2-rows-ragged"),
 }
 
 
 @pytest.mark.parametrize("name,mode,cos", [("cfg1", TCR, FULL), ("cfg1", ECR, POOLED), ("cfg1", BIDIR, FULL),
                                            ("cfg2s", TCR, FULL), ("cfg3s", ECR, FULL), ("cfg4s", BIDIR, POOLED),
                                            ("cfg5s", BIDIR, FULL), ("cfg2w", TCR, FULL), ("cfg5w", BIDIR, POOLED),
-                                           ("cfg2r", TCR, FULL)])
+                                           ("cfg2r", TCR, FULL), ("cfg2r", BIDIR, POOLED), ("cfg2q", BIDIR, FULL),
+                                           ("cfg2q", ECR, FULL)])
 def test_backward_small_all_gradients(H, oracle, name, mode, cos):
     shape = SMALL[name]()
     _say(f"backward case {name} mode={mode} cos={cos} T={shape.T} d={shape.d} E={shape.E} C={shape.capacity} H={shape.H}")
