@@ -491,10 +491,10 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
         // the transposing one.  The copy moves E*d*H elements, the product works on every kept row, so it pays
         // from a few thousand rows per expert on (8-expert workload, 32 000 rows per expert: the input-gradient
         // product 5.1 -> 4.7 ms for 0.08 ms of copies; 16 experts with 760 rows each: 0.43 ms of copies for less
-        // than 0.1 ms).  The row count lives on the device; the capacity stands in for it.  The kernel wants whole
-        // 256-column tiles of the output, which the input gradient (d columns) has and u (H columns) may not.
+        // than 0.1 ms).  The row count lives on the device; the capacity stands in for it.  The kernel wants at least
+        // one whole 256-column tile of the output.
         const bool many_rows = C >= 8192;
-        const bool nt_dxp = many_rows && d % 256 == 0, nt_u = many_rows && H % 256 == 0;
+        const bool nt_dxp = many_rows && d >= 256 && d % 8 == 0, nt_u = many_rows && H >= 256 && H % 8 == 0;
         if (nt_u) {
             hipLaunchKernelGGL(transpose_kernel<T>, dim3(cH, cd, E), dim3(kTileThreads), 0, st, static_cast<const T*>(w_down),
                                at(L.wdT), d, H, d, 0);

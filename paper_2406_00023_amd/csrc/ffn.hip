@@ -1250,7 +1250,9 @@ __global__ __launch_bounds__(512) void gemm_bf16_persistent_kernel(GemmParams p)
         const int mg = r % MG, ng = r / MG;
         const int vm = live_row_tiles(p, e, mg, BM);
         const int mt = mg * p.SM + u % vm, nt = ng * p.SN + u / vm;
-        t.e = e; t.m0 = mt * BM; t.n0 = nt * BN;
+        // (a ragged last column tile is moved back to end on the last column: it computes some columns of its left
+        // neighbour once more and stores the same values, and no weight-row address or store needs a bound)
+        t.e = e; t.m0 = mt * BM; t.n0 = min(nt * BN, p.N - BN);
         t.count = group_rows(p, e);
         t.KT = group_k(p, e) / 64;
         t.Abase = reinterpret_cast<uint64_t>(p.A) + (gather ? 0 : static_cast<uint64_t>(e) * p.capacity * KCA * 16);
@@ -1550,8 +1552,9 @@ hipError_t launch_bf16_persistent(GemmParams p, hipStream_t st, int n_cu) {
     hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(n_cu / 8 * 8)), dim3(512), lds, st, p);
     return hipGetLastError();
 }
-// the 64-wide persistent kernel also wants whole column tiles (its weight-row addresses are not clamped)
-inline bool whole_column_tiles(const GemmParams& g, bool glu) { return g.N % (glu ? 128 : 256) == 0; }
+// the 64-wide persistent kernel bounds no weight-row address: at least one whole column tile, and 16-byte stores
+// (its ragged last tile overlaps the one before)
+inline bool whole_column_tiles(const GemmParams& g, bool glu) { return g.N >= (glu ? 128 : 256) && g.N % 8 == 0; }
 inline bool persist_ok(const GemmParams& g, bool glu, int max_super = kMaxSuper) {
     GemmParams t = g;
     plan_tiles(t, 256, glu ? 128 : 256, max_super == kMaxSuperWide);
