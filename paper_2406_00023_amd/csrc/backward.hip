@@ -482,6 +482,11 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
     // It pays where the copies are large: 8 experts x 32 000 rows, 23.0 -> 21.9 ms per call (the fetching products are
     // 3-8 % slower than the plain ones, the two copies cost 1.6 ms); 16-64 experts with 500-2000 rows each, equal or
     // 1.5 % slower.  As above, the capacity stands in for the row count.
+    // dWg and dWu share x_p: one product with the 2H rows of (da | db)^T, its output rows split between the two
+    // gradients (H = 1408: 11 whole row tiles instead of twice 5.5)
+    GroupedGemm k56 = k5;
+    k56.M = 2 * H; k56.a_rows = 2 * H; k56.C = dw_gate; k56.C2 = dw_up; k56.split_m = H;
+    const bool both_gates = H % 32 == 0 && grouped_gemm_transposed_ok(k56);
     const bool fetch_rows = C >= 8192 && direct && grouped_gemm_transposed_ok(k4) && grouped_gemm_transposed_ok(k5) &&
                             grouped_gemm_transposed_ok(k6);
     int dxp_rows = C;
@@ -531,8 +536,12 @@ hipError_t backward_impl(const etr_config& c, const void* x, const float* w_emb,
             ETR_BW(launch_grouped_gemm(t3, st));
         }
         ETR_BW(launch_grouped_gemm(fetch_rows ? k4 : t4, st));
-        ETR_BW(launch_grouped_gemm(fetch_rows ? k5 : t5, st));
-        ETR_BW(launch_grouped_gemm(fetch_rows ? k6 : t6, st));
+        if (fetch_rows && both_gates) {
+            ETR_BW(launch_grouped_gemm(k56, st));
+        } else {
+            ETR_BW(launch_grouped_gemm(fetch_rows ? k5 : t5, st));
+            ETR_BW(launch_grouped_gemm(fetch_rows ? k6 : t6, st));
+        }
         dxp_rows = Cp;
     } else {
         // Fallback (fp32, or shapes the transposing kernel does not take): every product on the "NT" kernel, with

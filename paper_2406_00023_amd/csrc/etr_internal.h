@@ -86,6 +86,9 @@ struct GroupedGemm {
     // are then rounded up to at least 256.
     const int32_t* k_index = nullptr;
     int k_index_stride = 0, k_rows = 0, k_gather = 0;
+    // With ta and the plain epilogue: output rows m < split_m go to C, the others (as rows m - split_m) to C2, both
+    // [G][split_m][N]; M = 2 split_m, split_m a multiple of 32.  (Two products that share B in one launch.)
+    int split_m = 0;
 };
 hipError_t launch_grouped_gemm(const GroupedGemm& g, hipStream_t st);
 bool grouped_gemm_transposed_ok(const GroupedGemm& g);

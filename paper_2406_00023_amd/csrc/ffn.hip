@@ -45,6 +45,9 @@ struct GemmParams {
     // into [0, k_rows).  The per-group contraction length is then at least 256.
     const int32_t* k_index = nullptr;
     int k_index_stride = 0, k_rows = 0, k_gather = 0;
+    // Plain epilogue of the transposing kernel with the output rows split between two arrays: rows below split_m go
+    // to C, the others (as rows m - split_m) to C2, both [E][split_m][N] (a multiple of 32, capacity = 2 split_m).
+    int split_m = 0;
 };
 
 // rows of group e (counts may be absent: every group has `capacity` rows) and its contraction length
@@ -111,7 +114,13 @@ __device__ __forceinline__ void store_blocks(const GemmParams& p, const f32x16 (
                         }
                     }
                 } else {
-                    *reinterpret_cast<uint2*>(Cg + o) = pack_bf16x4(g0[q * 4], g0[q * 4 + 1], g0[q * 4 + 2], g0[q * 4 + 3]);
+                    uint16_t* dst = Cg + o;
+                    if (p.split_m) {
+                        const bool second = m >= p.split_m;
+                        dst = reinterpret_cast<uint16_t*>(second ? p.C2 : p.C) +
+                              (static_cast<size_t>(e) * p.split_m + (second ? m - p.split_m : m)) * p.N + n;
+                    }
+                    *reinterpret_cast<uint2*>(dst) = pack_bf16x4(g0[q * 4], g0[q * 4 + 1], g0[q * 4 + 2], g0[q * 4 + 3]);
                 }
             }
         __builtin_amdgcn_sched_barrier(0);               // one row of blocks at a time: keeps the live set small
@@ -1590,6 +1599,7 @@ static GemmParams params_of(const GroupedGemm& q) {
     GemmParams g{q.A, q.B0, q.B1, q.C, q.m_counts, q.G, q.M, q.N, q.K, 0, 0, 0, 0, q.row_index, q.a_rows};
     g.lda = q.lda; g.ldb = q.ldb; g.k_counts = q.k_counts; g.C2 = q.C2;
     g.k_index = q.k_index; g.k_index_stride = q.k_index_stride; g.k_rows = q.k_rows; g.k_gather = q.k_gather;
+    g.split_m = q.split_m;
     return g;
 }
 
@@ -1607,6 +1617,7 @@ bool grouped_gemm_transposed_ok(const GroupedGemm& q) {
     const size_t a_span = q.ta ? 32ull * lda * 2 : (q.row_index ? static_cast<size_t>(q.a_rows) : static_cast<size_t>(q.M)) * lda * 2;
     const size_t b_span = q.tb ? 32ull * ldb * 2 : static_cast<size_t>(q.N) * ldb * 2;
     if (a_span >= (1ull << 32) || b_span >= (1ull << 32)) return false;
+    if (q.split_m && (!q.ta || q.split_m % 32 != 0 || q.M != 2 * q.split_m || !q.C2 || q.m_counts)) return false;
     if (q.k_gather) {
         // gathered contraction rows: both operands transposed, eight k-tiles per group at least, 32-bit row offsets
         if (!(q.ta && q.tb) || (q.k_gather != 1 && q.k_gather != 2) || !q.k_index || q.k_index_stride < 1 || q.k_rows < 1) return false;
