@@ -25,6 +25,8 @@ HIPCC_FLAGS = [
 _SHIFT64 = re.compile(r"^\s*(v_lshlrev_b64|v_lshrrev_b64|v_ashrrev_i64)\s+v\[\d+:\d+\],\s*v(\d+),")
 _KERNEL = re.compile(r"^(_Z\S+):")
 _NEXT_FREE = re.compile(r"^\s*\.amdhsa_next_free_vgpr\s+(\d+)")
+_ACCUM = re.compile(r"^\s*\.amdhsa_accum_offset\s+(\d+)")
+_END = re.compile(r"^\s*\.end_amdhsa_kernel")
 
 
 def shift64_last_vgpr_hits(asm: str) -> list:
@@ -34,13 +36,14 @@ def shift64_last_vgpr_hits(asm: str) -> list:
     Measured on MI355X: such a shift takes a wrong amount whenever a wave of another workgroup shares the SIMD (the
     register after the last one of the allocation block belongs to that wave); the same instructions with a larger
     register allocation are correct.  The compiler guards this for gfx90a only, so the build checks its output.
+    The last ordinary register below a block of accumulation registers is flagged as well (not measured: on the safe side).
     Returns (kernel, line number, instruction) triples.
     """
-    hits, kernel, shifts = [], None, []
+    hits, kernel, shifts, ends = [], None, [], set()
     for ln, line in enumerate(asm.split("\n"), 1):
         m = _KERNEL.match(line)
         if m:
-            kernel, shifts = m.group(1), []
+            kernel, shifts, ends = m.group(1), [], set()
             continue
         if kernel is None:
             continue
@@ -48,10 +51,12 @@ def shift64_last_vgpr_hits(asm: str) -> list:
         if m:
             shifts.append((ln, int(m.group(2)), line.strip()))
             continue
-        m = _NEXT_FREE.match(line)
+        m = _NEXT_FREE.match(line) or _ACCUM.match(line)
         if m:
-            last = int(m.group(1)) - 1
-            hits += [(kernel, l, text) for (l, reg, text) in shifts if reg % 8 == 7 and reg == last]
+            ends.add(int(m.group(1)) - 1)
+            continue
+        if _END.match(line):
+            hits += [(kernel, l, text) for (l, reg, text) in shifts if reg % 8 == 7 and reg in ends]
             kernel = None
     return hits
 

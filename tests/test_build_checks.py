@@ -16,12 +16,13 @@ _Z6kernelPm:                            ; @_Z6kernelPm
 \ts_endpgm
 \t.amdhsa_kernel _Z6kernelPm
 \t\t.amdhsa_next_free_vgpr {nfv}
+\t\t.amdhsa_accum_offset {acc}
 \t.end_amdhsa_kernel
 """
 
 
 def test_scanner_flags_the_amount_in_the_last_register():
-    hits = build.shift64_last_vgpr_hits(SNIPPET.format(amount="v15", nfv=16))
+    hits = build.shift64_last_vgpr_hits(SNIPPET.format(amount="v15", nfv=16, acc=16))
     assert len(hits) == 1 and hits[0][0] == "_Z6kernelPm" and "v_lshlrev_b64" in hits[0][2]
 
 
@@ -30,11 +31,16 @@ def test_scanner_flags_the_amount_in_the_last_register():
                                         ("v7", 16),      # end of a block, but not the last register
                                         ("s4", 16), ("3", 16)])
 def test_scanner_passes_everything_else(amount, nfv):
-    assert build.shift64_last_vgpr_hits(SNIPPET.format(amount=amount, nfv=nfv)) == []
+    assert build.shift64_last_vgpr_hits(SNIPPET.format(amount=amount, nfv=nfv, acc=(nfv + 3) // 4 * 4)) == []
+
+
+def test_scanner_flags_the_last_ordinary_register_below_accumulation_registers():
+    assert len(build.shift64_last_vgpr_hits(SNIPPET.format(amount="v15", nfv=48, acc=16))) == 1
 
 
 def test_scanner_keeps_kernels_apart():
-    two = SNIPPET.format(amount="v15", nfv=24) + SNIPPET.format(amount="v23", nfv=24).replace("kernelPm", "otherPm")
+    two = (SNIPPET.format(amount="v15", nfv=24, acc=24) +
+           SNIPPET.format(amount="v23", nfv=24, acc=24).replace("kernelPm", "otherPm"))
     hits = build.shift64_last_vgpr_hits(two)
     assert [h[0] for h in hits] == ["_Z6otherPm"]
 
