@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
     float* w = sm;                       // [E][P]
     float* wn = w + E * P;               // [E] 1 / |w_e| (0 for a zero embedding)
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    float* g = wn + E + wave * (2 * P + 2 * E);   // per wave: g[P], v[P], ds[E], slot (as int)[E]
+    float* g = wn + E + wave * (2 * P + 2 * E);   // per wave: g[P], v[P], ds[E], rows of the kept pairs (as int)[E]
     float* v = g + P;
     float* ds = v + P;
     int* sl = reinterpret_cast<int*>(ds + E);
@@ -302,9 +302,39 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
     const int t = blockIdx.x * 4 + wave;
     if (t >= T_) return;                 // no block-wide barrier below
     const T* xr = x + static_cast<size_t>(t) * d;
+    // softmax backward (E <= 64: lane e); its scattered reads are requested first and land while the row is walked
+    float dg = 0.f, gt = 0.f, sc = 0.f;
+    int slot = -1;
+    if (lane < E) {
+        slot = slot_of[static_cast<size_t>(t) * E + lane];
+        gt = gate[static_cast<size_t>(t) * E + lane];
+        sc = score[static_cast<size_t>(t) * E + lane];
+        if (slot >= 0 && slot < C) {
+            for (int i = 0; i < n_part; ++i) dg += dgate_part[(static_cast<size_t>(i) * E + lane) * C + slot];
+        } else {
+            slot = -1;
+        }
+    }
     // pooled features and norms
     float xx = 0.f, gg = 0.f;
-    for (int p = lane; p < P; p += 64) {
+    constexpr int VX = Elt<T>::kVec;
+    const int LPG = D / VX;                                  // lanes that share a pooled group in the coalesced walk
+    const bool row_walk = D % VX == 0 && LPG <= 64 && (LPG & (LPG - 1)) == 0 && d % (64 * VX) == 0;
+    if (row_walk) {
+        // the row in whole 16-byte pieces, lane after lane; the LPG neighbouring lanes of a group add up by swaps
+        for (int c = lane; c < d / VX; c += 64) {
+            float f[VX], s = 0.f;
+            Elt<T>::load_vec(xr + static_cast<size_t>(c) * VX, f);
+#pragma unroll
+            for (int i = 0; i < VX; ++i) { s += f[i]; xx += f[i] * f[i]; }
+            for (int o = 1; o < LPG; o <<= 1) s += __shfl_xor(s, o, 64);
+            if ((lane & (LPG - 1)) == 0) {
+                s /= D;
+                g[c / LPG] = s; gg += s * s;
+            }
+        }
+    }
+    for (int p = lane; p < P && !row_walk; p += 64) {
         float s = 0.f;
         if (D % Elt<T>::kVec == 0) {
             for (int j = 0; j < D; j += Elt<T>::kVec) {
@@ -324,19 +354,6 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) { xx += __shfl_xor(xx, o, 64); gg += __shfl_xor(gg, o, 64); }
-    // softmax backward (E <= 64: lane e)
-    float dg = 0.f, gt = 0.f, sc = 0.f;
-    int slot = -1;
-    if (lane < E) {
-        slot = slot_of[static_cast<size_t>(t) * E + lane];
-        gt = gate[static_cast<size_t>(t) * E + lane];
-        sc = score[static_cast<size_t>(t) * E + lane];
-        if (slot >= 0 && slot < C) {
-            for (int i = 0; i < n_part; ++i) dg += dgate_part[(static_cast<size_t>(i) * E + lane) * C + slot];
-        } else {
-            slot = -1;
-        }
-    }
     if (gate_norm) {
         // dg is the gradient of the renormalised weight g' = g / S (S = sum of g over the kept experts);
         // d / d g_e = (dg'_e - sum_kept dg'_i g'_i) / S for kept e, 0 otherwise
@@ -356,8 +373,12 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
     float beta = dsv * sc;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) beta += __shfl_xor(beta, o, 64);
+    // the token's kept pairs in ascending expert order, as rows of dxp (sl[i], i < n_kept)
+    const uint64_t kept_mask = __ballot(slot >= 0);
+    const int n_kept = __popcll(kept_mask);
     if (lane < E) {
-        ds[lane] = dsv; sl[lane] = slot;
+        ds[lane] = dsv;
+        if (slot >= 0) sl[__popcll(kept_mask & ((1ull << lane) - 1ull))] = lane * Cx + slot;
         if (dgate_out) dgate_out[static_cast<size_t>(t) * E + lane] = dg;
         if (dscore_out) dscore_out[static_cast<size_t>(t) * E + lane] = dsv;
     }
@@ -387,12 +408,21 @@ __global__ __launch_bounds__(256) void dx_kernel(const T* __restrict__ x, const 
             const int p = (j + i) / D;
             acc[i] = v[p] - cb * (full ? f[i] : g[p]);
         }
-        for (int e = 0; e < E; ++e) {              // ascending expert order, as in the forward sum
-            const int s = sl[e];
-            if (s >= 0) {
-                Elt<T>::load_vec(dxp + (static_cast<size_t>(e) * Cx + s) * d + j, f);
+        // ascending expert order, as in the forward sum; four rows requested at a time (past the last kept pair the
+        // last one is requested again and not added)
+        for (int i0 = 0; i0 < n_kept; i0 += 4) {
+            float r[4][V];
 #pragma unroll
-                for (int i = 0; i < V; ++i) acc[i] += f[i];
+            for (int q = 0; q < 4; ++q) {
+                const int row = sl[min(i0 + q, n_kept - 1)];
+                Elt<T>::load_vec(dxp + static_cast<size_t>(row) * d + j, r[q]);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (i0 + q < n_kept) {
+#pragma unroll
+                    for (int i = 0; i < V; ++i) acc[i] += r[q][i];
+                }
             }
         }
         Elt<T>::store_vec(out + j, acc);
